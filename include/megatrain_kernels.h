@@ -1,0 +1,107 @@
+/*
+ * megatrain_kernels.h - C ABI of the individual gfx950 kernels behind the training step.
+ *
+ * These are the operations that make up f_i, the loss and LocalBackward of Algorithm 1
+ * (MegaTrain, Sections 3.1 and 3.4: "stateless templates" that take the streamed weight
+ * buffer as plain pointers at launch).  They are exported so that each kernel can be checked
+ * against the CPU oracle and timed on its own.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer unless its name starts with "host_".
+ *   - bf16 tensors are raw uint16_t bit patterns; "ld*" are leading dimensions in ELEMENTS.
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work; the caller synchronises.
+ *   - bf16 pointers must be 16-byte aligned and leading dimensions multiples of 8 unless
+ *     stated otherwise; violations return MT_ERR_INVALID_ARG before anything is launched.
+ *   - Return value: mt_status as in megatrain.h.
+ */
+#ifndef MEGATRAIN_KERNELS_H_
+#define MEGATRAIN_KERNELS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[M,N] = A[M,K] . B[N,K]^T with fp32 accumulation on the matrix cores.
+ * A [M,K] bf16 (lda), B [N,K] bf16 (ldb), K % 8 == 0.
+ * out_fp32 == 0: C bf16 [M,N] (ldc); if R != NULL, R bf16 [M,N] (ldr) is added before rounding
+ *                (the residual connection of the block).
+ * out_fp32 == 1: C fp32 [M,N] (ldc); accumulate != 0 adds to the existing C (weight gradients
+ *                of the LM head summed over token chunks).  R must be NULL. */
+int32_t mt_k_gemm_nt(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, void *C, int64_t ldc,
+                     const uint16_t *R, int64_t ldr, int32_t M, int32_t N, int32_t K, int32_t out_fp32,
+                     int32_t accumulate, void *stream);
+
+/* out[b0][b1][c][r] = in[b0][b1][r][c], bf16; rows, cols multiples of 8; batch strides in elements. */
+int32_t mt_k_transpose(const uint16_t *in, uint16_t *out, int32_t rows, int32_t cols, int64_t ld_in, int64_t ld_out,
+                       int32_t nb0, int32_t nb1, int64_t in_s0, int64_t in_s1, int64_t out_s0, int64_t out_s1,
+                       void *stream);
+
+/* y = x / sqrt(mean(x^2) + eps) * gain, rows of length d (d % 8 == 0, d <= 8192), contiguous. */
+int32_t mt_k_rmsnorm_fwd(uint16_t *y, const uint16_t *x, const uint16_t *gain, int64_t n, int32_t d, float eps,
+                         void *stream);
+
+/* dx = dres + dRMSNorm(dy; x, gain) (dres may be NULL), dgain[d] fp32 = sum over rows (written).
+ * ws: device scratch of at least mt_k_rmsnorm_bwd_ws_bytes(d) bytes. */
+size_t mt_k_rmsnorm_bwd_ws_bytes(int32_t d);
+int32_t mt_k_rmsnorm_bwd(uint16_t *dx, float *dgain, const uint16_t *dy, const uint16_t *x, const uint16_t *gain,
+                         const uint16_t *dres, void *ws, int64_t n, int32_t d, float eps, void *stream);
+
+/* Fill cos/sin tables [T, hd/2] fp32 on the HOST: angle = t * base^(-2j/hd), computed in double. */
+int32_t mt_k_rope_table(float *host_cos, float *host_sin, int32_t T, int32_t hd, double base);
+/* Rotate in place the first n_heads heads (hd wide, hd % 16 == 0) of every row of x [n, ld];
+ * the position of row r is r % T; sign = +1 forward, -1 inverse (the backward map). */
+int32_t mt_k_rope(uint16_t *x, int64_t ld, int64_t n, int32_t T, int32_t n_heads, int32_t hd, const float *cos_tab,
+                  const float *sin_tab, int32_t sign, void *stream);
+
+/* gu [n, 2F] holds gate in columns [0,F) and up in [F,2F).  s = silu(gate) * up, [n,F]. */
+int32_t mt_k_swiglu_fwd(uint16_t *s, const uint16_t *gu, int64_t n, int32_t F, void *stream);
+/* dgu [n,2F] = (dgate | dup) from ds [n,F] and gu. */
+int32_t mt_k_swiglu_bwd(uint16_t *dgu, const uint16_t *ds, const uint16_t *gu, int64_t n, int32_t F, void *stream);
+
+/* h[r,:] = table[tokens[r],:] */
+int32_t mt_k_embed_gather(uint16_t *h, const uint16_t *table, const int32_t *tokens, int64_t n, int32_t d,
+                          void *stream);
+/* dtable [V,d] fp32, every row written: row v = sum of dh[order[i],:] for i in [row_start[v], row_start[v+1]),
+ * added in that order (deterministic).  row_start has V+1 entries. */
+int32_t mt_k_embed_scatter(float *dtable, const uint16_t *dh, const int32_t *row_start, const int32_t *order,
+                           int32_t V, int32_t d, void *stream);
+
+/* Per row r of logits fp32 [n,V] (V % 4 == 0): loss_rows[r] = logsumexp(z_r) - z_r[label_r];
+ * dlogits bf16 [n,V] = (softmax(z_r) - onehot(label_r)) * inv_n.  A negative label gives a zero
+ * loss and a zero gradient row. */
+int32_t mt_k_cross_entropy(float *loss_rows, uint16_t *dlogits, const float *logits, const int32_t *labels, int64_t n,
+                           int32_t V, float inv_n, void *stream);
+/* out[0] = (accumulate ? out[0] : 0) + scale * sum(in[0..n)), fixed summation order. */
+int32_t mt_k_reduce_sum(float *out, const float *in, int64_t n, float scale, int32_t accumulate, void *stream);
+
+/* Causal attention forward.  Rows of q/k/v/o are tokens (b*T + t); head h occupies columns
+ * [h*hd, (h+1)*hd) after the given pointer.  hd in {64, 128}, T % 8 == 0, Hq % Hkv == 0.
+ * vT: per-head transposed values [B, Hkv, hd, T] (made with mt_k_transpose).
+ * o bf16, lse fp32 [B, Hq, T] = log sum_u exp(q_t.k_u * scale). */
+int32_t mt_k_flash_fwd(uint16_t *o, int64_t ldo, float *lse, const uint16_t *q, int64_t ldq, const uint16_t *k,
+                       int64_t ldk, const uint16_t *vT, int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t hd,
+                       float scale, void *stream);
+/* Causal attention backward: dq, dk, dv from dout, the forward's inputs, o and lse.
+ * qT, kT [B,H,hd,T] are transposed copies of q, k; doT [B,Hq,hd,T] and delta [B,Hq,T] fp32 are
+ * scratch written by this call (sizes B*Hq*hd*T bf16 and B*Hq*T fp32). */
+int32_t mt_k_flash_bwd(uint16_t *dq, int64_t lddq, uint16_t *dk, int64_t lddk, uint16_t *dv, int64_t lddv,
+                       const uint16_t *dout, int64_t lddo, const uint16_t *q, int64_t ldq, const uint16_t *k,
+                       int64_t ldk, const uint16_t *v, int64_t ldv, const uint16_t *o, int64_t ldo, const float *lse,
+                       const uint16_t *qT, const uint16_t *kT, uint16_t *doT, float *delta, int32_t B, int32_t T,
+                       int32_t Hq, int32_t Hkv, int32_t hd, float scale, void *stream);
+
+/* Host Adam on one array (the arithmetic of mt_adam_step; all HOST pointers).  shadow may be
+ * NULL, otherwise it receives the updated parameters rounded to bf16 (nearest even). */
+int32_t mt_k_host_adam(float *host_p, const float *host_g, float *host_m, float *host_v, uint16_t *host_shadow,
+                       size_t n, float lr, float beta1, float beta2, float eps, float wd, int64_t step);
+/* fp32 -> bf16 round-to-nearest-even on the host (the conversion applied to streamed weights). */
+int32_t mt_k_host_f32_to_bf16(uint16_t *host_out, const float *host_in, size_t n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MEGATRAIN_KERNELS_H_ */

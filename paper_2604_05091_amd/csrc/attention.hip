@@ -1,0 +1,455 @@
+// Causal flash attention for gfx950, forward and backward, grouped KV heads.
+//
+// The attention inside f_i and LocalBackward (Algorithm 1) never materialises the
+// T x T score matrix: scores are produced tile by tile on the matrix cores, the
+// softmax is carried online (running maximum and sum per query), and the backward
+// recomputes the probabilities from the saved log-sum-exp.
+//
+// Register layout.  v_mfma_f32_32x32x16_bf16 leaves, in lane l, the column l%32 of
+// the 32x32 result with rows 8(r/4) + 4(l/32) + r%4 for r = 0..15.  The kernels are
+// arranged so that the "column" is always the index a wave owns:
+//
+//   forward, dQ kernel:  S^T = K Q^T, so a lane owns one query.  Row statistics
+//       (max, sum, lse, delta) are per-lane scalars; the only cross-lane step is one
+//       exchange with lane l^32.  P^T in registers is already a valid B operand for
+//       O^T = V^T P^T and dQ^T = K^T dS^T (the reduction index of an MFMA may be
+//       permuted freely as long as both operands use the same permutation; the A
+//       operand is read from a transposed tile with that permutation).
+//   dK/dV kernel:        S = Q K^T, so a lane owns one key; dV^T = dO^T P and
+//       dK^T = Q^T dS take P and dS from registers in the same way.
+//
+// Transposed operands (V^T, K^T, Q^T, dO^T, each [B,H,hd,T]) are produced beforehand
+// by the transpose kernel, so every tile load here is a plain 16-byte row copy.
+// dQ and dK/dV are separate kernels: no atomics, results are bit-reproducible.
+#include "common.h"
+
+namespace mt {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// cooperative copy of a [ROWS x COLS] bf16 tile (row-major source with leading dimension ld, valid rows
+// < rows_valid, valid columns < cols_valid, both multiples of 8 for columns) into LDS with pitch LDP.
+template <int ROWS, int COLS, int LDP>
+__device__ __forceinline__ void load_tile(bf16_t *dst, const bf16_t *src, int64_t ld, int rows_valid, int cols_valid) {
+    constexpr int CPR = COLS / 8, CHUNKS = ROWS * CPR;
+    static_assert(CHUNKS % 256 == 0, "tile must split evenly over 256 threads");
+#pragma unroll
+    for (int j = 0; j < CHUNKS / 256; ++j) {
+        const int chunk = threadIdx.x + 256 * j, r = chunk / CPR, c = (chunk % CPR) * 8;
+        uint4 v = {0u, 0u, 0u, 0u};
+        if (r < rows_valid && c < cols_valid) v = *reinterpret_cast<const uint4 *>(src + (int64_t)r * ld + c);
+        *reinterpret_cast<uint4 *>(dst + r * LDP + c) = v;
+    }
+}
+
+// A operand whose reduction index follows the accumulator-register permutation: for chunk cch of row block
+// rb the lane reads columns rb*32 + cch*16 + 4 hl + {0..3} and + 8 + {0..3} of its row.
+__device__ __forceinline__ bf16x8 read_perm_frag(const bf16_t *row_ptr, int rb, int cch, int hl) {
+    const bf16_t *p = row_ptr + rb * 32 + cch * 16 + hl * 4;
+    const uint2 lo = *reinterpret_cast<const uint2 *>(p);
+    const uint2 hi = *reinterpret_cast<const uint2 *>(p + 8);
+    const uint4 u = {lo.x, lo.y, hi.x, hi.y};
+    return __builtin_bit_cast(bf16x8, u);
+}
+
+__device__ __forceinline__ bf16x8 pack_frag(const f32x16 &v, int cch) {
+    const int o = cch * 8;
+    const uint4 u = {pack2bf(v[o + 0], v[o + 1]), pack2bf(v[o + 2], v[o + 3]), pack2bf(v[o + 4], v[o + 5]),
+                     pack2bf(v[o + 6], v[o + 7])};
+    return __builtin_bit_cast(bf16x8, u);
+}
+
+__device__ __forceinline__ bf16x8 load_frag_global(const bf16_t *p, bool ok) {
+    uint4 u = {0u, 0u, 0u, 0u};
+    if (ok) u = *reinterpret_cast<const uint4 *>(p);
+    return __builtin_bit_cast(bf16x8, u);
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+    return z;
+}
+
+// lane-owned O^T / dQ^T style accumulator [HD rows][32 owned columns] -> out[owned][HD], scaled
+template <int HD>
+__device__ __forceinline__ void store_owned_rows(bf16_t *out_row, const f32x16 *acc, float mul, int hl) {
+#pragma unroll
+    for (int hb = 0; hb < HD / 32; ++hb)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int j = hb * 32 + r4 * 8 + hl * 4;
+            const uint2 u = {pack2bf(acc[hb][r4 * 4 + 0] * mul, acc[hb][r4 * 4 + 1] * mul),
+                             pack2bf(acc[hb][r4 * 4 + 2] * mul, acc[hb][r4 * 4 + 3] * mul)};
+            *reinterpret_cast<uint2 *>(out_row + j) = u;
+        }
+}
+
+// ------------------------------------------------------------------ forward
+// grid (q blocks of 128 rows, heaviest first; Hq; B); wave w owns 32 queries.
+template <int HD>
+__global__ __launch_bounds__(256) void flash_fwd_kernel(AttnArgs a) {
+    constexpr int LDK = HD + 8, LDV = 64 + 8;
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    bf16_t *Ks = smem;              // [64][LDK]   keys of the tile
+    bf16_t *VTs = smem + 64 * LDK;  // [HD][LDV]   values of the tile, transposed
+
+    const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int hk = h / (a.Hq / a.Hkv);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int T = a.T;
+    const int q0 = qb * 128 + wave * 32, q = q0 + l32;
+    const bool qok = q < T;
+    const int qm = qok ? q : T - 1;  // padded queries behave like the last row; never stored
+
+    bf16x8 qf[HD / 16];
+    {
+        const bf16_t *qp = a.q + ((int64_t)b * T + q) * a.ldq + (int64_t)h * HD + hl * 8;
+#pragma unroll
+        for (int ks = 0; ks < HD / 16; ++ks) qf[ks] = load_frag_global(qp + ks * 16, qok);
+    }
+    f32x16 oacc[HD / 32];
+#pragma unroll
+    for (int hb = 0; hb < HD / 32; ++hb) oacc[hb] = zero16();
+    float m = -INFINITY, lsum = 0.f;
+    const float c = a.scale * kLog2e;
+
+    const bf16_t *kbase = a.k + (int64_t)b * T * a.ldk + (int64_t)hk * HD;
+    const bf16_t *vtbase = a.vT + ((int64_t)b * a.Hkv + hk) * HD * (int64_t)T;
+    const int kv_end = min(T, qb * 128 + 128);
+    const int ntiles = (kv_end + 63) / 64;
+
+    for (int kt = 0; kt < ntiles; ++kt) {
+        const int kv0 = kt * 64;
+        __syncthreads();
+        load_tile<64, HD, LDK>(Ks, kbase + (int64_t)kv0 * a.ldk, a.ldk, T - kv0, HD);
+        load_tile<HD, 64, LDV>(VTs, vtbase + kv0, T, HD, T - kv0);
+        __syncthreads();
+        if (kv0 > q0 + 31) continue;  // the whole tile lies after every query of this wave
+
+        f32x16 sacc[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            sacc[rb] = zero16();
+            const bf16_t *kr = Ks + (rb * 32 + l32) * LDK + hl * 8;
+#pragma unroll
+            for (int ks = 0; ks < HD / 16; ++ks)
+                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(kr + ks * 16),
+                                                                   qf[ks], sacc[rb], 0, 0, 0);
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kv = kv0 + rb * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
+                const float s = kv > qm ? -INFINITY : sacc[rb][r] * c;
+                sacc[rb][r] = s;
+                mx = fmaxf(mx, s);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m, mx);  // finite: kv0 <= q0 <= qm, so key kv0 is visible to every query
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        float ps = 0.f;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(sacc[rb][r] - m_new);
+                sacc[rb][r] = p;
+                ps += p;
+            }
+        lsum = lsum * alpha + ps;
+        m = m_new;
+#pragma unroll
+        for (int hb = 0; hb < HD / 32; ++hb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[hb][r] *= alpha;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int cch = 0; cch < 2; ++cch) {
+                const bf16x8 pf = pack_frag(sacc[rb], cch);
+#pragma unroll
+                for (int hb = 0; hb < HD / 32; ++hb)
+                    oacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        read_perm_frag(VTs + (hb * 32 + l32) * LDV, rb, cch, hl), pf, oacc[hb], 0, 0, 0);
+            }
+    }
+    lsum += __shfl_xor(lsum, 32, 64);
+    if (qok) {
+        store_owned_rows<HD>(a.o + ((int64_t)b * T + q) * a.ldo + (int64_t)h * HD, oacc, 1.0f / lsum, hl);
+        if (hl == 0) a.lse[((int64_t)b * a.Hq + h) * T + q] = (m + __builtin_amdgcn_logf(lsum)) * kLn2;
+    }
+}
+
+// ------------------------------------------------------------------ backward: dQ
+// Same ownership as the forward: a lane owns one query, loops over key tiles <= q.
+template <int HD>
+__global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
+    constexpr int LDK = HD + 8, LDV = 64 + 8;
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    bf16_t *Ks = smem;               // [64][LDK]
+    bf16_t *Vs = Ks + 64 * LDK;      // [64][LDK]
+    bf16_t *KTs = Vs + 64 * LDK;     // [HD][LDV]
+
+    const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int hk = h / (a.Hq / a.Hkv);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int T = a.T;
+    const int q0 = qb * 128 + wave * 32, q = q0 + l32;
+    const bool qok = q < T;
+    const int qm = qok ? q : T - 1;
+
+    bf16x8 qf[HD / 16], dof[HD / 16];
+    {
+        const bf16_t *qp = a.q + ((int64_t)b * T + q) * a.ldq + (int64_t)h * HD + hl * 8;
+        const bf16_t *dp = a.dout + ((int64_t)b * T + q) * a.lddo + (int64_t)h * HD + hl * 8;
+#pragma unroll
+        for (int ks = 0; ks < HD / 16; ++ks) {
+            qf[ks] = load_frag_global(qp + ks * 16, qok);
+            dof[ks] = load_frag_global(dp + ks * 16, qok);
+        }
+    }
+    const int64_t stat = ((int64_t)b * a.Hq + h) * T + qm;
+    const float lse2 = a.lse[stat] * kLog2e, dlt = a.delta[stat];
+    const float c = a.scale * kLog2e;
+    f32x16 dqacc[HD / 32];
+#pragma unroll
+    for (int hb = 0; hb < HD / 32; ++hb) dqacc[hb] = zero16();
+
+    const bf16_t *kbase = a.k + (int64_t)b * T * a.ldk + (int64_t)hk * HD;
+    const bf16_t *vbase = a.v + (int64_t)b * T * a.ldv + (int64_t)hk * HD;
+    const bf16_t *ktbase = a.kT + ((int64_t)b * a.Hkv + hk) * HD * (int64_t)T;
+    const int kv_end = min(T, qb * 128 + 128);
+    const int ntiles = (kv_end + 63) / 64;
+
+    for (int kt = 0; kt < ntiles; ++kt) {
+        const int kv0 = kt * 64;
+        __syncthreads();
+        load_tile<64, HD, LDK>(Ks, kbase + (int64_t)kv0 * a.ldk, a.ldk, T - kv0, HD);
+        load_tile<64, HD, LDK>(Vs, vbase + (int64_t)kv0 * a.ldv, a.ldv, T - kv0, HD);
+        load_tile<HD, 64, LDV>(KTs, ktbase + kv0, T, HD, T - kv0);
+        __syncthreads();
+        if (kv0 > q0 + 31) continue;
+
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            f32x16 sacc = zero16(), dpacc = zero16();
+            const bf16_t *kr = Ks + (rb * 32 + l32) * LDK + hl * 8;
+            const bf16_t *vr = Vs + (rb * 32 + l32) * LDK + hl * 8;
+#pragma unroll
+            for (int ks = 0; ks < HD / 16; ++ks) {
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(kr + ks * 16), qf[ks],
+                                                               sacc, 0, 0, 0);
+                dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(vr + ks * 16),
+                                                                dof[ks], dpacc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kv = kv0 + rb * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
+                const float p = kv > qm ? 0.f : __builtin_amdgcn_exp2f(sacc[r] * c - lse2);
+                sacc[r] = p * (dpacc[r] - dlt);  // dS^T
+            }
+#pragma unroll
+            for (int cch = 0; cch < 2; ++cch) {
+                const bf16x8 dsf = pack_frag(sacc, cch);
+#pragma unroll
+                for (int hb = 0; hb < HD / 32; ++hb)
+                    dqacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        read_perm_frag(KTs + (hb * 32 + l32) * LDV, rb, cch, hl), dsf, dqacc[hb], 0, 0, 0);
+            }
+        }
+    }
+    if (qok) store_owned_rows<HD>(a.dq + ((int64_t)b * T + q) * a.lddq + (int64_t)h * HD, dqacc, a.scale, hl);
+}
+
+// ------------------------------------------------------------------ backward: dK, dV
+// grid (key blocks of 128, heaviest first = block 0; Hkv; B); a lane owns one key and keeps
+// its K and V fragments in registers; loops over the query heads of the group and the query
+// tiles >= the key block.
+template <int HD>
+__global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
+    constexpr int LDK = HD + 8, LDV = 64 + 8;
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    bf16_t *Qs = smem;                 // [64][LDK]
+    bf16_t *dOs = Qs + 64 * LDK;       // [64][LDK]
+    bf16_t *QTs = dOs + 64 * LDK;      // [HD][LDV]
+    bf16_t *dOTs = QTs + HD * LDV;     // [HD][LDV]
+    float *lses = reinterpret_cast<float *>(dOTs + HD * LDV);  // [64] lse * log2e
+    float *dlts = lses + 64;                                    // [64]
+
+    const int kvb = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    const int G = a.Hq / a.Hkv;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int T = a.T;
+    const int kv0w = kvb * 128 + wave * 32, kv = kv0w + l32;
+    const bool kvok = kv < T;
+
+    bf16x8 kf[HD / 16], vf[HD / 16];
+    {
+        const bf16_t *kp = a.k + ((int64_t)b * T + kv) * a.ldk + (int64_t)hk * HD + hl * 8;
+        const bf16_t *vp = a.v + ((int64_t)b * T + kv) * a.ldv + (int64_t)hk * HD + hl * 8;
+#pragma unroll
+        for (int ks = 0; ks < HD / 16; ++ks) {
+            kf[ks] = load_frag_global(kp + ks * 16, kvok);
+            vf[ks] = load_frag_global(vp + ks * 16, kvok);
+        }
+    }
+    f32x16 dvacc[HD / 32], dkacc[HD / 32];
+#pragma unroll
+    for (int hb = 0; hb < HD / 32; ++hb) {
+        dvacc[hb] = zero16();
+        dkacc[hb] = zero16();
+    }
+    const float c = a.scale * kLog2e;
+    const int qt_first = (kvb * 128) / 64, qt_end = (T + 63) / 64;
+
+    for (int g = 0; g < G; ++g) {
+        const int h = hk * G + g;
+        const bf16_t *qbase = a.q + (int64_t)b * T * a.ldq + (int64_t)h * HD;
+        const bf16_t *dobase = a.dout + (int64_t)b * T * a.lddo + (int64_t)h * HD;
+        const bf16_t *qtbase = a.qT + ((int64_t)b * a.Hq + h) * HD * (int64_t)T;
+        const bf16_t *dotbase = a.doT + ((int64_t)b * a.Hq + h) * HD * (int64_t)T;
+        const float *lsebase = a.lse + ((int64_t)b * a.Hq + h) * T;
+        const float *dltbase = a.delta + ((int64_t)b * a.Hq + h) * T;
+
+        for (int qt = qt_first; qt < qt_end; ++qt) {
+            const int q0t = qt * 64;
+            __syncthreads();
+            load_tile<64, HD, LDK>(Qs, qbase + (int64_t)q0t * a.ldq, a.ldq, T - q0t, HD);
+            load_tile<64, HD, LDK>(dOs, dobase + (int64_t)q0t * a.lddo, a.lddo, T - q0t, HD);
+            load_tile<HD, 64, LDV>(QTs, qtbase + q0t, T, HD, T - q0t);
+            load_tile<HD, 64, LDV>(dOTs, dotbase + q0t, T, HD, T - q0t);
+            if (threadIdx.x < 64) {
+                const int qq = q0t + threadIdx.x;
+                lses[threadIdx.x] = qq < T ? lsebase[qq] * kLog2e : 0.f;
+                dlts[threadIdx.x] = qq < T ? dltbase[qq] : 0.f;
+            }
+            __syncthreads();
+            if (q0t + 63 < kv0w) continue;  // every query of the tile precedes every key of this wave
+
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                f32x16 sacc = zero16(), dpacc = zero16();
+                const bf16_t *qr = Qs + (rb * 32 + l32) * LDK + hl * 8;
+                const bf16_t *dor = dOs + (rb * 32 + l32) * LDK + hl * 8;
+#pragma unroll
+                for (int ks = 0; ks < HD / 16; ++ks) {
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(qr + ks * 16),
+                                                                   kf[ks], sacc, 0, 0, 0);
+                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(dor + ks * 16),
+                                                                    vf[ks], dpacc, 0, 0, 0);
+                }
+                f32x16 pacc;
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int qi = rb * 32 + r4 * 8 + hl * 4;  // 4 consecutive query rows of the tile
+                    const float4 l4 = *reinterpret_cast<const float4 *>(lses + qi);
+                    const float4 d4 = *reinterpret_cast<const float4 *>(dlts + qi);
+                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int r = r4 * 4 + e, qq = q0t + qi + e;
+                        const float p = (kv > qq || qq >= T) ? 0.f : __builtin_amdgcn_exp2f(sacc[r] * c - lv[e]);
+                        pacc[r] = p;
+                        sacc[r] = p * (dpacc[r] - dv4[e]);  // dS
+                    }
+                }
+#pragma unroll
+                for (int cch = 0; cch < 2; ++cch) {
+                    const bf16x8 pf = pack_frag(pacc, cch), dsf = pack_frag(sacc, cch);
+#pragma unroll
+                    for (int hb = 0; hb < HD / 32; ++hb) {
+                        dvacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            read_perm_frag(dOTs + (hb * 32 + l32) * LDV, rb, cch, hl), pf, dvacc[hb], 0, 0, 0);
+                        dkacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            read_perm_frag(QTs + (hb * 32 + l32) * LDV, rb, cch, hl), dsf, dkacc[hb], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    if (kvok) {
+        store_owned_rows<HD>(a.dk + ((int64_t)b * T + kv) * a.lddk + (int64_t)hk * HD, dkacc, a.scale, hl);
+        store_owned_rows<HD>(a.dv + ((int64_t)b * T + kv) * a.lddv + (int64_t)hk * HD, dvacc, 1.0f, hl);
+    }
+}
+
+template <typename K>
+hipError_t set_lds(K kernel, size_t bytes) {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)bytes);
+}
+
+bool attn_shape_ok(const AttnArgs &a) {
+    if (a.B <= 0 || a.T <= 0 || a.Hq <= 0 || a.Hkv <= 0 || a.Hq % a.Hkv) return false;
+    if (a.hd != 64 && a.hd != 128) return false;
+    if (a.T & 7) return false;
+    if (a.Hq > 65535 || a.B > 65535) return false;
+    return true;
+}
+bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+
+hipError_t flash_fwd(const AttnArgs &a, hipStream_t s) {
+    if (!attn_shape_ok(a) || (a.ldq & 7) || (a.ldk & 7) || (a.ldo & 3)) return hipErrorInvalidValue;
+    if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.vT) || ((uintptr_t)a.o & 7)) return hipErrorInvalidValue;
+    const dim3 grid((a.T + 127) / 128, a.Hq, a.B);
+    if (a.hd == 128) {
+        constexpr size_t lds = (64 * (128 + 8) + 128 * 72) * sizeof(bf16_t);
+        hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, dim3(256), lds, s, a);
+    } else {
+        constexpr size_t lds = (64 * (64 + 8) + 64 * 72) * sizeof(bf16_t);
+        hipLaunchKernelGGL(flash_fwd_kernel<64>, grid, dim3(256), lds, s, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t flash_bwd_dq(const AttnArgs &a, hipStream_t s) {
+    if (!attn_shape_ok(a) || (a.ldq & 7) || (a.ldk & 7) || (a.ldv & 7) || (a.lddo & 7) || (a.lddq & 3))
+        return hipErrorInvalidValue;
+    if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.kT) || !aligned16(a.dout) ||
+        ((uintptr_t)a.dq & 7))
+        return hipErrorInvalidValue;
+    const dim3 grid((a.T + 127) / 128, a.Hq, a.B);
+    if (a.hd == 128) {
+        constexpr size_t lds = (2 * 64 * (128 + 8) + 128 * 72) * sizeof(bf16_t);
+        hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, dim3(256), lds, s, a);
+    } else {
+        constexpr size_t lds = (2 * 64 * (64 + 8) + 64 * 72) * sizeof(bf16_t);
+        hipLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, dim3(256), lds, s, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t flash_bwd_dkdv(const AttnArgs &a, hipStream_t s) {
+    if (!attn_shape_ok(a) || (a.ldq & 7) || (a.ldk & 7) || (a.ldv & 7) || (a.lddo & 7) || (a.lddk & 3) ||
+        (a.lddv & 3))
+        return hipErrorInvalidValue;
+    if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.qT) || !aligned16(a.doT) ||
+        !aligned16(a.dout) || ((uintptr_t)a.dk & 7) || ((uintptr_t)a.dv & 7))
+        return hipErrorInvalidValue;
+    const dim3 grid((a.T + 127) / 128, a.Hkv, a.B);
+    if (a.hd == 128) {
+        constexpr size_t lds = (2 * 64 * (128 + 8) + 2 * 128 * 72) * sizeof(bf16_t) + 128 * sizeof(float);
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = set_lds(&flash_bwd_dkdv_kernel<128>, lds);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(flash_bwd_dkdv_kernel<128>, grid, dim3(256), lds, s, a);
+    } else {
+        constexpr size_t lds = (2 * 64 * (64 + 8) + 2 * 64 * 72) * sizeof(bf16_t) + 128 * sizeof(float);
+        hipLaunchKernelGGL(flash_bwd_dkdv_kernel<64>, grid, dim3(256), lds, s, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace mt

@@ -1,0 +1,125 @@
+// Shared declarations of the gfx950 library: vector types, bf16 helpers, wave
+// reductions and the launchers that the engine and the kernel-level C ABI call.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace mt {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits in memory
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ float bflo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bfhi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+// round-to-nearest-even pack of two floats (hardware v_cvt_pk_bf16_f32); a in the low half
+__device__ __forceinline__ uint32_t pack2bf(float a, float b) {
+    f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ bf16_t f2bf(float a) { return __builtin_bit_cast(bf16_t, (__bf16)a); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ---------------------------------------------------------------- launchers (host side)
+// Every launcher validates nothing: callers (engine, C ABI wrappers) check shapes first.
+
+// C[M,N] = A[M,K] . B[N,K]^T (+ R) ; A, B bf16 with the reduction index contiguous.
+//   out_fp32 = 0: C bf16, optional residual R bf16 [M,N] added before rounding
+//   out_fp32 = 1: C fp32; accumulate = 1 adds to the existing C
+struct GemmArgs {
+    const bf16_t *A; int64_t lda;
+    const bf16_t *B; int64_t ldb;
+    void *C; int64_t ldc;
+    const bf16_t *R; int64_t ldr;
+    int32_t M, N, K;
+    int32_t out_fp32, accumulate;
+};
+hipError_t gemm_nt(const GemmArgs &g, hipStream_t s);
+
+// out[b][c][r] = in[b][r][c] for r < rows, c < cols (bf16); leading dimensions in elements.
+// Two batch levels (b0 < nb0, b1 < nb1) with independent strides on each side.
+struct TransposeArgs {
+    const bf16_t *in; bf16_t *out;
+    int32_t rows, cols;
+    int64_t ld_in, ld_out;
+    int32_t nb0, nb1;
+    int64_t in_s0, in_s1, out_s0, out_s1;
+};
+hipError_t transpose_bf16(const TransposeArgs &t, hipStream_t s);
+
+hipError_t rmsnorm_fwd(bf16_t *y, const bf16_t *x, const bf16_t *gain, int64_t n, int32_t d, float eps, hipStream_t s);
+// dx_out = dres + rmsnorm_backward(dy; x, gain); dgain[d] fp32 (written). partial: >= rmsnorm_bwd_ws_floats(d) floats.
+size_t rmsnorm_bwd_ws_floats(int32_t d);
+hipError_t rmsnorm_bwd(bf16_t *dx_out, float *dgain, const bf16_t *dy, const bf16_t *x, const bf16_t *gain,
+                       const bf16_t *dres, float *partial, int64_t n, int32_t d, float eps, hipStream_t s);
+
+// In-place rotation of the first n_heads heads of each row of x [n, ld]; cos/sin tables [T, hd/2] fp32;
+// position of row r is r % T; sign +1 forward, -1 inverse.
+hipError_t rope_inplace(bf16_t *x, int64_t ld, int64_t n, int32_t T, int32_t n_heads, int32_t hd, const float *cs,
+                        const float *sn, int sign, hipStream_t s);
+
+// gu [n, 2F] (gate | up) -> s [n, F]
+hipError_t swiglu_fwd(bf16_t *sout, const bf16_t *gu, int64_t n, int32_t F, hipStream_t s);
+// dgu [n, 2F] from ds [n, F] and gu
+hipError_t swiglu_bwd(bf16_t *dgu, const bf16_t *ds, const bf16_t *gu, int64_t n, int32_t F, hipStream_t s);
+
+hipError_t embed_gather(bf16_t *h, const bf16_t *table, const int32_t *tokens, int64_t n, int32_t d, hipStream_t s);
+// dtable[V,d] fp32 fully written: row v = sum of dh rows listed in order[start[v] .. start[v+1])
+hipError_t embed_scatter(float *dtable, const bf16_t *dh, const int32_t *row_start, const int32_t *order, int32_t V,
+                         int32_t d, hipStream_t s);
+
+// Per row: loss_rows[r] = logsumexp(z_r) - z_r[label] (0 for ignored rows); dlogits bf16 = (softmax - onehot) * inv_n
+hipError_t cross_entropy(float *loss_rows, bf16_t *dlogits, const float *logits, const int32_t *labels, int64_t n,
+                         int32_t V, float inv_n, hipStream_t s);
+// out[0] = (accumulate ? out[0] : 0) + scale * sum(in[0..n)) , one block, fixed order
+hipError_t reduce_sum(float *out, const float *in, int64_t n, float scale, int accumulate, hipStream_t s);
+
+// Flash attention (causal, grouped KV heads).  q/k/v/o rows are tokens (b*T + t); head h occupies
+// columns [h*hd, (h+1)*hd) from the given base pointer with the given leading dimension.
+// kT / vT / qT / doT are per-head transposed copies [B, H, hd, T].
+// lse [B, Hq, T] fp32 = log sum_u exp(s_tu) of the scaled scores.
+struct AttnArgs {
+    int32_t B, T, Hq, Hkv, hd;
+    float scale;
+    const bf16_t *q; int64_t ldq;
+    const bf16_t *k; int64_t ldk;
+    const bf16_t *v; int64_t ldv;
+    const bf16_t *qT, *kT, *vT;
+    bf16_t *o; int64_t ldo;
+    float *lse;
+    // backward only
+    const bf16_t *dout; int64_t lddo;
+    const bf16_t *doT;
+    const float *delta;  // [B,Hq,T] rowsum(do * o)
+    bf16_t *dq; int64_t lddq;
+    bf16_t *dk; int64_t lddk;
+    bf16_t *dv; int64_t lddv;
+};
+hipError_t flash_fwd(const AttnArgs &a, hipStream_t s);
+// delta[b,h,t] = sum_j do[b,t,h,j] * o[b,t,h,j]
+hipError_t attn_delta(float *delta, const bf16_t *dout, int64_t lddo, const bf16_t *o, int64_t ldo, int32_t B, int32_t T,
+                      int32_t H, int32_t hd, hipStream_t s);
+hipError_t flash_bwd_dkdv(const AttnArgs &a, hipStream_t s);
+hipError_t flash_bwd_dq(const AttnArgs &a, hipStream_t s);
+
+hipError_t fill_u32(void *p, uint32_t value, size_t n_words, hipStream_t s);
+
+}  // namespace mt

@@ -1,0 +1,988 @@
+// The streamed training step: host-resident state, double-buffered weight streaming,
+// per-block recompute + backward, asynchronous gradient offload (Algorithm 1 and
+// Sections 3.2-3.4 of the MegaTrain paper), scheduled on three HIP streams.
+//
+// Units.  The model is cut into L+2 streamed units: E (embedding table), blocks 1..L and
+// H (final norm + LM head).  Each unit owns one contiguous pinned bf16 block on the host
+// (what StreamIn copies, one DMA per unit) and one contiguous pinned fp32 gradient block
+// (what Offload fills, one DMA per unit).  Inside a block the tensors are ordered
+//     wq | wk | wv | wo | w_gate | w_up | w_down | attn_norm | mlp_norm
+// so q/k/v and gate/up form single [out,in] matrices and run as one GEMM each.  The device
+// "templates" are just kernels taking pointers: binding a streamed buffer is pointer
+// arithmetic on the buffer base, done at launch.
+//
+// Streams and events.  S_comp runs kernels, S_h2d the weight copies, S_d2h the gradient
+// copies.  Weight loads are numbered s = 0..2L+1 (E, 1..L, H, L..1) and use device buffer
+// s % 2; gradient blocks are numbered r = 0..L+1 (H, L..1, E) and use buffer r % 2.
+//   w_ready[s]  recorded on S_h2d after load s          -> S_comp waits before using it
+//   w_free[s]   recorded on S_comp after its last use    -> S_h2d waits before load s+2
+//   g_ready[r]  recorded on S_comp after grads r exist   -> S_d2h waits before copying
+//   g_free[r]   recorded on S_d2h after the copy         -> S_comp waits before grads r+2
+// The paper names three of these (Weights-Ready, Backward-Done, Buffer-Free); w_free is the
+// event behind its "Release(theta_i)".
+#include <hip/hip_runtime.h>
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <algorithm>
+#include <chrono>
+#include <string>
+#include <vector>
+
+#include "../../include/megatrain.h"
+#include "common.h"
+#include "host_ops.h"
+
+using namespace mt;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+mt_status fail(mt_status code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIPCHK(expr)                                                                                  \
+    do {                                                                                              \
+        hipError_t e_ = (expr);                                                                       \
+        if (e_ != hipSuccess)                                                                         \
+            return fail(MT_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+double now_ms() {
+    return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+struct Dims {
+    int L, d, Hq, Hkv, hd, F, V;
+    int64_t Nq, Nkv, Nqkv;
+};
+
+struct TensorRef {
+    int unit;        // which streamed unit
+    size_t off;      // element offset inside the unit block
+    size_t numel;
+};
+
+struct Unit {
+    size_t numel = 0;
+    uint16_t *h_shadow = nullptr;  // pinned bf16 block
+    float *h_grad = nullptr;       // pinned fp32 block
+};
+
+// element offsets inside a block unit
+struct LayerOff {
+    size_t wqkv, wo, wgu, wd, g1, g2, total;
+};
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+mt_status check_cfg(const mt_model_cfg *c) {
+    if (!c) return fail(MT_ERR_INVALID_ARG, "cfg is NULL");
+    if (c->struct_size != sizeof(mt_model_cfg)) return fail(MT_ERR_INVALID_ARG, "cfg.struct_size mismatch");
+    if (c->abi_version != MT_ABI_VERSION) return fail(MT_ERR_INVALID_ARG, "cfg.abi_version mismatch");
+    if (c->n_layers <= 0 || c->hidden <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 ||
+        c->ffn <= 0 || c->vocab <= 0)
+        return fail(MT_ERR_INVALID_ARG, "model dimensions must be positive");
+    if (c->n_q_heads % c->n_kv_heads) return fail(MT_ERR_INVALID_ARG, "n_q_heads must be a multiple of n_kv_heads");
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(MT_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if ((c->hidden & 7) || (c->ffn & 7) || (c->vocab & 7))
+        return fail(MT_ERR_UNSUPPORTED, "hidden, ffn and vocab must be multiples of 8");
+    if (c->hidden > 8192) return fail(MT_ERR_UNSUPPORTED, "hidden > 8192 is not supported");
+    if (c->ckpt_interval != 1) return fail(MT_ERR_UNSUPPORTED, "only checkpoint interval 1 is implemented");
+    if (!(c->rope_base > 0.f) || !(c->rms_eps > 0.f)) return fail(MT_ERR_INVALID_ARG, "rope_base and rms_eps must be > 0");
+    return MT_OK;
+}
+
+Dims dims_of(const mt_model_cfg *c) {
+    Dims D;
+    D.L = c->n_layers; D.d = c->hidden; D.Hq = c->n_q_heads; D.Hkv = c->n_kv_heads; D.hd = c->head_dim;
+    D.F = c->ffn; D.V = c->vocab;
+    D.Nq = (int64_t)D.Hq * D.hd; D.Nkv = (int64_t)D.Hkv * D.hd; D.Nqkv = D.Nq + 2 * D.Nkv;
+    return D;
+}
+
+LayerOff layer_off(const Dims &D) {
+    LayerOff o;
+    o.wqkv = 0;
+    o.wo = o.wqkv + (size_t)D.Nqkv * D.d;
+    o.wgu = o.wo + (size_t)D.d * D.Nq;
+    o.wd = o.wgu + (size_t)2 * D.F * D.d;
+    o.g1 = o.wd + (size_t)D.d * D.F;
+    o.g2 = o.g1 + D.d;
+    o.total = o.g2 + D.d;
+    return o;
+}
+
+void tensor_shape(const Dims &D, int idx, int64_t *rows, int64_t *cols, std::string *name) {
+    const int n = 9 * D.L + 3;
+    auto set = [&](int64_t r, int64_t c, const std::string &s) {
+        *rows = r; *cols = c;
+        if (name) *name = s;
+    };
+    if (idx == 0) return set(D.V, D.d, "embed");
+    if (idx == n - 2) return set(D.d, 1, "final_norm");
+    if (idx == n - 1) return set(D.V, D.d, "lm_head");
+    const int l = (idx - 1) / 9, k = (idx - 1) % 9;
+    const std::string p = "l" + std::to_string(l) + ".";
+    switch (k) {
+        case 0: return set(D.d, 1, p + "attn_norm");
+        case 1: return set(D.Nq, D.d, p + "wq");
+        case 2: return set(D.Nkv, D.d, p + "wk");
+        case 3: return set(D.Nkv, D.d, p + "wv");
+        case 4: return set(D.d, D.Nq, p + "wo");
+        case 5: return set(D.d, 1, p + "mlp_norm");
+        case 6: return set(D.F, D.d, p + "w_gate");
+        case 7: return set(D.F, D.d, p + "w_up");
+        default: return set(D.d, D.F, p + "w_down");
+    }
+}
+
+}  // namespace
+
+struct mt_handle {
+    mt_model_cfg cfg;
+    Dims D;
+    LayerOff lo;
+    int n_tensors = 0;
+    std::vector<float *> params;      // caller-owned fp32 master
+    std::vector<TensorRef> tref;      // where each tensor lives inside its unit
+    std::vector<Unit> units;          // 0 = E, 1..L = blocks, L+1 = H
+    std::vector<float *> adam_m, adam_v;  // per unit, pageable
+    size_t pmax = 0;                  // largest unit, elements
+
+    // device
+    char *arena = nullptr;
+    size_t arena_bytes = 0;
+    uint16_t *Wbuf[2] = {nullptr, nullptr};
+    float *Gbuf[2] = {nullptr, nullptr};
+    std::vector<uint16_t *> anchors;  // h_0..h_L
+    uint16_t *xn, *yn, *qkv, *att, *h1, *gu, *sact, *vT, *qT, *kT, *doT;
+    uint16_t *dsact, *dgu, *dyn, *dh1, *datt, *dqkv, *dxn, *gA, *gB, *tA, *tB, *wT;
+    uint16_t *dlogits, *dlT;
+    float *lse, *delta, *logits, *loss_rows, *loss_dev, *norm_ws, *rope_cos, *rope_sin;
+    int32_t *tok_dev, *lab_dev, *rowstart_dev, *order_dev;
+    int64_t ce_chunk = 0;
+    // pinned staging
+    int32_t *tok_host = nullptr;  // tokens | labels | row_start | order
+    float *loss_host = nullptr;
+
+    hipStream_t s_comp = nullptr, s_h2d = nullptr, s_d2h = nullptr;
+    std::vector<hipEvent_t> w_ready, w_free, g_ready, g_free, h2d_start, comp_start, d2h_start;
+    hipEvent_t ev_ref = nullptr, ev_inputs = nullptr;
+    int resident[2] = {-1, -1};
+
+    mt_stats stats;
+    bool have_grads = false;
+    size_t pinned_bytes = 0, pageable_bytes = 0;
+};
+
+namespace {
+
+// ------------------------------------------------------------------ small launch helpers
+#define KCHK(expr)                                                                                   \
+    do {                                                                                             \
+        hipError_t e_ = (expr);                                                                      \
+        if (e_ != hipSuccess)                                                                        \
+            return fail(MT_ERR_HIP, "%s: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+hipError_t gemm(hipStream_t s, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, void *C, int64_t ldc,
+                int64_t M, int64_t N, int64_t K, bool out_fp32 = false, bool accumulate = false,
+                const uint16_t *R = nullptr, int64_t ldr = 0) {
+    GemmArgs g;
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.R = R; g.ldr = ldr;
+    g.M = (int32_t)M; g.N = (int32_t)N; g.K = (int32_t)K;
+    g.out_fp32 = out_fp32; g.accumulate = accumulate;
+    return gemm_nt(g, s);
+}
+
+// out[cols, rows] = in[rows, cols]^T
+hipError_t transpose2d(hipStream_t s, const uint16_t *in, uint16_t *out, int64_t rows, int64_t cols, int64_t ld_in,
+                       int64_t ld_out) {
+    TransposeArgs t;
+    t.in = in; t.out = out; t.rows = (int32_t)rows; t.cols = (int32_t)cols; t.ld_in = ld_in; t.ld_out = ld_out;
+    t.nb0 = 1; t.nb1 = 1; t.in_s0 = t.in_s1 = t.out_s0 = t.out_s1 = 0;
+    return transpose_bf16(t, s);
+}
+
+// per-head transpose of a [B*T, ld] activation slice (H heads of hd columns) into [B, H, hd, T]
+hipError_t transpose_heads(hipStream_t s, const uint16_t *in, int64_t ld, uint16_t *out, int B, int T, int H, int hd) {
+    TransposeArgs t;
+    t.in = in; t.out = out; t.rows = T; t.cols = hd; t.ld_in = ld; t.ld_out = T;
+    t.nb0 = B; t.nb1 = H;
+    t.in_s0 = (int64_t)T * ld; t.in_s1 = hd;
+    t.out_s0 = (int64_t)H * hd * T; t.out_s1 = (int64_t)hd * T;
+    return transpose_bf16(t, s);
+}
+
+struct LayerW {
+    const uint16_t *wqkv, *wo, *wgu, *wd, *g1, *g2;
+};
+LayerW bind_layer(const uint16_t *base, const LayerOff &o) {
+    return {base + o.wqkv, base + o.wo, base + o.wgu, base + o.wd, base + o.g1, base + o.g2};
+}
+
+AttnArgs attn_args(const mt_handle *h, int B, int T) {
+    const Dims &D = h->D;
+    AttnArgs a;
+    memset(&a, 0, sizeof(a));
+    a.B = B; a.T = T; a.Hq = D.Hq; a.Hkv = D.Hkv; a.hd = D.hd;
+    a.scale = 1.0f / sqrtf((float)D.hd);
+    a.q = h->qkv; a.ldq = D.Nqkv;
+    a.k = h->qkv + D.Nq; a.ldk = D.Nqkv;
+    a.v = h->qkv + D.Nq + D.Nkv; a.ldv = D.Nqkv;
+    a.qT = h->qT; a.kT = h->kT; a.vT = h->vT;
+    a.o = h->att; a.ldo = D.Nq;
+    a.lse = h->lse;
+    a.dout = h->datt; a.lddo = D.Nq;
+    a.doT = h->doT;
+    a.delta = h->delta;
+    a.dq = h->dqkv; a.lddq = D.Nqkv;
+    a.dk = h->dqkv + D.Nq; a.lddk = D.Nqkv;
+    a.dv = h->dqkv + D.Nq + D.Nkv; a.lddv = D.Nqkv;
+    return a;
+}
+
+// f_i of Algorithm 1.  y may be NULL (recompute before backward does not need the block output).
+mt_status layer_forward(mt_handle *h, const LayerW &w, const uint16_t *x, uint16_t *y, int B, int T) {
+    const Dims &D = h->D;
+    const int64_t n = (int64_t)B * T;
+    hipStream_t s = h->s_comp;
+    KCHK(rmsnorm_fwd(h->xn, x, w.g1, n, D.d, h->cfg.rms_eps, s));
+    KCHK(gemm(s, h->xn, D.d, w.wqkv, D.d, h->qkv, D.Nqkv, n, D.Nqkv, D.d));
+    KCHK(rope_inplace(h->qkv, D.Nqkv, n, T, D.Hq + D.Hkv, D.hd, h->rope_cos, h->rope_sin, +1, s));
+    KCHK(transpose_heads(s, h->qkv + D.Nq + D.Nkv, D.Nqkv, h->vT, B, T, D.Hkv, D.hd));
+    const AttnArgs a = attn_args(h, B, T);
+    KCHK(flash_fwd(a, s));
+    KCHK(gemm(s, h->att, D.Nq, w.wo, D.Nq, h->h1, D.d, n, D.d, D.Nq, false, false, x, D.d));
+    KCHK(rmsnorm_fwd(h->yn, h->h1, w.g2, n, D.d, h->cfg.rms_eps, s));
+    KCHK(gemm(s, h->yn, D.d, w.wgu, D.d, h->gu, 2 * D.F, n, 2 * D.F, D.d));
+    KCHK(swiglu_fwd(h->sact, h->gu, n, D.F, s));
+    if (y) KCHK(gemm(s, h->sact, D.F, w.wd, D.F, y, D.d, n, D.d, D.F, false, false, h->h1, D.d));
+    return MT_OK;
+}
+
+// LocalBackward of Algorithm 1: the block's internals are in the work buffers (just recomputed).
+// gy = dl/dy, gx receives dl/dx; fp32 weight gradients go to G (unit layout).
+mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t *x, const uint16_t *gy, uint16_t *gx,
+                         int B, int T) {
+    const Dims &D = h->D;
+    const LayerOff &o = h->lo;
+    const int64_t n = (int64_t)B * T;
+    hipStream_t s = h->s_comp;
+    // y = h1 + s Wd^T
+    KCHK(transpose2d(s, gy, h->tA, n, D.d, D.d, n));
+    KCHK(transpose2d(s, h->sact, h->tB, n, D.F, D.F, n));
+    KCHK(gemm(s, h->tA, n, h->tB, n, G + o.wd, D.F, D.d, D.F, n, true));
+    KCHK(transpose2d(s, w.wd, h->wT, D.d, D.F, D.F, D.d));
+    KCHK(gemm(s, gy, D.d, h->wT, D.d, h->dsact, D.F, n, D.F, D.d));
+    KCHK(swiglu_bwd(h->dgu, h->dsact, h->gu, n, D.F, s));
+    // gu = yn Wgu^T
+    KCHK(transpose2d(s, h->dgu, h->tA, n, 2 * D.F, 2 * D.F, n));
+    KCHK(transpose2d(s, h->yn, h->tB, n, D.d, D.d, n));
+    KCHK(gemm(s, h->tA, n, h->tB, n, G + o.wgu, D.d, 2 * D.F, D.d, n, true));
+    KCHK(transpose2d(s, w.wgu, h->wT, 2 * D.F, D.d, D.d, 2 * D.F));
+    KCHK(gemm(s, h->dgu, 2 * D.F, h->wT, 2 * D.F, h->dyn, D.d, n, D.d, 2 * D.F));
+    KCHK(rmsnorm_bwd(h->dh1, G + o.g2, h->dyn, h->h1, w.g2, gy, h->norm_ws, n, D.d, h->cfg.rms_eps, s));
+    // h1 = x + att Wo^T
+    KCHK(transpose2d(s, h->dh1, h->tA, n, D.d, D.d, n));
+    KCHK(transpose2d(s, h->att, h->tB, n, D.Nq, D.Nq, n));
+    KCHK(gemm(s, h->tA, n, h->tB, n, G + o.wo, D.Nq, D.d, D.Nq, n, true));
+    KCHK(transpose2d(s, w.wo, h->wT, D.d, D.Nq, D.Nq, D.d));
+    KCHK(gemm(s, h->dh1, D.d, h->wT, D.d, h->datt, D.Nq, n, D.Nq, D.d));
+    // attention
+    const AttnArgs a = attn_args(h, B, T);
+    KCHK(transpose_heads(s, h->qkv, D.Nqkv, h->qT, B, T, D.Hq, D.hd));
+    KCHK(transpose_heads(s, h->qkv + D.Nq, D.Nqkv, h->kT, B, T, D.Hkv, D.hd));
+    KCHK(transpose_heads(s, h->datt, D.Nq, h->doT, B, T, D.Hq, D.hd));
+    KCHK(attn_delta(h->delta, h->datt, D.Nq, h->att, D.Nq, B, T, D.Hq, D.hd, s));
+    KCHK(flash_bwd_dkdv(a, s));
+    KCHK(flash_bwd_dq(a, s));
+    KCHK(rope_inplace(h->dqkv, D.Nqkv, n, T, D.Hq + D.Hkv, D.hd, h->rope_cos, h->rope_sin, -1, s));
+    // qkv = xn Wqkv^T
+    KCHK(transpose2d(s, h->dqkv, h->tA, n, D.Nqkv, D.Nqkv, n));
+    KCHK(transpose2d(s, h->xn, h->tB, n, D.d, D.d, n));
+    KCHK(gemm(s, h->tA, n, h->tB, n, G + o.wqkv, D.d, D.Nqkv, D.d, n, true));
+    KCHK(transpose2d(s, w.wqkv, h->wT, D.Nqkv, D.d, D.d, D.Nqkv));
+    KCHK(gemm(s, h->dqkv, D.Nqkv, h->wT, D.Nqkv, h->dxn, D.d, n, D.d, D.Nqkv));
+    KCHK(rmsnorm_bwd(gx, G + o.g1, h->dxn, x, w.g1, h->dh1, h->norm_ws, n, D.d, h->cfg.rms_eps, s));
+    return MT_OK;
+}
+
+// Phase 2 of Algorithm 1: loss, g_L and the head gradients, in token chunks so the logits stay small.
+mt_status head_forward_backward(mt_handle *h, const uint16_t *W, float *G, const uint16_t *x, uint16_t *gx, int64_t n,
+                                float inv_n) {
+    const Dims &D = h->D;
+    hipStream_t s = h->s_comp;
+    const uint16_t *wlm = W, *gf = W + (size_t)D.V * D.d;
+    float *dWlm = G, *dgf = G + (size_t)D.V * D.d;
+    uint16_t *zn = h->xn, *dzn = h->dxn;
+    KCHK(rmsnorm_fwd(zn, x, gf, n, D.d, h->cfg.rms_eps, s));
+    KCHK(transpose2d(s, wlm, h->wT, D.V, D.d, D.d, D.V));   // [d, V]
+    KCHK(transpose2d(s, zn, h->tB, n, D.d, D.d, n));        // [d, n]
+    for (int64_t c0 = 0; c0 < n; c0 += h->ce_chunk) {
+        const int64_t rows = std::min<int64_t>(h->ce_chunk, n - c0);
+        KCHK(gemm(s, zn + c0 * D.d, D.d, wlm, D.d, h->logits, D.V, rows, D.V, D.d, true));
+        KCHK(cross_entropy(h->loss_rows + c0, h->dlogits, h->logits, h->lab_dev + c0, rows, D.V, inv_n, s));
+        KCHK(gemm(s, h->dlogits, D.V, h->wT, D.V, dzn + c0 * D.d, D.d, rows, D.d, D.V));
+        KCHK(transpose2d(s, h->dlogits, h->dlT, rows, D.V, D.V, rows));  // [V, rows]
+        KCHK(gemm(s, h->dlT, rows, h->tB + c0, n, dWlm, D.d, D.V, D.d, rows, true, c0 > 0));
+    }
+    KCHK(reduce_sum(h->loss_dev, h->loss_rows, n, inv_n, 0, s));
+    KCHK(rmsnorm_bwd(gx, dgf, dzn, x, gf, nullptr, h->norm_ws, n, D.d, h->cfg.rms_eps, s));
+    return MT_OK;
+}
+
+void build_shadow(mt_handle *h) {
+    for (int i = 0; i < h->n_tensors; ++i) {
+        const TensorRef &t = h->tref[i];
+        host_f32_to_bf16(h->units[t.unit].h_shadow + t.off, h->params[i], t.numel);
+    }
+    h->resident[0] = h->resident[1] = -1;
+}
+
+void free_handle(mt_handle *h) {
+    if (!h) return;
+    (void)hipSetDevice(h->cfg.device_id);
+    (void)hipDeviceSynchronize();
+    auto kill_events = [](std::vector<hipEvent_t> &v) {
+        for (auto e : v)
+            if (e) (void)hipEventDestroy(e);
+        v.clear();
+    };
+    kill_events(h->w_ready); kill_events(h->w_free); kill_events(h->g_ready); kill_events(h->g_free);
+    kill_events(h->h2d_start); kill_events(h->comp_start); kill_events(h->d2h_start);
+    if (h->ev_ref) (void)hipEventDestroy(h->ev_ref);
+    if (h->ev_inputs) (void)hipEventDestroy(h->ev_inputs);
+    if (h->s_comp) (void)hipStreamDestroy(h->s_comp);
+    if (h->s_h2d) (void)hipStreamDestroy(h->s_h2d);
+    if (h->s_d2h) (void)hipStreamDestroy(h->s_d2h);
+    if (h->arena) (void)hipFree(h->arena);
+    for (auto &u : h->units) {
+        if (u.h_shadow) (void)hipHostFree(u.h_shadow);
+        if (u.h_grad) (void)hipHostFree(u.h_grad);
+    }
+    for (auto p : h->adam_m) free(p);
+    for (auto p : h->adam_v) free(p);
+    if (h->tok_host) (void)hipHostFree(h->tok_host);
+    if (h->loss_host) (void)hipHostFree(h->loss_host);
+    delete h;
+}
+
+// interval arithmetic for the overlap statistics
+struct Iv { double a, b; };
+double overlap_with_union(const std::vector<Iv> &xs, std::vector<Iv> busy) {
+    std::sort(busy.begin(), busy.end(), [](const Iv &p, const Iv &q) { return p.a < q.a; });
+    std::vector<Iv> u;
+    for (const Iv &iv : busy) {
+        if (iv.b <= iv.a) continue;
+        if (!u.empty() && iv.a <= u.back().b) u.back().b = std::max(u.back().b, iv.b);
+        else u.push_back(iv);
+    }
+    double tot = 0;
+    for (const Iv &x : xs)
+        for (const Iv &y : u) {
+            const double lo = std::max(x.a, y.a), hi = std::min(x.b, y.b);
+            if (hi > lo) tot += hi - lo;
+        }
+    return tot;
+}
+
+}  // namespace
+
+// ====================================================================== C ABI
+extern "C" {
+
+const char *mt_last_error(void) { return g_err; }
+
+mt_status mt_tensor_count(const mt_model_cfg *cfg, int32_t *n) {
+    if (!cfg || !n) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (cfg->n_layers <= 0) return fail(MT_ERR_INVALID_ARG, "n_layers must be positive");
+    *n = 9 * cfg->n_layers + 3;
+    return MT_OK;
+}
+
+mt_status mt_tensor_info(const mt_model_cfg *cfg, int32_t idx, int64_t *rows, int64_t *cols, const char **name) {
+    if (!cfg || !rows || !cols) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (cfg->n_layers <= 0 || idx < 0 || idx >= 9 * cfg->n_layers + 3) return fail(MT_ERR_INVALID_ARG, "tensor index out of range");
+    static thread_local std::string nm;
+    const Dims D = dims_of(cfg);
+    tensor_shape(D, idx, rows, cols, &nm);
+    if (name) *name = nm.c_str();
+    return MT_OK;
+}
+
+void *mt_host_alloc(size_t bytes) {
+    void *p = nullptr;
+    if (bytes == 0) return nullptr;
+    if (hipHostMalloc(&p, bytes, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    return p;
+}
+
+void mt_host_free(void *p) {
+    if (p) (void)hipHostFree(p);
+}
+
+mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_handle **out) {
+    if (!out) return fail(MT_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    mt_status st = check_cfg(cfg);
+    if (st != MT_OK) return st;
+    if (!host_param_ptrs) return fail(MT_ERR_INVALID_ARG, "host_param_ptrs is NULL");
+    if (cfg->max_batch <= 0 || cfg->max_seq <= 0) return fail(MT_ERR_INVALID_ARG, "max_batch and max_seq must be positive");
+    if (cfg->max_seq & 7) return fail(MT_ERR_UNSUPPORTED, "max_seq must be a multiple of 8");
+    const Dims D = dims_of(cfg);
+    const int nt = 9 * D.L + 3;
+    for (int i = 0; i < nt; ++i)
+        if (!host_param_ptrs[i]) return fail(MT_ERR_INVALID_ARG, "host_param_ptrs[%d] is NULL", i);
+    const int64_t n = (int64_t)cfg->max_batch * cfg->max_seq;
+    if (n > (int64_t)1 << 24) return fail(MT_ERR_UNSUPPORTED, "more than 2^24 tokens per step");
+
+    mt_handle *h = new (std::nothrow) mt_handle();
+    if (!h) return fail(MT_ERR_HOST_OOM, "handle allocation failed");
+    h->cfg = *cfg;
+    h->D = D;
+    h->lo = layer_off(D);
+    h->n_tensors = nt;
+    h->params.assign(host_param_ptrs, host_param_ptrs + nt);
+    memset(&h->stats, 0, sizeof(h->stats));
+
+    // ---- unit table and where every canonical tensor sits inside its unit
+    h->units.resize(D.L + 2);
+    h->units[0].numel = (size_t)D.V * D.d;
+    for (int l = 1; l <= D.L; ++l) h->units[l].numel = h->lo.total;
+    h->units[D.L + 1].numel = (size_t)D.V * D.d + D.d;
+    h->tref.resize(nt);
+    h->tref[0] = {0, 0, (size_t)D.V * D.d};
+    for (int l = 0; l < D.L; ++l) {
+        const int u = l + 1, b = 1 + 9 * l;
+        const LayerOff &o = h->lo;
+        h->tref[b + 0] = {u, o.g1, (size_t)D.d};
+        h->tref[b + 1] = {u, o.wqkv, (size_t)D.Nq * D.d};
+        h->tref[b + 2] = {u, o.wqkv + (size_t)D.Nq * D.d, (size_t)D.Nkv * D.d};
+        h->tref[b + 3] = {u, o.wqkv + (size_t)(D.Nq + D.Nkv) * D.d, (size_t)D.Nkv * D.d};
+        h->tref[b + 4] = {u, o.wo, (size_t)D.d * D.Nq};
+        h->tref[b + 5] = {u, o.g2, (size_t)D.d};
+        h->tref[b + 6] = {u, o.wgu, (size_t)D.F * D.d};
+        h->tref[b + 7] = {u, o.wgu + (size_t)D.F * D.d, (size_t)D.F * D.d};
+        h->tref[b + 8] = {u, o.wd, (size_t)D.d * D.F};
+    }
+    h->tref[nt - 2] = {D.L + 1, (size_t)D.V * D.d, (size_t)D.d};
+    h->tref[nt - 1] = {D.L + 1, 0, (size_t)D.V * D.d};
+    h->pmax = 0;
+    size_t total = 0;
+    for (auto &u : h->units) {
+        h->pmax = std::max(h->pmax, u.numel);
+        total += u.numel;
+    }
+    h->stats.n_params = total;
+
+    // ---- device arena plan (all offsets 256-byte aligned)
+    const int64_t chunk = std::min<int64_t>(n, 8192);
+    h->ce_chunk = chunk;
+    size_t off = 0;
+    auto plan = [&](size_t bytes) {
+        const size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    const size_t e2 = sizeof(uint16_t), e4 = sizeof(float);
+    const size_t tA_rows = (size_t)std::max<int64_t>(std::max<int64_t>(2 * D.F, D.Nqkv), D.d);
+    const size_t tB_rows = (size_t)std::max<int64_t>(std::max<int64_t>(D.F, D.Nq), D.d);
+    const size_t wT_elems = std::max<size_t>(std::max<size_t>((size_t)2 * D.F * D.d, (size_t)D.Nqkv * D.d),
+                                            std::max<size_t>((size_t)D.V * D.d, (size_t)D.d * D.Nq));
+    struct Plan {
+        size_t W[2], G[2], anchors, xn, yn, qkv, att, h1, gu, sact, vT, qT, kT, doT, dsact, dgu, dyn, dh1, datt, dqkv,
+            dxn, gA, gB, tA, tB, wT, dlogits, dlT, lse, delta, logits, loss_rows, loss_dev, norm_ws, rope_cos, rope_sin,
+            tok, lab, rowstart, order;
+    } P;
+    for (int i = 0; i < 2; ++i) P.W[i] = plan(h->pmax * e2);
+    for (int i = 0; i < 2; ++i) P.G[i] = plan(h->pmax * e4);
+    P.anchors = plan((size_t)(D.L + 1) * n * D.d * e2);
+    P.xn = plan(n * D.d * e2); P.yn = plan(n * D.d * e2);
+    P.qkv = plan(n * D.Nqkv * e2); P.att = plan(n * D.Nq * e2); P.h1 = plan(n * D.d * e2);
+    P.gu = plan(n * 2 * D.F * e2); P.sact = plan(n * D.F * e2);
+    P.vT = plan(n * D.Nkv * e2); P.qT = plan(n * D.Nq * e2); P.kT = plan(n * D.Nkv * e2); P.doT = plan(n * D.Nq * e2);
+    P.dsact = plan(n * D.F * e2); P.dgu = plan(n * 2 * D.F * e2);
+    P.dyn = plan(n * D.d * e2); P.dh1 = plan(n * D.d * e2); P.datt = plan(n * D.Nq * e2);
+    P.dqkv = plan(n * D.Nqkv * e2); P.dxn = plan(n * D.d * e2);
+    P.gA = plan(n * D.d * e2); P.gB = plan(n * D.d * e2);
+    P.tA = plan(tA_rows * n * e2); P.tB = plan(tB_rows * n * e2);
+    P.wT = plan(wT_elems * e2);
+    P.dlogits = plan((size_t)chunk * D.V * e2); P.dlT = plan((size_t)chunk * D.V * e2);
+    P.lse = plan((size_t)n * D.Hq * e4); P.delta = plan((size_t)n * D.Hq * e4);
+    P.logits = plan((size_t)chunk * D.V * e4);
+    P.loss_rows = plan(n * e4); P.loss_dev = plan(256);
+    P.norm_ws = plan(rmsnorm_bwd_ws_floats(D.d) * e4);
+    P.rope_cos = plan((size_t)cfg->max_seq * (D.hd / 2) * e4);
+    P.rope_sin = plan((size_t)cfg->max_seq * (D.hd / 2) * e4);
+    P.tok = plan(n * 4); P.lab = plan(n * 4); P.rowstart = plan(((size_t)D.V + 1) * 4); P.order = plan(n * 4);
+    h->arena_bytes = off;
+    h->stats.device_arena_bytes = off;
+    if (cfg->max_device_bytes && off > cfg->max_device_bytes) {
+        const size_t need = off;
+        delete h;
+        return fail(MT_ERR_DEVICE_OOM, "device arena needs %zu bytes, cap is %llu", need,
+                    (unsigned long long)cfg->max_device_bytes);
+    }
+
+#define CREATE_HIP(expr)                                                                            \
+    do {                                                                                            \
+        hipError_t e_ = (expr);                                                                     \
+        if (e_ != hipSuccess) {                                                                     \
+            fail(MT_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));                        \
+            (void)hipGetLastError();                                                                \
+            free_handle(h);                                                                         \
+            return MT_ERR_HIP;                                                                      \
+        }                                                                                           \
+    } while (0)
+
+    CREATE_HIP(hipSetDevice(cfg->device_id));
+    {
+        hipError_t e = hipMalloc((void **)&h->arena, h->arena_bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            h->arena = nullptr;
+            const size_t need = h->arena_bytes;
+            free_handle(h);
+            return fail(MT_ERR_DEVICE_OOM, "hipMalloc of the %zu-byte device arena failed: %s", need,
+                        hipGetErrorString(e));
+        }
+    }
+    char *A = h->arena;
+    for (int i = 0; i < 2; ++i) {
+        h->Wbuf[i] = (uint16_t *)(A + P.W[i]);
+        h->Gbuf[i] = (float *)(A + P.G[i]);
+    }
+    h->anchors.resize(D.L + 1);
+    for (int i = 0; i <= D.L; ++i) h->anchors[i] = (uint16_t *)(A + P.anchors) + (size_t)i * n * D.d;
+    h->xn = (uint16_t *)(A + P.xn); h->yn = (uint16_t *)(A + P.yn); h->qkv = (uint16_t *)(A + P.qkv);
+    h->att = (uint16_t *)(A + P.att); h->h1 = (uint16_t *)(A + P.h1); h->gu = (uint16_t *)(A + P.gu);
+    h->sact = (uint16_t *)(A + P.sact); h->vT = (uint16_t *)(A + P.vT); h->qT = (uint16_t *)(A + P.qT);
+    h->kT = (uint16_t *)(A + P.kT); h->doT = (uint16_t *)(A + P.doT); h->dsact = (uint16_t *)(A + P.dsact);
+    h->dgu = (uint16_t *)(A + P.dgu); h->dyn = (uint16_t *)(A + P.dyn); h->dh1 = (uint16_t *)(A + P.dh1);
+    h->datt = (uint16_t *)(A + P.datt); h->dqkv = (uint16_t *)(A + P.dqkv); h->dxn = (uint16_t *)(A + P.dxn);
+    h->gA = (uint16_t *)(A + P.gA); h->gB = (uint16_t *)(A + P.gB); h->tA = (uint16_t *)(A + P.tA);
+    h->tB = (uint16_t *)(A + P.tB); h->wT = (uint16_t *)(A + P.wT); h->dlogits = (uint16_t *)(A + P.dlogits);
+    h->dlT = (uint16_t *)(A + P.dlT); h->lse = (float *)(A + P.lse); h->delta = (float *)(A + P.delta);
+    h->logits = (float *)(A + P.logits); h->loss_rows = (float *)(A + P.loss_rows);
+    h->loss_dev = (float *)(A + P.loss_dev); h->norm_ws = (float *)(A + P.norm_ws);
+    h->rope_cos = (float *)(A + P.rope_cos); h->rope_sin = (float *)(A + P.rope_sin);
+    h->tok_dev = (int32_t *)(A + P.tok); h->lab_dev = (int32_t *)(A + P.lab);
+    h->rowstart_dev = (int32_t *)(A + P.rowstart); h->order_dev = (int32_t *)(A + P.order);
+
+    CREATE_HIP(hipStreamCreateWithFlags(&h->s_comp, hipStreamNonBlocking));
+    CREATE_HIP(hipStreamCreateWithFlags(&h->s_h2d, hipStreamNonBlocking));
+    CREATE_HIP(hipStreamCreateWithFlags(&h->s_d2h, hipStreamNonBlocking));
+    const int nloads = 2 * D.L + 2, ngrads = D.L + 2;
+    auto make_events = [&](std::vector<hipEvent_t> &v, int cnt) -> hipError_t {
+        v.assign(cnt, nullptr);
+        for (int i = 0; i < cnt; ++i) {
+            hipError_t e = hipEventCreate(&v[i]);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    };
+    CREATE_HIP(make_events(h->w_ready, nloads));
+    CREATE_HIP(make_events(h->w_free, nloads));
+    CREATE_HIP(make_events(h->h2d_start, nloads));
+    CREATE_HIP(make_events(h->comp_start, nloads + 1));  // + the embedding backward
+    CREATE_HIP(make_events(h->g_ready, ngrads));
+    CREATE_HIP(make_events(h->g_free, ngrads));
+    CREATE_HIP(make_events(h->d2h_start, ngrads));
+    CREATE_HIP(hipEventCreate(&h->ev_ref));
+    CREATE_HIP(hipEventCreate(&h->ev_inputs));
+
+    // ---- host state
+    size_t pinned = 0, pageable = 0;
+    for (auto &u : h->units) {
+        if (hipHostMalloc((void **)&u.h_shadow, align_up(u.numel * e2, 4096), hipHostMallocDefault) != hipSuccess ||
+            hipHostMalloc((void **)&u.h_grad, align_up(u.numel * e4, 4096), hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            free_handle(h);
+            return fail(MT_ERR_HOST_OOM, "pinned host allocation failed");
+        }
+        pinned += align_up(u.numel * e2, 4096) + align_up(u.numel * e4, 4096);
+    }
+    h->adam_m.assign(h->units.size(), nullptr);
+    h->adam_v.assign(h->units.size(), nullptr);
+    for (size_t u = 0; u < h->units.size(); ++u) {
+        void *pm = nullptr, *pv = nullptr;
+        const size_t bytes = align_up(h->units[u].numel * e4, 4096);
+        if (posix_memalign(&pm, 4096, bytes) || posix_memalign(&pv, 4096, bytes)) {
+            free(pm);
+            free_handle(h);
+            return fail(MT_ERR_HOST_OOM, "Adam moment allocation failed");
+        }
+        h->adam_m[u] = (float *)pm;
+        h->adam_v[u] = (float *)pv;
+        host_zero(pm, bytes);
+        host_zero(pv, bytes);
+        host_zero(h->units[u].h_grad, bytes);
+        pageable += 2 * bytes;
+    }
+    const size_t stage_ints = (size_t)3 * n + D.V + 1;
+    if (hipHostMalloc((void **)&h->tok_host, stage_ints * 4, hipHostMallocDefault) != hipSuccess ||
+        hipHostMalloc((void **)&h->loss_host, 256, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        free_handle(h);
+        return fail(MT_ERR_HOST_OOM, "pinned staging allocation failed");
+    }
+    pinned += stage_ints * 4 + 256;
+    h->pinned_bytes = pinned;
+    h->pageable_bytes = pageable;
+    h->stats.host_pinned_bytes = pinned;
+    h->stats.host_pageable_bytes = pageable;
+    build_shadow(h);
+
+    // rotary tables (double precision angles, stored fp32)
+    {
+        const size_t cnt = (size_t)cfg->max_seq * (D.hd / 2);
+        std::vector<float> cs(cnt), sn(cnt);
+        rope_table(cs.data(), sn.data(), cfg->max_seq, D.hd, (double)cfg->rope_base);
+        CREATE_HIP(hipMemcpy(h->rope_cos, cs.data(), cnt * 4, hipMemcpyHostToDevice));
+        CREATE_HIP(hipMemcpy(h->rope_sin, sn.data(), cnt * 4, hipMemcpyHostToDevice));
+    }
+    CREATE_HIP(hipDeviceSynchronize());
+#undef CREATE_HIP
+    *out = h;
+    return MT_OK;
+}
+
+mt_status mt_refresh_shadow(mt_handle *h) {
+    if (!h) return fail(MT_ERR_INVALID_ARG, "handle is NULL");
+    build_shadow(h);
+    return MT_OK;
+}
+
+mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
+                        float *loss) {
+    if (!h || !tokens || !labels || !loss) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (batch <= 0 || seq <= 0) return fail(MT_ERR_SHAPE, "batch and seq must be positive");
+    const Dims &D = h->D;
+    const int64_t n = (int64_t)batch * seq, nmax = (int64_t)h->cfg.max_batch * h->cfg.max_seq;
+    if (seq > h->cfg.max_seq || n > nmax) return fail(MT_ERR_SHAPE, "batch*seq = %lld exceeds the capacity %lld (max_seq %d)", (long long)n, (long long)nmax, h->cfg.max_seq);
+    if (seq & 7) return fail(MT_ERR_SHAPE, "seq must be a multiple of 8");
+    int64_t n_valid = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (tokens[i] < 0 || tokens[i] >= D.V) return fail(MT_ERR_TOKEN_RANGE, "tokens[%lld] = %d outside [0, %d)", (long long)i, tokens[i], D.V);
+        if (labels[i] >= D.V) return fail(MT_ERR_TOKEN_RANGE, "labels[%lld] = %d outside the vocabulary", (long long)i, labels[i]);
+        n_valid += labels[i] >= 0;
+    }
+    const float inv_n = n_valid ? (float)(1.0 / (double)n_valid) : 0.f;
+    const double t_begin = now_ms();
+    HIPCHK(hipSetDevice(h->cfg.device_id));
+
+    const bool serial = h->cfg.flags & MT_FLAG_SERIAL;
+    const bool no_copy = h->cfg.flags & MT_FLAG_COMPUTE_ONLY;
+    const bool no_kern = h->cfg.flags & MT_FLAG_COPY_ONLY;
+    hipStream_t sc = h->s_comp, sh = h->s_h2d, sd = h->s_d2h;
+
+    // ---- stage inputs: tokens | labels | row_start | order (token -> positions, counting sort)
+    int32_t *st_tok = h->tok_host, *st_lab = st_tok + n, *st_rs = st_lab + n, *st_ord = st_rs + (D.V + 1);
+    memcpy(st_tok, tokens, n * 4);
+    memcpy(st_lab, labels, n * 4);
+    memset(st_rs, 0, ((size_t)D.V + 1) * 4);
+    for (int64_t i = 0; i < n; ++i) st_rs[tokens[i] + 1]++;
+    for (int v = 0; v < D.V; ++v) st_rs[v + 1] += st_rs[v];
+    {
+        std::vector<int32_t> cursor(st_rs, st_rs + D.V);
+        for (int64_t i = 0; i < n; ++i) st_ord[cursor[tokens[i]]++] = (int32_t)i;
+    }
+    HIPCHK(hipEventRecord(h->ev_ref, sc));
+    HIPCHK(hipStreamWaitEvent(sh, h->ev_ref, 0));
+    HIPCHK(hipStreamWaitEvent(sd, h->ev_ref, 0));
+    HIPCHK(hipMemcpyAsync(h->tok_dev, st_tok, n * 4, hipMemcpyHostToDevice, sh));
+    HIPCHK(hipMemcpyAsync(h->lab_dev, st_lab, n * 4, hipMemcpyHostToDevice, sh));
+    HIPCHK(hipMemcpyAsync(h->rowstart_dev, st_rs, ((size_t)D.V + 1) * 4, hipMemcpyHostToDevice, sh));
+    HIPCHK(hipMemcpyAsync(h->order_dev, st_ord, n * 4, hipMemcpyHostToDevice, sh));
+    HIPCHK(hipEventRecord(h->ev_inputs, sh));
+    HIPCHK(hipStreamWaitEvent(sc, h->ev_inputs, 0));
+
+    // ---- load schedule: E, 1..L, H, L..1
+    const int nloads = 2 * D.L + 2;
+    std::vector<int> load_unit(nloads);
+    load_unit[0] = 0;
+    for (int l = 1; l <= D.L; ++l) load_unit[l] = l;
+    load_unit[D.L + 1] = D.L + 1;
+    for (int i = 0; i < D.L; ++i) load_unit[D.L + 2 + i] = D.L - i;
+    std::vector<char> load_issued(nloads, 0);
+    h->resident[0] = h->resident[1] = -1;
+    uint64_t h2d_bytes = 0, d2h_bytes = 0;
+    if (no_copy) {
+        // weights of block 1 in both buffers once, so the kernels see finite numbers
+        for (int b = 0; b < 2; ++b)
+            HIPCHK(hipMemcpyAsync(h->Wbuf[b], h->units[1].h_shadow, h->units[1].numel * 2, hipMemcpyHostToDevice, sc));
+    }
+
+    auto issue_load = [&](int s) -> mt_status {
+        const int u = load_unit[s], b = s & 1;
+        if (no_copy || h->resident[b] == u) return MT_OK;
+        if (s >= 2) HIPCHK(hipStreamWaitEvent(sh, h->w_free[s - 2], 0));
+        HIPCHK(hipEventRecord(h->h2d_start[s], sh));
+        HIPCHK(hipMemcpyAsync(h->Wbuf[b], h->units[u].h_shadow, h->units[u].numel * 2, hipMemcpyHostToDevice, sh));
+        HIPCHK(hipEventRecord(h->w_ready[s], sh));
+        h->resident[b] = u;
+        load_issued[s] = 1;
+        h2d_bytes += h->units[u].numel * 2;
+        if (serial) HIPCHK(hipDeviceSynchronize());
+        return MT_OK;
+    };
+    std::vector<char> grad_issued(D.L + 2, 0);
+    auto issue_offload = [&](int r, int u) -> mt_status {
+        HIPCHK(hipEventRecord(h->g_ready[r], sc));
+        if (no_copy) return MT_OK;
+        HIPCHK(hipStreamWaitEvent(sd, h->g_ready[r], 0));
+        HIPCHK(hipEventRecord(h->d2h_start[r], sd));
+        HIPCHK(hipMemcpyAsync(h->units[u].h_grad, h->Gbuf[r & 1], h->units[u].numel * 4, hipMemcpyDeviceToHost, sd));
+        HIPCHK(hipEventRecord(h->g_free[r], sd));
+        grad_issued[r] = 1;
+        d2h_bytes += h->units[u].numel * 4;
+        if (serial) HIPCHK(hipDeviceSynchronize());
+        return MT_OK;
+    };
+    auto begin_unit = [&](int s) -> mt_status {
+        if (load_issued[s]) HIPCHK(hipStreamWaitEvent(sc, h->w_ready[s], 0));
+        HIPCHK(hipEventRecord(h->comp_start[s], sc));
+        return MT_OK;
+    };
+    auto end_unit = [&](int s) -> mt_status {
+        HIPCHK(hipEventRecord(h->w_free[s], sc));
+        if (serial) HIPCHK(hipDeviceSynchronize());
+        return MT_OK;
+    };
+    auto wait_gbuf = [&](int r) -> mt_status {
+        if (r >= 2 && grad_issued[r - 2]) HIPCHK(hipStreamWaitEvent(sc, h->g_free[r - 2], 0));
+        return MT_OK;
+    };
+#define STEP(expr)                   \
+    do {                             \
+        mt_status s_ = (expr);       \
+        if (s_ != MT_OK) {           \
+            (void)hipDeviceSynchronize(); \
+            return s_;               \
+        }                            \
+    } while (0)
+
+    // ---- Phase 1: streaming forward
+    STEP(issue_load(0));
+    for (int s = 0; s <= D.L; ++s) {
+        STEP(issue_load(s + 1));  // prefetch the next unit while this one computes
+        STEP(begin_unit(s));
+        const uint16_t *W = h->Wbuf[s & 1];
+        if (!no_kern) {
+            if (s == 0) {
+                KCHK(embed_gather(h->anchors[0], W, h->tok_dev, n, D.d, sc));
+            } else {
+                STEP(layer_forward(h, bind_layer(W, h->lo), h->anchors[s - 1], h->anchors[s], batch, seq));
+            }
+        }
+        STEP(end_unit(s));
+    }
+    // ---- Phase 2: loss anchoring (head unit, load index L+1, gradient block 0)
+    uint16_t *gcur = h->gA, *gnext = h->gB;
+    {
+        const int s = D.L + 1;
+        STEP(issue_load(s + 1));
+        STEP(begin_unit(s));
+        if (!no_kern)
+            STEP(head_forward_backward(h, h->Wbuf[s & 1], h->Gbuf[0], h->anchors[D.L], gcur, n, inv_n));
+        STEP(end_unit(s));
+        STEP(issue_offload(0, D.L + 1));
+    }
+    // ---- Phase 3: block-wise backward, one block per recomputation block
+    for (int i = 0; i < D.L; ++i) {
+        const int s = D.L + 2 + i, l = D.L - i, r = 1 + i;
+        if (s + 1 < nloads) STEP(issue_load(s + 1));
+        STEP(begin_unit(s));
+        STEP(wait_gbuf(r));
+        if (!no_kern) {
+            const LayerW w = bind_layer(h->Wbuf[s & 1], h->lo);
+            STEP(layer_forward(h, w, h->anchors[l - 1], nullptr, batch, seq));  // RecomputeBlock
+            STEP(layer_backward(h, w, h->Gbuf[r & 1], h->anchors[l - 1], gcur, gnext, batch, seq));
+            std::swap(gcur, gnext);
+        }
+        STEP(end_unit(s));
+        STEP(issue_offload(r, l));
+    }
+    // ---- embedding backward (no weights needed), gradient block L+1
+    {
+        const int r = D.L + 1;
+        HIPCHK(hipEventRecord(h->comp_start[nloads], sc));
+        STEP(wait_gbuf(r));
+        if (!no_kern) KCHK(embed_scatter(h->Gbuf[r & 1], gcur, h->rowstart_dev, h->order_dev, D.V, D.d, sc));
+        STEP(issue_offload(r, 0));
+    }
+    if (!no_kern) HIPCHK(hipMemcpyAsync(h->loss_host, h->loss_dev, 4, hipMemcpyDeviceToHost, sc));
+    HIPCHK(hipStreamSynchronize(sc));
+    HIPCHK(hipStreamSynchronize(sh));
+    HIPCHK(hipStreamSynchronize(sd));
+#undef STEP
+    *loss = no_kern ? 0.f : h->loss_host[0];
+    h->have_grads = true;
+
+    // ---- statistics from event timestamps
+    mt_stats &S = h->stats;
+    S.step_ms = now_ms() - t_begin;
+    S.h2d_bytes = h2d_bytes;
+    S.d2h_bytes = d2h_bytes;
+    S.steps_done++;
+    auto ts = [&](hipEvent_t e, double *out_ms) -> bool {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, h->ev_ref, e) != hipSuccess) {
+            (void)hipGetLastError();
+            return false;
+        }
+        *out_ms = ms;
+        return true;
+    };
+    std::vector<Iv> comp, h2d, d2h;
+    bool ok = true;
+    for (int s = 0; s < nloads && ok; ++s) {
+        Iv iv;
+        ok = ts(h->comp_start[s], &iv.a) && ts(h->w_free[s], &iv.b);
+        if (ok) comp.push_back(iv);
+        if (ok && load_issued[s]) {
+            Iv c;
+            ok = ts(h->h2d_start[s], &c.a) && ts(h->w_ready[s], &c.b);
+            if (ok) h2d.push_back(c);
+        }
+    }
+    for (int r = 0; r < D.L + 2 && ok; ++r) {
+        if (r == D.L + 1) {
+            Iv iv;
+            ok = ts(h->comp_start[nloads], &iv.a) && ts(h->g_ready[r], &iv.b);
+            if (ok) comp.push_back(iv);
+        }
+        if (ok && grad_issued[r]) {
+            Iv c;
+            ok = ts(h->d2h_start[r], &c.a) && ts(h->g_free[r], &c.b);
+            if (ok) d2h.push_back(c);
+        }
+    }
+    S.compute_busy_ms = S.h2d_busy_ms = S.d2h_busy_ms = S.h2d_hidden_ms = S.d2h_hidden_ms = 0;
+    if (ok) {
+        for (auto &iv : comp) S.compute_busy_ms += iv.b - iv.a;
+        for (auto &iv : h2d) S.h2d_busy_ms += iv.b - iv.a;
+        for (auto &iv : d2h) S.d2h_busy_ms += iv.b - iv.a;
+        S.h2d_hidden_ms = overlap_with_union(h2d, comp);
+        S.d2h_hidden_ms = overlap_with_union(d2h, comp);
+    }
+    return MT_OK;
+}
+
+mt_status mt_adam_step(mt_handle *h, float lr, float beta1, float beta2, float eps, float wd, int64_t step) {
+    if (!h) return fail(MT_ERR_INVALID_ARG, "handle is NULL");
+    if (step < 1) return fail(MT_ERR_INVALID_ARG, "step must be >= 1");
+    if (!h->have_grads) return fail(MT_ERR_STATE, "mt_adam_step before any successful mt_train_step");
+    const double t0 = now_ms();
+    for (int i = 0; i < h->n_tensors; ++i) {
+        const TensorRef &t = h->tref[i];
+        Unit &u = h->units[t.unit];
+        host_adam(h->params[i], u.h_grad + t.off, h->adam_m[t.unit] + t.off, h->adam_v[t.unit] + t.off,
+                  u.h_shadow + t.off, t.numel, lr, beta1, beta2, eps, wd, step);
+    }
+    h->resident[0] = h->resident[1] = -1;
+    h->stats.adam_ms = now_ms() - t0;
+    return MT_OK;
+}
+
+mt_status mt_get_tensor(mt_handle *h, int32_t idx, int32_t kind, float **p, size_t *numel) {
+    if (!h || !p) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (idx < 0 || idx >= h->n_tensors) return fail(MT_ERR_INVALID_ARG, "tensor index out of range");
+    const TensorRef &t = h->tref[idx];
+    switch (kind) {
+        case MT_KIND_GRAD: *p = h->units[t.unit].h_grad + t.off; break;
+        case MT_KIND_ADAM_M: *p = h->adam_m[t.unit] + t.off; break;
+        case MT_KIND_ADAM_V: *p = h->adam_v[t.unit] + t.off; break;
+        default: return fail(MT_ERR_INVALID_ARG, "unknown tensor kind %d", kind);
+    }
+    if (numel) *numel = t.numel;
+    return MT_OK;
+}
+
+mt_status mt_get_stats(mt_handle *h, mt_stats *out) {
+    if (!h || !out) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    *out = h->stats;
+    return MT_OK;
+}
+
+mt_status mt_destroy(mt_handle *h) {
+    free_handle(h);
+    return MT_OK;
+}
+
+mt_status mt_link_probe(int32_t device_id, size_t bytes, int32_t reps, double *h2d_gbs, double *d2h_gbs,
+                        double *bidir_gbs) {
+    if (bytes == 0 || reps <= 0) return fail(MT_ERR_INVALID_ARG, "bytes and reps must be positive");
+    HIPCHK(hipSetDevice(device_id));
+    void *h1 = nullptr, *h2 = nullptr, *d1 = nullptr, *d2 = nullptr;
+    hipStream_t s1 = nullptr, s2 = nullptr;
+    mt_status rc = MT_OK;
+    auto cleanup = [&]() {
+        if (h1) (void)hipHostFree(h1);
+        if (h2) (void)hipHostFree(h2);
+        if (d1) (void)hipFree(d1);
+        if (d2) (void)hipFree(d2);
+        if (s1) (void)hipStreamDestroy(s1);
+        if (s2) (void)hipStreamDestroy(s2);
+    };
+#define PCHK(expr)                                                                       \
+    do {                                                                                 \
+        hipError_t e_ = (expr);                                                          \
+        if (e_ != hipSuccess) {                                                          \
+            rc = fail(MT_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));        \
+            (void)hipGetLastError();                                                     \
+            cleanup();                                                                   \
+            return rc;                                                                   \
+        }                                                                                \
+    } while (0)
+    PCHK(hipHostMalloc(&h1, bytes, hipHostMallocDefault));
+    PCHK(hipHostMalloc(&h2, bytes, hipHostMallocDefault));
+    PCHK(hipMalloc(&d1, bytes));
+    PCHK(hipMalloc(&d2, bytes));
+    host_zero(h1, bytes);
+    host_zero(h2, bytes);
+    PCHK(hipStreamCreateWithFlags(&s1, hipStreamNonBlocking));
+    PCHK(hipStreamCreateWithFlags(&s2, hipStreamNonBlocking));
+    PCHK(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, s1));
+    PCHK(hipMemcpyAsync(h2, d2, bytes, hipMemcpyDeviceToHost, s2));
+    PCHK(hipStreamSynchronize(s1));
+    PCHK(hipStreamSynchronize(s2));
+    double t0 = now_ms();
+    for (int i = 0; i < reps; ++i) PCHK(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, s1));
+    PCHK(hipStreamSynchronize(s1));
+    double t1 = now_ms();
+    if (h2d_gbs) *h2d_gbs = (double)bytes * reps / ((t1 - t0) * 1e6);
+    t0 = now_ms();
+    for (int i = 0; i < reps; ++i) PCHK(hipMemcpyAsync(h2, d2, bytes, hipMemcpyDeviceToHost, s2));
+    PCHK(hipStreamSynchronize(s2));
+    t1 = now_ms();
+    if (d2h_gbs) *d2h_gbs = (double)bytes * reps / ((t1 - t0) * 1e6);
+    t0 = now_ms();
+    for (int i = 0; i < reps; ++i) {
+        PCHK(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, s1));
+        PCHK(hipMemcpyAsync(h2, d2, bytes, hipMemcpyDeviceToHost, s2));
+    }
+    PCHK(hipStreamSynchronize(s1));
+    PCHK(hipStreamSynchronize(s2));
+    t1 = now_ms();
+    if (bidir_gbs) *bidir_gbs = 2.0 * (double)bytes * reps / ((t1 - t0) * 1e6);
+#undef PCHK
+    cleanup();
+    return MT_OK;
+}
+
+}  // extern "C"

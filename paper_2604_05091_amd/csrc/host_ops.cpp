@@ -1,0 +1,126 @@
+// Host-side arithmetic: Adam (Algorithm 1, "AdamUpdate" on the CPU; Section 3.1 optimizer
+// update phase), bf16 conversion of the weights that StreamIn transfers, rotary tables.
+#include "host_ops.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#include <thread>
+#include <vector>
+
+namespace mt {
+
+int host_threads() {
+    static int n = [] {
+        int v = 0;
+        if (const char *e = getenv("MT_HOST_THREADS")) v = atoi(e);
+        if (v <= 0) v = (int)std::thread::hardware_concurrency();
+        if (v <= 0) v = 1;
+        if (v > 128) v = 128;
+        return v;
+    }();
+    return n;
+}
+
+void parallel_for(size_t n, size_t min_chunk, const std::function<void(size_t, size_t)> &fn) {
+    if (n == 0) return;
+    size_t nt = (size_t)host_threads();
+    if (min_chunk == 0) min_chunk = 1;
+    const size_t max_by_size = (n + min_chunk - 1) / min_chunk;
+    if (nt > max_by_size) nt = max_by_size;
+    if (nt <= 1) {
+        fn(0, n);
+        return;
+    }
+    // chunk boundaries on multiples of 64 elements so vector loops stay aligned
+    const size_t per = ((n + nt - 1) / nt + 63) & ~(size_t)63;
+    std::vector<std::thread> th;
+    th.reserve(nt);
+    for (size_t t = 1; t < nt; ++t) {
+        const size_t b = t * per, e = b + per < n ? b + per : n;
+        if (b >= n) break;
+        th.emplace_back([&fn, b, e] { fn(b, e); });
+    }
+    fn(0, per < n ? per : n);
+    for (auto &t : th) t.join();
+}
+
+namespace {
+
+inline uint16_t bf16_rne(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__attribute__((target_clones("avx512f", "avx2", "default"))) void cvt_chunk(uint16_t *out, const float *in,
+                                                                           size_t n) {
+    for (size_t i = 0; i < n; ++i) out[i] = bf16_rne(in[i]);
+}
+
+__attribute__((target_clones("avx512f", "avx2", "default"))) void adam_chunk(float *p, const float *g, float *m,
+                                                                            float *v, uint16_t *shadow, size_t n,
+                                                                            float decay, float lr, float b1, float b2,
+                                                                            float eps, float inv_c1, float inv_c2) {
+    const float ob1 = 1.0f - b1, ob2 = 1.0f - b2;
+    if (shadow) {
+        for (size_t i = 0; i < n; ++i) {
+            const float gi = g[i];
+            const float mi = b1 * m[i] + ob1 * gi;
+            const float vi = b2 * v[i] + ob2 * gi * gi;
+            const float pi = p[i] * decay - lr * (mi * inv_c1) / (sqrtf(vi * inv_c2) + eps);
+            m[i] = mi;
+            v[i] = vi;
+            p[i] = pi;
+            shadow[i] = bf16_rne(pi);
+        }
+    } else {
+        for (size_t i = 0; i < n; ++i) {
+            const float gi = g[i];
+            const float mi = b1 * m[i] + ob1 * gi;
+            const float vi = b2 * v[i] + ob2 * gi * gi;
+            const float pi = p[i] * decay - lr * (mi * inv_c1) / (sqrtf(vi * inv_c2) + eps);
+            m[i] = mi;
+            v[i] = vi;
+            p[i] = pi;
+        }
+    }
+}
+
+}  // namespace
+
+void host_f32_to_bf16(uint16_t *out, const float *in, size_t n) {
+    parallel_for(n, 1 << 16, [&](size_t b, size_t e) { cvt_chunk(out + b, in + b, e - b); });
+}
+
+void host_adam(float *p, const float *g, float *m, float *v, uint16_t *shadow, size_t n, float lr, float beta1,
+               float beta2, float eps, float wd, int64_t step) {
+    const double c1 = 1.0 - pow((double)beta1, (double)step), c2 = 1.0 - pow((double)beta2, (double)step);
+    const float inv_c1 = (float)(1.0 / c1), inv_c2 = (float)(1.0 / c2);
+    const float decay = (float)(1.0 - (double)lr * (double)wd);
+    parallel_for(n, 1 << 16, [&](size_t b, size_t e) {
+        adam_chunk(p + b, g + b, m + b, v + b, shadow ? shadow + b : nullptr, e - b, decay, lr, beta1, beta2, eps,
+                   inv_c1, inv_c2);
+    });
+}
+
+void host_zero(void *p, size_t bytes) {
+    char *c = (char *)p;
+    parallel_for(bytes, 1 << 22, [&](size_t b, size_t e) { memset(c + b, 0, e - b); });
+}
+
+void rope_table(float *cs, float *sn, int T, int hd, double base) {
+    const int half = hd / 2;
+    parallel_for((size_t)T, 256, [&](size_t b, size_t e) {
+        for (size_t t = b; t < e; ++t)
+            for (int j = 0; j < half; ++j) {
+                const double ang = (double)t * pow(base, -2.0 * (double)j / (double)hd);
+                cs[t * half + j] = (float)cos(ang);
+                sn[t * half + j] = (float)sin(ang);
+            }
+    });
+}
+
+}  // namespace mt

@@ -1,0 +1,272 @@
+"""GPU parity of every kernel against the CPU oracle, element by element, through the C ABI.
+
+Inputs are rounded to bf16 first and the oracle (fp64) is fed exactly those values, so the
+differences measured here are the kernels' own arithmetic: fp32 accumulation order and one
+bf16 rounding of each stored output (relative 2^-9 per element)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_05091_amd as mt
+from gpu_util import bf16_round, cosine, dev_bf16, dev_f32, dev_i32, host, ok, rel_l2
+
+pytestmark = pytest.mark.gpu
+L = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    global L
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    L = mt.lib()
+    yield
+
+
+BF16_TOL = 6e-3   # rel. L2 of a tensor whose elements carry one bf16 rounding (2^-9 = 2e-3 each) plus fp32 sums
+
+
+# ----------------------------------------------------------------------------- GEMM
+@pytest.mark.parametrize("M,N,K", [(256, 1376, 256), (256, 256, 688), (300, 200, 136), (72, 1024, 264),
+                                   (4000, 3100, 200), (4096, 3072, 128)])
+def test_gemm_nt_bf16_out(orc64, M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    a, b = bf16_round(rng.standard_normal((M, K))), bf16_round(rng.standard_normal((N, K)))
+    ref = orc64.linear_fwd(a, b)
+    A, B = dev_bf16(a), dev_bf16(b)
+    C = torch.full((M, N), 7.0, dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_gemm_nt(A.data_ptr(), K, B.data_ptr(), K, C.data_ptr(), N, None, 0, M, N, K, 0, 0, None))
+    got = host(C)
+    assert rel_l2(got, ref) < BF16_TOL
+    assert np.max(np.abs(got - ref)) <= 2.0 ** -8 * np.max(np.abs(ref)) + 1e-3 * np.sqrt(K)
+
+
+def test_gemm_nt_residual_strides_fp32_accumulate(orc64):
+    rng = np.random.default_rng(1)
+    M, N, K, lda, ldb, ldc = 328, 200, 88, 96, 104, 208
+    a_full, b_full = bf16_round(rng.standard_normal((M, lda))), bf16_round(rng.standard_normal((N, ldb)))
+    r = bf16_round(rng.standard_normal((M, N)))
+    ref = orc64.linear_fwd(a_full[:, :K], b_full[:, :K])
+    A, B, R = dev_bf16(a_full), dev_bf16(b_full), dev_bf16(r)
+    C = torch.zeros((M, ldc), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_gemm_nt(A.data_ptr(), lda, B.data_ptr(), ldb, C.data_ptr(), ldc, R.data_ptr(), N, M, N, K, 0, 0, None))
+    got = host(C)
+    assert rel_l2(got[:, :N], ref + r) < BF16_TOL
+    assert np.all(got[:, N:] == 0)              # nothing written outside the N columns
+    # fp32 output, then accumulate a second product on top
+    C32 = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    ok(L.mt_k_gemm_nt(A.data_ptr(), lda, B.data_ptr(), ldb, C32.data_ptr(), N, None, 0, M, N, K, 1, 0, None))
+    assert rel_l2(host(C32), ref) < 2e-6
+    ok(L.mt_k_gemm_nt(A.data_ptr(), lda, B.data_ptr(), ldb, C32.data_ptr(), N, None, 0, M, N, K, 1, 1, None))
+    assert rel_l2(host(C32), 2 * ref) < 2e-6
+
+
+def test_gemm_weight_gradient_form_long_reduction(orc64):
+    """dW[out,in] = sum_t dy[t,out] x[t,in]: both operands transposed first, fp32 result."""
+    rng = np.random.default_rng(2)
+    n, out, inn = 2056, 136, 264
+    dy, x = bf16_round(rng.standard_normal((n, out))), bf16_round(rng.standard_normal((n, inn)))
+    ref = orc64.linear_bwd_w(dy, x)
+    DY, X = dev_bf16(dy), dev_bf16(x)
+    DYT = torch.empty((out, n), dtype=torch.bfloat16, device="cuda")
+    XT = torch.empty((inn, n), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_transpose(DY.data_ptr(), DYT.data_ptr(), n, out, out, n, 1, 1, 0, 0, 0, 0, None))
+    ok(L.mt_k_transpose(X.data_ptr(), XT.data_ptr(), n, inn, inn, n, 1, 1, 0, 0, 0, 0, None))
+    assert np.array_equal(host(DYT), dy.T) and np.array_equal(host(XT), x.T)
+    DW = torch.empty((out, inn), dtype=torch.float32, device="cuda")
+    ok(L.mt_k_gemm_nt(DYT.data_ptr(), n, XT.data_ptr(), n, DW.data_ptr(), inn, None, 0, out, inn, n, 1, 0, None))
+    assert rel_l2(host(DW), ref) < 5e-6
+
+
+def test_gemm_rejects_bad_arguments():
+    A = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    C = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    assert L.mt_k_gemm_nt(A.data_ptr(), 64, A.data_ptr(), 64, C.data_ptr(), 64, None, 0, 64, 64, 60, 0, 0, None) == -1
+    assert L.mt_k_gemm_nt(A.data_ptr(), 60, A.data_ptr(), 64, C.data_ptr(), 64, None, 0, 64, 64, 56, 0, 0, None) == -1
+    assert L.mt_k_gemm_nt(A.data_ptr() + 2, 64, A.data_ptr(), 64, C.data_ptr(), 64, None, 0, 32, 32, 32, 0, 0, None) == -1
+    assert L.mt_k_gemm_nt(None, 64, A.data_ptr(), 64, C.data_ptr(), 64, None, 0, 64, 64, 64, 0, 0, None) == -1
+    assert L.mt_k_gemm_nt(A.data_ptr(), 64, A.data_ptr(), 64, C.data_ptr(), 64, None, 0, 0, 64, 64, 0, 0, None) == -1
+
+
+def test_batched_head_transpose():
+    rng = np.random.default_rng(3)
+    B, T, H, hd, ld = 2, 72, 3, 64, 3 * 64 + 128
+    x = bf16_round(rng.standard_normal((B * T, ld)))
+    X = dev_bf16(x)
+    out = torch.zeros((B, H, hd, T), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_transpose(X.data_ptr() + 2 * 128, out.data_ptr(), T, hd, ld, T, B, H, T * ld, hd, H * hd * T, hd * T, None))
+    ref = x[:, 128:128 + H * hd].reshape(B, T, H, hd).transpose(0, 2, 3, 1)
+    assert np.array_equal(host(out), ref)
+
+
+# ----------------------------------------------------------------------------- RMSNorm
+@pytest.mark.parametrize("n,d", [(37, 256), (130, 2048), (64, 4096), (19, 5120)])
+def test_rmsnorm_forward_backward(orc64, n, d):
+    rng = np.random.default_rng(n + d)
+    x, g = bf16_round(rng.standard_normal((n, d)) * 1.7), bf16_round(1 + 0.3 * rng.standard_normal(d))
+    dy, dres = bf16_round(rng.standard_normal((n, d))), bf16_round(rng.standard_normal((n, d)))
+    X, G, DY, DR = dev_bf16(x), dev_bf16(g), dev_bf16(dy), dev_bf16(dres)
+    Y = torch.empty_like(X)
+    ok(L.mt_k_rmsnorm_fwd(Y.data_ptr(), X.data_ptr(), G.data_ptr(), n, d, 1e-5, None))
+    assert rel_l2(host(Y), orc64.rmsnorm_fwd(x, g, 1e-5)) < BF16_TOL
+    dx_ref, dg_ref = orc64.rmsnorm_bwd(dy, x, g, 1e-5)
+    ws = torch.empty(L.mt_k_rmsnorm_bwd_ws_bytes(d) // 4, dtype=torch.float32, device="cuda")
+    DX = torch.empty_like(X)
+    DG = torch.empty(d, dtype=torch.float32, device="cuda")
+    ok(L.mt_k_rmsnorm_bwd(DX.data_ptr(), DG.data_ptr(), DY.data_ptr(), X.data_ptr(), G.data_ptr(), DR.data_ptr(),
+                          ws.data_ptr(), n, d, 1e-5, None))
+    assert rel_l2(host(DX), dx_ref + dres) < BF16_TOL
+    assert rel_l2(host(DG), dg_ref) < 1e-5
+    ok(L.mt_k_rmsnorm_bwd(DX.data_ptr(), DG.data_ptr(), DY.data_ptr(), X.data_ptr(), G.data_ptr(), None,
+                          ws.data_ptr(), n, d, 1e-5, None))
+    assert rel_l2(host(DX), dx_ref) < BF16_TOL
+
+
+def test_rmsnorm_backward_many_rows_gain_reduction(orc64):
+    rng = np.random.default_rng(5)
+    n, d = 5000, 256      # more rows than waves in the grid: exercises the strided row loop
+    x, g, dy = bf16_round(rng.standard_normal((n, d))), bf16_round(np.ones(d)), bf16_round(rng.standard_normal((n, d)))
+    dx_ref, dg_ref = orc64.rmsnorm_bwd(dy, x, g, 1e-5)
+    X, G, DY = dev_bf16(x), dev_bf16(g), dev_bf16(dy)
+    ws = torch.empty(L.mt_k_rmsnorm_bwd_ws_bytes(d) // 4, dtype=torch.float32, device="cuda")
+    DX, DG = torch.empty_like(X), torch.empty(d, dtype=torch.float32, device="cuda")
+    ok(L.mt_k_rmsnorm_bwd(DX.data_ptr(), DG.data_ptr(), DY.data_ptr(), X.data_ptr(), G.data_ptr(), None,
+                          ws.data_ptr(), n, d, 1e-5, None))
+    assert rel_l2(host(DG), dg_ref) < 1e-5 and rel_l2(host(DX), dx_ref) < BF16_TOL
+
+
+# ----------------------------------------------------------------------------- RoPE
+@pytest.mark.parametrize("hd,base", [(64, 10000.0), (128, 1.0e6)])
+def test_rope_forward_and_inverse(orc64, hd, base):
+    rng = np.random.default_rng(hd)
+    B, T, H, extra = 2, 40, 3, 2 * hd
+    ld = H * hd + extra
+    x = bf16_round(rng.standard_normal((B * T, ld)))
+    cs, sn = np.empty((T, hd // 2), np.float32), np.empty((T, hd // 2), np.float32)
+    assert L.mt_k_rope_table(cs.ctypes.data, sn.ctypes.data, T, hd, base) == 0
+    X, CS, SN = dev_bf16(x), dev_f32(cs), dev_f32(sn)
+    ok(L.mt_k_rope(X.data_ptr(), ld, B * T, T, H, hd, CS.data_ptr(), SN.data_ptr(), +1, None))
+    got = host(X)
+    ref = orc64.rope(x[:, :H * hd], B, T, H, hd, base, +1)
+    assert rel_l2(got[:, :H * hd], ref) < BF16_TOL
+    assert np.array_equal(got[:, H * hd:], x[:, H * hd:])       # columns after the heads untouched
+    ok(L.mt_k_rope(X.data_ptr(), ld, B * T, T, H, hd, CS.data_ptr(), SN.data_ptr(), -1, None))
+    assert rel_l2(host(X)[:, :H * hd], x[:, :H * hd]) < 2 * BF16_TOL
+
+
+# ----------------------------------------------------------------------------- SwiGLU
+def test_swiglu_forward_backward(orc64):
+    rng = np.random.default_rng(6)
+    n, F = 77, 688
+    gu, ds = bf16_round(rng.standard_normal((n, 2 * F)) * 2), bf16_round(rng.standard_normal((n, F)))
+    GU, DS = dev_bf16(gu), dev_bf16(ds)
+    S = torch.empty((n, F), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_swiglu_fwd(S.data_ptr(), GU.data_ptr(), n, F, None))
+    assert rel_l2(host(S), orc64.swiglu_fwd(gu[:, :F], gu[:, F:])) < BF16_TOL
+    DGU = torch.empty_like(GU)
+    ok(L.mt_k_swiglu_bwd(DGU.data_ptr(), DS.data_ptr(), GU.data_ptr(), n, F, None))
+    dg, du = orc64.swiglu_bwd(ds, gu[:, :F], gu[:, F:])
+    got = host(DGU)
+    assert rel_l2(got[:, :F], dg) < BF16_TOL and rel_l2(got[:, F:], du) < BF16_TOL
+
+
+# ----------------------------------------------------------------------------- embedding
+def test_embedding_gather_and_scatter(orc64):
+    rng = np.random.default_rng(7)
+    V, d, n = 50, 264, 333
+    table = bf16_round(rng.standard_normal((V, d)))
+    tok = rng.integers(0, V - 5, n).astype(np.int32)      # the last rows get no token at all
+    TB, TK = dev_bf16(table), dev_i32(tok)
+    H = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_embed_gather(H.data_ptr(), TB.data_ptr(), TK.data_ptr(), n, d, None))
+    assert np.array_equal(host(H), orc64.embed_fwd(table, tok))
+    dh = bf16_round(rng.standard_normal((n, d)))
+    order = np.argsort(tok, kind="stable").astype(np.int32)
+    row_start = np.zeros(V + 1, np.int32)
+    row_start[1:] = np.cumsum(np.bincount(tok, minlength=V))
+    DT = torch.full((V, d), 3.0, dtype=torch.float32, device="cuda")
+    ok(L.mt_k_embed_scatter(DT.data_ptr(), dev_bf16(dh).data_ptr(), dev_i32(row_start).data_ptr(),
+                            dev_i32(order).data_ptr(), V, d, None))
+    got = host(DT)
+    assert rel_l2(got, orc64.embed_bwd(dh, tok, V)) < 1e-6
+    assert np.all(got[V - 5:] == 0)
+
+
+# ----------------------------------------------------------------------------- cross-entropy
+@pytest.mark.parametrize("n,V", [(9, 1024), (5, 32000), (7, 520)])
+def test_cross_entropy(orc64, n, V):
+    rng = np.random.default_rng(V)
+    z = (rng.standard_normal((n, V)) * 3).astype(np.float32)
+    y = rng.integers(0, V, n).astype(np.int32)
+    y[1] = -1                                            # an ignored position
+    nv = int((y >= 0).sum())
+    loss_ref, dl_ref = orc64.cross_entropy(z, y)
+    Z, Y = dev_f32(z), dev_i32(y)
+    LR = torch.empty(n, dtype=torch.float32, device="cuda")
+    DZ = torch.empty((n, V), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_cross_entropy(LR.data_ptr(), DZ.data_ptr(), Z.data_ptr(), Y.data_ptr(), n, V, 1.0 / nv, None))
+    out = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ok(L.mt_k_reduce_sum(out.data_ptr(), LR.data_ptr(), n, 1.0 / nv, 0, None))
+    assert abs(host(out)[0] - loss_ref) < 1e-5 * abs(loss_ref)
+    got = host(DZ)
+    assert rel_l2(got, dl_ref) < BF16_TOL
+    assert np.all(got[1] == 0)
+
+
+# ----------------------------------------------------------------------------- attention
+def _attention_case(orc64, B, T, Hq, Hkv, hd, seed):
+    rng = np.random.default_rng(seed)
+    nq, nkv = Hq * hd, Hkv * hd
+    ld = nq + 2 * nkv
+    qkv = bf16_round(rng.standard_normal((B * T, ld)))
+    q, k, v = qkv[:, :nq], qkv[:, nq:nq + nkv], qkv[:, nq + nkv:]
+    scale = 1.0 / np.sqrt(hd)
+    QKV = dev_bf16(qkv)
+    pq, pk, pv = QKV.data_ptr(), QKV.data_ptr() + 2 * nq, QKV.data_ptr() + 2 * (nq + nkv)
+    VT = torch.empty((B, Hkv, hd, T), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_transpose(pv, VT.data_ptr(), T, hd, ld, T, B, Hkv, T * ld, hd, Hkv * hd * T, hd * T, None))
+    O = torch.zeros((B * T, nq), dtype=torch.bfloat16, device="cuda")
+    LSE = torch.zeros((B, Hq, T), dtype=torch.float32, device="cuda")
+    ok(L.mt_k_flash_fwd(O.data_ptr(), nq, LSE.data_ptr(), pq, ld, pk, ld, VT.data_ptr(), B, T, Hq, Hkv, hd, scale, None))
+    a_ref = orc64.attention_fwd(q, k, v, B, T, Hq, Hkv, hd)
+    assert rel_l2(host(O), a_ref) < BF16_TOL
+    # log-sum-exp of the first and last row of head 0: lse_0 = s_00, lse_last from the definition
+    lse = host(LSE)
+    s00 = float(q[0, :hd].astype(np.float64) @ k[0, :hd].astype(np.float64)) * scale
+    assert abs(lse[0, 0, 0] - s00) < 1e-3 * max(1, abs(s00))
+    # backward
+    dout = bf16_round(rng.standard_normal((B * T, nq)))
+    dq_ref, dk_ref, dv_ref = orc64.attention_bwd(dout, q, k, v, B, T, Hq, Hkv, hd)
+    DO = dev_bf16(dout)
+    QT = torch.empty((B, Hq, hd, T), dtype=torch.bfloat16, device="cuda")
+    KT = torch.empty((B, Hkv, hd, T), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_transpose(pq, QT.data_ptr(), T, hd, ld, T, B, Hq, T * ld, hd, Hq * hd * T, hd * T, None))
+    ok(L.mt_k_transpose(pk, KT.data_ptr(), T, hd, ld, T, B, Hkv, T * ld, hd, Hkv * hd * T, hd * T, None))
+    DOT = torch.empty((B, Hq, hd, T), dtype=torch.bfloat16, device="cuda")
+    DELTA = torch.empty((B, Hq, T), dtype=torch.float32, device="cuda")
+    DQKV = torch.zeros((B * T, ld), dtype=torch.bfloat16, device="cuda")
+    pdq, pdk, pdv = DQKV.data_ptr(), DQKV.data_ptr() + 2 * nq, DQKV.data_ptr() + 2 * (nq + nkv)
+    ok(L.mt_k_flash_bwd(pdq, ld, pdk, ld, pdv, ld, DO.data_ptr(), nq, pq, ld, pk, ld, pv, ld, O.data_ptr(), nq,
+                        LSE.data_ptr(), QT.data_ptr(), KT.data_ptr(), DOT.data_ptr(), DELTA.data_ptr(), B, T, Hq, Hkv,
+                        hd, scale, None))
+    got = host(DQKV)
+    # the backward reads O and P in bf16, so its error is a few bf16 roundings deep
+    assert rel_l2(got[:, :nq], dq_ref) < 2e-2 and cosine(got[:, :nq], dq_ref) > 0.9995
+    assert rel_l2(got[:, nq:nq + nkv], dk_ref) < 2e-2 and cosine(got[:, nq:nq + nkv], dk_ref) > 0.9995
+    assert rel_l2(got[:, nq + nkv:], dv_ref) < 1e-2 and cosine(got[:, nq + nkv:], dv_ref) > 0.9995
+
+
+@pytest.mark.parametrize("B,T,Hq,Hkv,hd", [(2, 128, 4, 4, 64), (1, 200, 4, 2, 64), (2, 72, 2, 2, 128),
+                                           (1, 392, 5, 1, 128), (1, 8, 2, 1, 64)])
+def test_flash_attention_forward_backward(orc64, B, T, Hq, Hkv, hd):
+    _attention_case(orc64, B, T, Hq, Hkv, hd, seed=T + hd)
+
+
+def test_flash_attention_rejects_bad_shapes():
+    x = torch.zeros(4096, dtype=torch.bfloat16, device="cuda")
+    f = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    p = x.data_ptr()
+    assert L.mt_k_flash_fwd(p, 64, f.data_ptr(), p, 64, p, 64, p, 1, 12, 1, 1, 64, 0.125, None) == -1   # T % 8
+    assert L.mt_k_flash_fwd(p, 96, f.data_ptr(), p, 96, p, 96, p, 1, 8, 1, 1, 96, 0.1, None) == -1      # head_dim
+    assert L.mt_k_flash_fwd(p, 64, f.data_ptr(), p, 64, p, 64, p, 1, 8, 3, 2, 64, 0.125, None) == -1    # Hq % Hkv
