@@ -186,8 +186,8 @@ def test_embedding_gather_and_scatter(orc64):
     row_start = np.zeros(V + 1, np.int32)
     row_start[1:] = np.cumsum(np.bincount(tok, minlength=V))
     DT = torch.full((V, d), 3.0, dtype=torch.float32, device="cuda")
-    ok(L.mt_k_embed_scatter(DT.data_ptr(), dev_bf16(dh).data_ptr(), dev_i32(row_start).data_ptr(),
-                            dev_i32(order).data_ptr(), V, d, None))
+    DH, RS, ORD = dev_bf16(dh), dev_i32(row_start), dev_i32(order)      # keep the device buffers alive
+    ok(L.mt_k_embed_scatter(DT.data_ptr(), DH.data_ptr(), RS.data_ptr(), ORD.data_ptr(), V, d, None))
     got = host(DT)
     assert rel_l2(got, orc64.embed_bwd(dh, tok, V)) < 1e-6
     assert np.all(got[V - 5:] == 0)
