@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the streamed training step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config auto|tiny|1.3B|7B|14B|7B-128k]
+
+A "step" is one pass of the whole hot path over one synthetic batch: mt_train_step
+(weight streaming, forward, loss, per-block recompute + backward, gradient offload)
+followed by mt_adam_step (host Adam + refresh of the streamed bf16 copy).  Inputs are
+resident in host memory, as the method prescribes, when the timed region starts.
+
+Prints ONE JSON line.  `value` is model TFLOP/s by the paper's accounting (6ND + 12LHT^2,
+recompute not counted).  `roofline` is for the dominant kernel class (the MFMA GEMM unless
+attention dominates), measured live with HIP events on the compute stream inside the timed
+region.  `cpu_baseline` is the CPU oracle (fp32 build) timed on a bounded sample of the same
+layer shapes on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from dataclasses import replace
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+SAMPLE_TOKENS = {"tiny": 256, "1.3B": 256, "7B": 128, "14B": 96, "7B-128k": 128}
+
+
+def mem_available_gb() -> float:
+    try:
+        for line in open("/proc/meminfo"):
+            if line.startswith("MemAvailable:"):
+                return int(line.split()[1]) / 1e6
+    except OSError:
+        pass
+    return 0.0
+
+
+def host_bytes_needed(n_params: int) -> float:
+    # caller fp32 master 4 + grads 4 + m 4 + v 4 + bf16 copy 2 bytes per parameter
+    return 18.0 * n_params
+
+
+def pick_config(name: str):
+    import mt_inputs
+    if name != "auto":
+        return name
+    # the metric is quoted at 7B and 14B; 7B is the default when the host can hold its state
+    need = host_bytes_needed(mt_inputs.n_params(mt_inputs.CONFIGS["7B"][0])) / 1e9
+    return "7B" if mem_available_gb() > need + 24 else "1.3B"
+
+
+def cpu_baseline(name: str) -> dict:
+    """The oracle as it stands (fp32 build) on a bounded sample: same layer shapes, one block,
+    one short sequence; reported in the metric's unit (model TFLOP/s by the same formula)."""
+    import mt_inputs
+    import oracle
+    import paper_2604_05091_amd as mt
+    oracle.build()
+    shape, _, T = mt_inputs.CONFIGS[name]
+    Ls = 2 if name == "tiny" else 1
+    Ts = min(T, SAMPLE_TOKENS[name])
+    Bs = 2 if name == "tiny" else 1
+    s1 = replace(shape, n_layers=Ls)
+    params = mt_inputs.make_params(s1, seed=0)
+    tok, lab = mt_inputs.make_batch(s1.vocab, Bs, Ts, seed=1)
+    orc = oracle.Oracle("f32")
+    t0 = time.time()
+    loss, grads = orc.train_step(s1, params, tok, lab, mode=1)
+    for p, g in zip(params, grads):
+        m, v = p * 0, p * 0
+        orc.adam(p, g, m, v, 1e-4, 0.9, 0.999, 1e-8, 0.0, 1)
+    dt = time.time() - t0
+    flops = mt.model_flops(mt_inputs.n_params(s1), Ls, s1.hidden, Bs, Ts)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())),
+            "kind": "oracle",
+            "sample": f"{name} layer shapes, {Ls} block(s), batch {Bs} x seq {Ts}, fp32 oracle step + Adam, "
+                      f"{dt:.2f} s, loss {loss:.4f}"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="auto")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--flags", type=int, default=0, help="extra MT_FLAG_* bits (diagnostics)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import mt_inputs
+    import paper_2604_05091_amd as mt
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
+        return 3
+    mt.lib()  # fail loudly if the extension is not built
+
+    name = pick_config(args.config)
+    shape, B, T = mt_inputs.CONFIGS[name]
+    n_params = mt_inputs.n_params(shape)
+    t_setup = time.time()
+    params = mt_inputs.make_params(shape, seed=0)
+    tok, lab = mt_inputs.make_batch(shape.vocab, B, T, seed=1)
+    cfg = mt.ModelCfg.make(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
+                           shape.vocab, B, T, rope_base=shape.rope_base, rms_eps=shape.rms_eps,
+                           flags=mt.FLAG_KERNEL_TIMING | args.flags)
+    link = mt.link_probe(256 << 20, 4)     # copy-bandwidth probe of this session: the host-link roofline
+    h = mt.TrainHandle(cfg, params)
+    t_setup = time.time() - t_setup
+    print(f"[bench] {name}: {n_params/1e9:.3f} B params, batch {B} x seq {T}, setup {t_setup:.1f} s, "
+          f"link probe {link}", file=sys.stderr, flush=True)
+
+    lr, step_no = 1e-4, 0
+    losses = []
+    for _ in range(args.warmup):
+        step_no += 1
+        losses.append(h.train_step(tok, lab))
+        h.adam_step(lr, step=step_no)
+        print(f"[bench] warmup step {step_no} loss {losses[-1]:.4f}", file=sys.stderr, flush=True)
+    torch.cuda.synchronize()
+    per_step = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_no += 1
+        losses.append(h.train_step(tok, lab))
+        st = h.stats()
+        h.adam_step(lr, step=step_no)
+        st["adam_ms"] = h.stats()["adam_ms"]
+        per_step.append(st)
+        print(f"[bench] step {step_no} loss {losses[-1]:.4f} train {st['step_ms']:.0f} ms adam {st['adam_ms']:.0f} ms",
+              file=sys.stderr, flush=True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    flops = mt.model_flops(n_params, shape.n_layers, shape.hidden, B, T)
+    mean = lambda k: float(np.mean([s[k] for s in per_step]))
+    cls_ms = np.sum([s["class_ms"] for s in per_step], axis=0)
+    cls_fl = np.sum([s["class_flops"] for s in per_step], axis=0)
+    cls_n = np.sum([s["class_launches"] for s in per_step], axis=0)
+    names = ["gemm_nt_kernel (bf16 MFMA GEMM)", "flash_fwd_kernel", "flash_bwd_dkdv_kernel + flash_bwd_dq_kernel"]
+    dom = int(np.argmax(cls_ms))
+    achieved = cls_fl[dom] / (cls_ms[dom] * 1e-3) / 1e12 if cls_ms[dom] > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(name)
+        except Exception:
+            traffic = None
+    roofline = {"bound": "mfma", "kernel": names[dom], "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+                "launches_per_step": int(cls_n[dom] / args.steps),
+                "avg_launch_ms": float(cls_ms[dom] / max(cls_n[dom], 1)),
+                "share_of_compute_busy": float(cls_ms[dom] / args.steps / max(mean("compute_busy_ms"), 1e-9)),
+                "classes": {names[i]: {"ms_per_step": float(cls_ms[i] / args.steps),
+                                       "tflops": float(cls_fl[i] / max(cls_ms[i] * 1e-3, 1e-12) / 1e12)}
+                            for i in range(3)}}
+    h2d_busy, d2h_busy = mean("h2d_busy_ms"), mean("d2h_busy_ms")
+    link_stats = {
+        "probe_h2d_gbs": link["h2d_gbs"], "probe_d2h_gbs": link["d2h_gbs"], "probe_bidir_gbs": link["bidir_gbs"],
+        "h2d_gb_per_step": mean("h2d_bytes") / 1e9, "d2h_gb_per_step": mean("d2h_bytes") / 1e9,
+        "h2d_achieved_gbs": mean("h2d_bytes") / 1e6 / max(h2d_busy, 1e-9),
+        "d2h_achieved_gbs": mean("d2h_bytes") / 1e6 / max(d2h_busy, 1e-9),
+        "h2d_hidden_frac": mean("h2d_hidden_ms") / max(h2d_busy, 1e-9),
+        "d2h_hidden_frac": mean("d2h_hidden_ms") / max(d2h_busy, 1e-9),
+        "link_hidden_frac": (mean("h2d_hidden_ms") + mean("d2h_hidden_ms")) / max(h2d_busy + d2h_busy, 1e-9),
+    }
+    out = {
+        "metric": "sustained model TFLOPS per step (6ND + 12LHT^2; train step + host Adam)",
+        "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{name}: {shape.n_layers} layers, hidden {shape.hidden}, {shape.n_q_heads}/"
+                               f"{shape.n_kv_heads} heads x {shape.head_dim}, ffn {shape.ffn}, vocab {shape.vocab}, "
+                               f"batch {B} x seq {T}", "n_params": n_params, "tokens_per_step": B * T,
+                   "host_state": "fp32 master/grad/Adam on host, bf16 streamed weights"},
+        "roofline": roofline,
+        "train_step_ms": mean("step_ms"), "adam_step_ms": mean("adam_ms"),
+        "train_only_tflops": flops / (mean("step_ms") * 1e-3) / 1e12,
+        "compute_busy_ms": mean("compute_busy_ms"),
+        "link": link_stats,
+        "device_arena_gb": per_step[-1]["device_arena_bytes"] / 1e9,
+        "host_pinned_gb": per_step[-1]["host_pinned_bytes"] / 1e9,
+        "loss_first": losses[0], "loss_last": losses[-1],
+    }
+    h.close()
+    del params
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(name)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

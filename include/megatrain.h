@@ -75,6 +75,8 @@ typedef int32_t mt_status;
                                    D2H copies are skipped inside the step (gradients stay on the device).
                                    For timing the compute stream alone; results on the host are stale. */
 #define MT_FLAG_COPY_ONLY 4u    /* only the copies of a step are issued, no kernels. For timing the link. */
+#define MT_FLAG_KERNEL_TIMING 8u /* bracket every GEMM and attention launch with HIP events on the compute
+                                   stream and report per-class time, FLOPs and launch counts in mt_stats */
 
 typedef struct {
     uint32_t struct_size; /* sizeof(mt_model_cfg), checked */
@@ -102,6 +104,14 @@ typedef struct {
     uint64_t device_arena_bytes, host_pinned_bytes, host_pageable_bytes;
     uint64_t n_params;
     uint64_t steps_done;
+    /* With MT_FLAG_KERNEL_TIMING, for the last step, per kernel class
+     *   0 = matrix-core GEMM (all projections, their input/weight gradients, LM head)
+     *   1 = flash-attention forward (including recompute)   2 = flash-attention backward (dK/dV + dQ kernels)
+     * class_ms: summed launch durations from HIP events on the compute stream; class_flops: executed
+     * FLOPs (2MNK per GEMM; causal tile products for attention); class_launches: bracketed launches. */
+    double class_ms[3];
+    double class_flops[3];
+    uint64_t class_launches[3];
 } mt_stats;
 
 /* Number of parameter tensors (9 n_layers + 3) for this configuration. */

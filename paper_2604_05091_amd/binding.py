@@ -18,7 +18,7 @@ _LIB = None
 STATUS_NAMES = {0: "MT_OK", -1: "MT_ERR_INVALID_ARG", -2: "MT_ERR_UNSUPPORTED", -3: "MT_ERR_HOST_OOM",
                 -4: "MT_ERR_DEVICE_OOM", -5: "MT_ERR_HIP", -6: "MT_ERR_SHAPE", -7: "MT_ERR_TOKEN_RANGE",
                 -8: "MT_ERR_STATE"}
-FLAG_SERIAL, FLAG_COMPUTE_ONLY, FLAG_COPY_ONLY = 1, 2, 4
+FLAG_SERIAL, FLAG_COMPUTE_ONLY, FLAG_COPY_ONLY, FLAG_KERNEL_TIMING = 1, 2, 4, 8
 KIND_GRAD, KIND_ADAM_M, KIND_ADAM_V = 0, 1, 2
 ABI_VERSION = 1
 
@@ -51,10 +51,15 @@ class Stats(ctypes.Structure):
                 ("h2d_hidden_ms", c_double), ("d2h_hidden_ms", c_double),
                 ("h2d_bytes", c_uint64), ("d2h_bytes", c_uint64),
                 ("device_arena_bytes", c_uint64), ("host_pinned_bytes", c_uint64), ("host_pageable_bytes", c_uint64),
-                ("n_params", c_uint64), ("steps_done", c_uint64)]
+                ("n_params", c_uint64), ("steps_done", c_uint64),
+                ("class_ms", c_double * 3), ("class_flops", c_double * 3), ("class_launches", c_uint64 * 3)]
 
     def dict(self):
-        return {k: getattr(self, k) for k, _ in self._fields_}
+        out = {}
+        for k, _ in self._fields_:
+            v = getattr(self, k)
+            out[k] = list(v) if hasattr(v, "__len__") else v
+        return out
 
 
 def lib_path() -> str:

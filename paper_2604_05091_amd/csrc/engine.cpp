@@ -180,6 +180,12 @@ struct mt_handle {
     hipEvent_t ev_ref = nullptr, ev_inputs = nullptr;
     int resident[2] = {-1, -1};
 
+    // optional per-kernel-class timing (MT_FLAG_KERNEL_TIMING): event pairs around launches on S_comp
+    struct Span { hipEvent_t a, b; int cls; double flops; };
+    std::vector<Span> spans;
+    size_t spans_used = 0;
+    bool timing = false;
+
     mt_stats stats;
     bool have_grads = false;
     size_t pinned_bytes = 0, pageable_bytes = 0;
@@ -195,7 +201,30 @@ namespace {
             return fail(MT_ERR_HIP, "%s: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
     } while (0)
 
-hipError_t gemm(hipStream_t s, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, void *C, int64_t ldc,
+enum { CLS_GEMM = 0, CLS_ATTN_FWD = 1, CLS_ATTN_BWD = 2, CLS_COUNT = 3 };
+
+// Brackets a launch with two events when kernel timing is on.
+struct Timed {
+    mt_handle *h;
+    mt_handle::Span *sp = nullptr;
+    Timed(mt_handle *h_, int cls, double flops) : h(h_) {
+        if (!h->timing) return;
+        if (h->spans_used == h->spans.size()) {
+            mt_handle::Span n{nullptr, nullptr, 0, 0.0};
+            if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess) return;
+            h->spans.push_back(n);
+        }
+        sp = &h->spans[h->spans_used++];
+        sp->cls = cls;
+        sp->flops = flops;
+        (void)hipEventRecord(sp->a, h->s_comp);
+    }
+    ~Timed() {
+        if (sp) (void)hipEventRecord(sp->b, h->s_comp);
+    }
+};
+
+hipError_t gemm_raw(hipStream_t s, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, void *C, int64_t ldc,
                 int64_t M, int64_t N, int64_t K, bool out_fp32 = false, bool accumulate = false,
                 const uint16_t *R = nullptr, int64_t ldr = 0) {
     GemmArgs g;
@@ -203,6 +232,13 @@ hipError_t gemm(hipStream_t s, const uint16_t *A, int64_t lda, const uint16_t *B
     g.M = (int32_t)M; g.N = (int32_t)N; g.K = (int32_t)K;
     g.out_fp32 = out_fp32; g.accumulate = accumulate;
     return gemm_nt(g, s);
+}
+
+hipError_t gemm(mt_handle *h, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, void *C, int64_t ldc,
+                int64_t M, int64_t N, int64_t K, bool out_fp32 = false, bool accumulate = false,
+                const uint16_t *R = nullptr, int64_t ldr = 0) {
+    Timed t(h, CLS_GEMM, 2.0 * (double)M * (double)N * (double)K);
+    return gemm_raw(h->s_comp, A, lda, B, ldb, C, ldc, M, N, K, out_fp32, accumulate, R, ldr);
 }
 
 // out[cols, rows] = in[rows, cols]^T
@@ -258,16 +294,19 @@ mt_status layer_forward(mt_handle *h, const LayerW &w, const uint16_t *x, uint16
     const int64_t n = (int64_t)B * T;
     hipStream_t s = h->s_comp;
     KCHK(rmsnorm_fwd(h->xn, x, w.g1, n, D.d, h->cfg.rms_eps, s));
-    KCHK(gemm(s, h->xn, D.d, w.wqkv, D.d, h->qkv, D.Nqkv, n, D.Nqkv, D.d));
+    KCHK(gemm(h, h->xn, D.d, w.wqkv, D.d, h->qkv, D.Nqkv, n, D.Nqkv, D.d));
     KCHK(rope_inplace(h->qkv, D.Nqkv, n, T, D.Hq + D.Hkv, D.hd, h->rope_cos, h->rope_sin, +1, s));
     KCHK(transpose_heads(s, h->qkv + D.Nq + D.Nkv, D.Nqkv, h->vT, B, T, D.Hkv, D.hd));
     const AttnArgs a = attn_args(h, B, T);
-    KCHK(flash_fwd(a, s));
-    KCHK(gemm(s, h->att, D.Nq, w.wo, D.Nq, h->h1, D.d, n, D.d, D.Nq, false, false, x, D.d));
+    {
+        Timed t(h, CLS_ATTN_FWD, 2.0 * (double)B * D.Hq * D.hd * (double)T * ((double)T + 1.0));
+        KCHK(flash_fwd(a, s));
+    }
+    KCHK(gemm(h, h->att, D.Nq, w.wo, D.Nq, h->h1, D.d, n, D.d, D.Nq, false, false, x, D.d));
     KCHK(rmsnorm_fwd(h->yn, h->h1, w.g2, n, D.d, h->cfg.rms_eps, s));
-    KCHK(gemm(s, h->yn, D.d, w.wgu, D.d, h->gu, 2 * D.F, n, 2 * D.F, D.d));
+    KCHK(gemm(h, h->yn, D.d, w.wgu, D.d, h->gu, 2 * D.F, n, 2 * D.F, D.d));
     KCHK(swiglu_fwd(h->sact, h->gu, n, D.F, s));
-    if (y) KCHK(gemm(s, h->sact, D.F, w.wd, D.F, y, D.d, n, D.d, D.F, false, false, h->h1, D.d));
+    if (y) KCHK(gemm(h, h->sact, D.F, w.wd, D.F, y, D.d, n, D.d, D.F, false, false, h->h1, D.d));
     return MT_OK;
 }
 
@@ -282,38 +321,42 @@ mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t
     // y = h1 + s Wd^T
     KCHK(transpose2d(s, gy, h->tA, n, D.d, D.d, n));
     KCHK(transpose2d(s, h->sact, h->tB, n, D.F, D.F, n));
-    KCHK(gemm(s, h->tA, n, h->tB, n, G + o.wd, D.F, D.d, D.F, n, true));
+    KCHK(gemm(h, h->tA, n, h->tB, n, G + o.wd, D.F, D.d, D.F, n, true));
     KCHK(transpose2d(s, w.wd, h->wT, D.d, D.F, D.F, D.d));
-    KCHK(gemm(s, gy, D.d, h->wT, D.d, h->dsact, D.F, n, D.F, D.d));
+    KCHK(gemm(h, gy, D.d, h->wT, D.d, h->dsact, D.F, n, D.F, D.d));
     KCHK(swiglu_bwd(h->dgu, h->dsact, h->gu, n, D.F, s));
     // gu = yn Wgu^T
     KCHK(transpose2d(s, h->dgu, h->tA, n, 2 * D.F, 2 * D.F, n));
     KCHK(transpose2d(s, h->yn, h->tB, n, D.d, D.d, n));
-    KCHK(gemm(s, h->tA, n, h->tB, n, G + o.wgu, D.d, 2 * D.F, D.d, n, true));
+    KCHK(gemm(h, h->tA, n, h->tB, n, G + o.wgu, D.d, 2 * D.F, D.d, n, true));
     KCHK(transpose2d(s, w.wgu, h->wT, 2 * D.F, D.d, D.d, 2 * D.F));
-    KCHK(gemm(s, h->dgu, 2 * D.F, h->wT, 2 * D.F, h->dyn, D.d, n, D.d, 2 * D.F));
+    KCHK(gemm(h, h->dgu, 2 * D.F, h->wT, 2 * D.F, h->dyn, D.d, n, D.d, 2 * D.F));
     KCHK(rmsnorm_bwd(h->dh1, G + o.g2, h->dyn, h->h1, w.g2, gy, h->norm_ws, n, D.d, h->cfg.rms_eps, s));
     // h1 = x + att Wo^T
     KCHK(transpose2d(s, h->dh1, h->tA, n, D.d, D.d, n));
     KCHK(transpose2d(s, h->att, h->tB, n, D.Nq, D.Nq, n));
-    KCHK(gemm(s, h->tA, n, h->tB, n, G + o.wo, D.Nq, D.d, D.Nq, n, true));
+    KCHK(gemm(h, h->tA, n, h->tB, n, G + o.wo, D.Nq, D.d, D.Nq, n, true));
     KCHK(transpose2d(s, w.wo, h->wT, D.d, D.Nq, D.Nq, D.d));
-    KCHK(gemm(s, h->dh1, D.d, h->wT, D.d, h->datt, D.Nq, n, D.Nq, D.d));
+    KCHK(gemm(h, h->dh1, D.d, h->wT, D.d, h->datt, D.Nq, n, D.Nq, D.d));
     // attention
     const AttnArgs a = attn_args(h, B, T);
     KCHK(transpose_heads(s, h->qkv, D.Nqkv, h->qT, B, T, D.Hq, D.hd));
     KCHK(transpose_heads(s, h->qkv + D.Nq, D.Nqkv, h->kT, B, T, D.Hkv, D.hd));
     KCHK(transpose_heads(s, h->datt, D.Nq, h->doT, B, T, D.Hq, D.hd));
     KCHK(attn_delta(h->delta, h->datt, D.Nq, h->att, D.Nq, B, T, D.Hq, D.hd, s));
-    KCHK(flash_bwd_dkdv(a, s));
-    KCHK(flash_bwd_dq(a, s));
+    {
+        // 7 tile products (4 in the dK/dV kernel, 3 in the dQ kernel), causal half of T^2
+        Timed t(h, CLS_ATTN_BWD, 7.0 * (double)B * D.Hq * D.hd * (double)T * ((double)T + 1.0));
+        KCHK(flash_bwd_dkdv(a, s));
+        KCHK(flash_bwd_dq(a, s));
+    }
     KCHK(rope_inplace(h->dqkv, D.Nqkv, n, T, D.Hq + D.Hkv, D.hd, h->rope_cos, h->rope_sin, -1, s));
     // qkv = xn Wqkv^T
     KCHK(transpose2d(s, h->dqkv, h->tA, n, D.Nqkv, D.Nqkv, n));
     KCHK(transpose2d(s, h->xn, h->tB, n, D.d, D.d, n));
-    KCHK(gemm(s, h->tA, n, h->tB, n, G + o.wqkv, D.d, D.Nqkv, D.d, n, true));
+    KCHK(gemm(h, h->tA, n, h->tB, n, G + o.wqkv, D.d, D.Nqkv, D.d, n, true));
     KCHK(transpose2d(s, w.wqkv, h->wT, D.Nqkv, D.d, D.d, D.Nqkv));
-    KCHK(gemm(s, h->dqkv, D.Nqkv, h->wT, D.Nqkv, h->dxn, D.d, n, D.d, D.Nqkv));
+    KCHK(gemm(h, h->dqkv, D.Nqkv, h->wT, D.Nqkv, h->dxn, D.d, n, D.d, D.Nqkv));
     KCHK(rmsnorm_bwd(gx, G + o.g1, h->dxn, x, w.g1, h->dh1, h->norm_ws, n, D.d, h->cfg.rms_eps, s));
     return MT_OK;
 }
@@ -331,11 +374,11 @@ mt_status head_forward_backward(mt_handle *h, const uint16_t *W, float *G, const
     KCHK(transpose2d(s, zn, h->tB, n, D.d, D.d, n));        // [d, n]
     for (int64_t c0 = 0; c0 < n; c0 += h->ce_chunk) {
         const int64_t rows = std::min<int64_t>(h->ce_chunk, n - c0);
-        KCHK(gemm(s, zn + c0 * D.d, D.d, wlm, D.d, h->logits, D.V, rows, D.V, D.d, true));
+        KCHK(gemm(h, zn + c0 * D.d, D.d, wlm, D.d, h->logits, D.V, rows, D.V, D.d, true));
         KCHK(cross_entropy(h->loss_rows + c0, h->dlogits, h->logits, h->lab_dev + c0, rows, D.V, inv_n, s));
-        KCHK(gemm(s, h->dlogits, D.V, h->wT, D.V, dzn + c0 * D.d, D.d, rows, D.d, D.V));
+        KCHK(gemm(h, h->dlogits, D.V, h->wT, D.V, dzn + c0 * D.d, D.d, rows, D.d, D.V));
         KCHK(transpose2d(s, h->dlogits, h->dlT, rows, D.V, D.V, rows));  // [V, rows]
-        KCHK(gemm(s, h->dlT, rows, h->tB + c0, n, dWlm, D.d, D.V, D.d, rows, true, c0 > 0));
+        KCHK(gemm(h, h->dlT, rows, h->tB + c0, n, dWlm, D.d, D.V, D.d, rows, true, c0 > 0));
     }
     KCHK(reduce_sum(h->loss_dev, h->loss_rows, n, inv_n, 0, s));
     KCHK(rmsnorm_bwd(gx, dgf, dzn, x, gf, nullptr, h->norm_ws, n, D.d, h->cfg.rms_eps, s));
@@ -361,6 +404,10 @@ void free_handle(mt_handle *h) {
     };
     kill_events(h->w_ready); kill_events(h->w_free); kill_events(h->g_ready); kill_events(h->g_free);
     kill_events(h->h2d_start); kill_events(h->comp_start); kill_events(h->d2h_start);
+    for (auto &sp : h->spans) {
+        if (sp.a) (void)hipEventDestroy(sp.a);
+        if (sp.b) (void)hipEventDestroy(sp.b);
+    }
     if (h->ev_ref) (void)hipEventDestroy(h->ev_ref);
     if (h->ev_inputs) (void)hipEventDestroy(h->ev_inputs);
     if (h->s_comp) (void)hipStreamDestroy(h->s_comp);
@@ -456,6 +503,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     h->D = D;
     h->lo = layer_off(D);
     h->n_tensors = nt;
+    h->timing = (cfg->flags & MT_FLAG_KERNEL_TIMING) != 0;
     h->params.assign(host_param_ptrs, host_param_ptrs + nt);
     memset(&h->stats, 0, sizeof(h->stats));
 
@@ -684,6 +732,7 @@ mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labe
     const float inv_n = n_valid ? (float)(1.0 / (double)n_valid) : 0.f;
     const double t_begin = now_ms();
     HIPCHK(hipSetDevice(h->cfg.device_id));
+    h->spans_used = 0;
 
     const bool serial = h->cfg.flags & MT_FLAG_SERIAL;
     const bool no_copy = h->cfg.flags & MT_FLAG_COMPUTE_ONLY;
@@ -871,6 +920,22 @@ mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labe
             ok = ts(h->d2h_start[r], &c.a) && ts(h->g_free[r], &c.b);
             if (ok) d2h.push_back(c);
         }
+    }
+    for (int c = 0; c < 3; ++c) {
+        S.class_ms[c] = 0;
+        S.class_flops[c] = 0;
+        S.class_launches[c] = 0;
+    }
+    for (size_t i = 0; i < h->spans_used; ++i) {
+        const mt_handle::Span &sp = h->spans[i];
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, sp.a, sp.b) != hipSuccess) {
+            (void)hipGetLastError();
+            continue;
+        }
+        S.class_ms[sp.cls] += ms;
+        S.class_flops[sp.cls] += sp.flops;
+        S.class_launches[sp.cls] += 1;
     }
     S.compute_busy_ms = S.h2d_busy_ms = S.d2h_busy_ms = S.h2d_hidden_ms = S.d2h_hidden_ms = 0;
     if (ok) {
