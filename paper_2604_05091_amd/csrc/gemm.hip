@@ -20,6 +20,8 @@
 // 8 XCDs, each with a private L2.  The id is first re-numbered so that every XCD gets
 // a contiguous range of tiles, then walked in column-major groups of 8 tile rows so
 // the tiles resident on one XCD share A and B panels.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace mt {
@@ -30,13 +32,17 @@ constexpr int BK = 64;
 constexpr int LDT = BK + 8;
 constexpr int kXcd = 8;
 constexpr int kGroupM = 8;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void gemm_nt_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(GemmArgs g, int tiles_m, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
     constexpr int A_ELEMS = BM * LDT, B_ELEMS = BN * LDT, STAGE = A_ELEMS + B_ELEMS;
-    constexpr int NA = BM / 32, NB = BN / 32;  // 16-byte chunks per thread and operand
+    constexpr int RS = NT / 8;                       // rows covered by one pass of the loader
+    constexpr int NA = BM / RS, NB = BN / RS;        // 16-byte chunks per thread and operand
+    static_assert(BM % RS == 0 && BN % RS == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
 
     // ---- tile of this workgroup
     const int nb = tiles_m * tiles_n;
@@ -53,37 +59,22 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmArgs g, int tiles_m, i
     const int m0 = tm * BM, n0 = tn * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int l32 = lane & 31, hl = lane >> 5;
 
-    // ---- global -> register loader: thread owns chunk column (tid&7) of rows (tid>>3) + 32 j
+    // ---- global -> register loader.  Thread owns 16-byte chunk (tid&7) of rows (tid>>3) + RS j.
+    // Rows past the matrix edge are clamped to the last row: they only feed C rows/columns that are
+    // never stored.  Only the K tail needs real zeros; it is handled in the last step alone.
     const int lrow = tid >> 3, lkc = (tid & 7) * 8;
-    const bf16_t *ap = g.A + (int64_t)(m0 + lrow) * g.lda + lkc;
-    const bf16_t *bp = g.B + (int64_t)(n0 + lrow) * g.ldb + lkc;
-    uint4 ra[NA], rb[NB];
-    const uint4 zero = {0u, 0u, 0u, 0u};
-
-    auto load_global = [&](int k0) {
-        const bool kok = (k0 + lkc) < g.K;
+    const bf16_t *abase = g.A + (int64_t)m0 * g.lda;
+    const bf16_t *bbase = g.B + (int64_t)n0 * g.ldb;
+    uint32_t aoff[NA], boff[NB];
 #pragma unroll
-        for (int j = 0; j < NA; ++j) {
-            const bool ok = kok && (m0 + lrow + 32 * j) < g.M;
-            ra[j] = ok ? *reinterpret_cast<const uint4 *>(ap + (int64_t)(32 * j) * g.lda + k0) : zero;
-        }
+    for (int j = 0; j < NA; ++j) aoff[j] = (uint32_t)(min(lrow + RS * j, g.M - 1 - m0) * (int)g.lda + lkc);
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            const bool ok = kok && (n0 + lrow + 32 * j) < g.N;
-            rb[j] = ok ? *reinterpret_cast<const uint4 *>(bp + (int64_t)(32 * j) * g.ldb + k0) : zero;
-        }
-    };
-    auto store_lds = [&](int buf) {
-        bf16_t *as = smem + buf * STAGE + lrow * LDT + lkc;
-        bf16_t *bs = as + A_ELEMS;
-#pragma unroll
-        for (int j = 0; j < NA; ++j) *reinterpret_cast<uint4 *>(as + 32 * j * LDT) = ra[j];
-#pragma unroll
-        for (int j = 0; j < NB; ++j) *reinterpret_cast<uint4 *>(bs + 32 * j * LDT) = rb[j];
-    };
+    for (int j = 0; j < NB; ++j) boff[j] = (uint32_t)(min(lrow + RS * j, g.N - 1 - n0) * (int)g.ldb + lkc);
+    u32x4 ra[NA], rb[NB];  // native vectors: selects below stay value selects (no address-taking)
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -94,14 +85,36 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmArgs g, int tiles_m, i
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const int nk = (g.K + BK - 1) / BK;
-    load_global(0);
-    store_lds(0);
+    // K tail: a chunk at or beyond K is read from column 0 of its row instead (always in bounds) and
+    // replaced by zeros when it is written to LDS.  kok describes the chunk currently held in ra/rb.
+    bool kok = lkc < g.K;
+    {
+        const bf16_t *ak = abase + (kok ? 0 : -lkc), *bk = bbase + (kok ? 0 : -lkc);
+#pragma unroll
+        for (int j = 0; j < NA; ++j) ra[j] = *reinterpret_cast<const u32x4 *>(ak + aoff[j]);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) rb[j] = *reinterpret_cast<const u32x4 *>(bk + boff[j]);
+        bf16_t *as = smem + lrow * LDT + lkc;
+        bf16_t *bs = as + A_ELEMS;
+#pragma unroll
+        for (int j = 0; j < NA; ++j) *reinterpret_cast<u32x4 *>(as + RS * j * LDT) = kok ? ra[j] : zero4;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) *reinterpret_cast<u32x4 *>(bs + RS * j * LDT) = kok ? rb[j] : zero4;
+    }
     __syncthreads();
 
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
         const bool more = kt + 1 < nk;
-        if (more) load_global((kt + 1) * BK);
+        if (more) {
+            const int k0 = (kt + 1) * BK;
+            kok = (k0 + lkc) < g.K;
+            const bf16_t *ak = abase + (kok ? k0 : -lkc), *bk = bbase + (kok ? k0 : -lkc);
+#pragma unroll
+            for (int j = 0; j < NA; ++j) ra[j] = *reinterpret_cast<const u32x4 *>(ak + aoff[j]);
+#pragma unroll
+            for (int j = 0; j < NB; ++j) rb[j] = *reinterpret_cast<const u32x4 *>(bk + boff[j]);
+        }
         const bf16_t *as = smem + cur * STAGE + (wm * WM + l32) * LDT + hl * 8;
         const bf16_t *bs = smem + cur * STAGE + A_ELEMS + (wn * WN + l32) * LDT + hl * 8;
 #pragma unroll
@@ -117,48 +130,81 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmArgs g, int tiles_m, i
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
         }
-        if (more) store_lds(cur ^ 1);
+        if (more) {
+            bf16_t *ws = smem + (cur ^ 1) * STAGE + lrow * LDT + lkc;
+            bf16_t *wb = ws + A_ELEMS;
+#pragma unroll
+            for (int j = 0; j < NA; ++j) *reinterpret_cast<u32x4 *>(ws + RS * j * LDT) = kok ? ra[j] : zero4;
+#pragma unroll
+            for (int j = 0; j < NB; ++j) *reinterpret_cast<u32x4 *>(wb + RS * j * LDT) = kok ? rb[j] : zero4;
+        }
         __syncthreads();
     }
 
     // ---- epilogue: lane holds C[row = 8 (r/4) + 4 hl + r%4][col = l32] of each 32x32 block
+    const int row_w = m0 + wm * WM + hl * 4, col_w = n0 + wn * WN + l32;
+    const bool full = (m0 + BM <= g.M) && (n0 + BN <= g.N);
+    if (g.out_fp32) {
+        float *cw = reinterpret_cast<float *>(g.C) + (int64_t)row_w * g.ldc + col_w;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * WN + j * 32 + l32;
-            if (col >= g.N) continue;
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * WM + i * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
-                if (row >= g.M) continue;
-                float v = acc[i][j][r];
-                if (g.out_fp32) {
-                    float *c = reinterpret_cast<float *>(g.C) + (int64_t)row * g.ldc + col;
-                    if (g.accumulate) v += *c;
-                    *c = v;
-                } else {
-                    if (g.R) v += bf2f(g.R[(int64_t)row * g.ldr + col]);
-                    reinterpret_cast<bf16_t *>(g.C)[(int64_t)row * g.ldc + col] = f2bf(v);
+                const int dr = i * 32 + (r >> 2) * 8 + (r & 3);
+                if (!full && row_w + dr >= g.M) continue;
+                float *cr = cw + (int64_t)dr * g.ldc;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    if (!full && col_w + j * 32 >= g.N) continue;
+                    float v = acc[i][j][r];
+                    if (g.accumulate) v += cr[j * 32];
+                    cr[j * 32] = v;
                 }
             }
-        }
+    } else {
+        bf16_t *cw = reinterpret_cast<bf16_t *>(g.C) + (int64_t)row_w * g.ldc + col_w;
+        const bf16_t *rw = g.R ? g.R + (int64_t)row_w * g.ldr + col_w : nullptr;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = i * 32 + (r >> 2) * 8 + (r & 3);
+                if (!full && row_w + dr >= g.M) continue;
+                bf16_t *cr = cw + (int64_t)dr * g.ldc;
+                const bf16_t *rr = rw ? rw + (int64_t)dr * g.ldr : nullptr;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    if (!full && col_w + j * 32 >= g.N) continue;
+                    float v = acc[i][j][r];
+                    if (rr) v += bf2f(rr[j * 32]);
+                    cr[j * 32] = f2bf(v);
+                }
+            }
+    }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int WGM, int WGN>
 hipError_t launch(const GemmArgs &g, hipStream_t s) {
     constexpr size_t lds = (size_t)2 * (BM + BN) * LDT * sizeof(bf16_t);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_kernel<BM, BN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_kernel<BM, BN, WGM, WGN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-    hipLaunchKernelGGL((gemm_nt_kernel<BM, BN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds, s, g, tiles_m,
-                       tiles_n);
+    hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, WGM, WGN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WGM * WGN),
+                       lds, s, g, tiles_m, tiles_n);
     return hipGetLastError();
+}
+
+int variant_override() {
+    static int v = [] {
+        const char *e = getenv("MT_GEMM_VARIANT");
+        return e ? atoi(e) : 0;
+    }();
+    return v;
 }
 
 }  // namespace
@@ -169,9 +215,19 @@ hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
     if (((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
     if (g.lda < g.K || g.ldb < g.K || g.ldc < g.N) return hipErrorInvalidValue;
     if (g.R && (g.out_fp32 || g.ldr < g.N)) return hipErrorInvalidValue;
+    // offsets inside one tile are 32-bit: 256 rows of either operand must stay below 2^31 elements
+    if (g.lda >= (1 << 22) || g.ldb >= (1 << 22)) return hipErrorInvalidValue;
     const int64_t big_tiles = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256);
-    if (big_tiles >= 192) return launch<256, 256>(g, s);
-    return launch<128, 128>(g, s);
+    switch (variant_override()) {   // diagnostic override (MT_GEMM_VARIANT), 0 = heuristic
+        case 1: return launch<256, 256, 2, 2>(g, s);
+        case 2: return launch<256, 256, 2, 4>(g, s);
+        case 3: return launch<128, 128, 2, 2>(g, s);
+        case 4: return launch<256, 128, 2, 2>(g, s);
+        case 5: return launch<256, 128, 4, 2>(g, s);
+        default: break;
+    }
+    if (big_tiles >= 192) return launch<256, 256, 2, 4>(g, s);
+    return launch<128, 128, 2, 2>(g, s);
 }
 
 }  // namespace mt
