@@ -96,13 +96,14 @@ def main() -> int:
         return 2
 
     import numpy as np
-    import torch
     import mt_inputs
     import paper_2604_05091_amd as mt
-    if not torch.cuda.is_available():
+    # The library owns its device memory and streams; torch is deliberately not imported here, so the
+    # HIP runtime in use is the system one that the library was linked against.
+    mt.lib()  # fail loudly if the extension is not built
+    if mt.device_count() < 1:
         print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
         return 3
-    mt.lib()  # fail loudly if the extension is not built
 
     name = pick_config(args.config)
     shape, B, T = mt_inputs.CONFIGS[name]
@@ -126,7 +127,7 @@ def main() -> int:
         losses.append(h.train_step(tok, lab))
         h.adam_step(lr, step=step_no)
         print(f"[bench] warmup step {step_no} loss {losses[-1]:.4f}", file=sys.stderr, flush=True)
-    torch.cuda.synchronize()
+    mt.device_synchronize()
     per_step = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -138,7 +139,7 @@ def main() -> int:
         per_step.append(st)
         print(f"[bench] step {step_no} loss {losses[-1]:.4f} train {st['step_ms']:.0f} ms adam {st['adam_ms']:.0f} ms",
               file=sys.stderr, flush=True)
-    torch.cuda.synchronize()
+    mt.device_synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
 

@@ -168,6 +168,11 @@ mt_status mt_destroy(mt_handle *h);
 void *mt_host_alloc(size_t bytes);
 void mt_host_free(void *p);
 
+/* Number of visible HIP devices (0 if none or the runtime cannot initialise). */
+int32_t mt_device_count(void);
+/* Block until all work on the device has finished (hipDeviceSynchronize). */
+mt_status mt_device_synchronize(int32_t device_id);
+
 /* Message of the last error raised on the calling thread ("" if none). */
 const char *mt_last_error(void);
 

@@ -5,6 +5,6 @@ host Adam); this package is its thin ctypes binding.  There is no CPU fallback: 
 missing or no GPU is present, the calls that need one fail loudly.
 """
 from .binding import (  # noqa: F401
-    MtError, ModelCfg, Stats, TrainHandle, lib, lib_path, link_probe, model_flops, STATUS_NAMES,
+    MtError, ModelCfg, Stats, TrainHandle, lib, lib_path, link_probe, device_count, device_synchronize, model_flops, STATUS_NAMES,
     FLAG_SERIAL, FLAG_COMPUTE_ONLY, FLAG_COPY_ONLY, FLAG_KERNEL_TIMING,
 )

@@ -89,6 +89,8 @@ def lib():
         "mt_host_alloc": ([c_size_t], c_void_p),
         "mt_host_free": ([c_void_p], None),
         "mt_last_error": ([], c_char_p),
+        "mt_device_count": ([], c_int32),
+        "mt_device_synchronize": ([c_int32], c_int32),
         "mt_link_probe": ([c_int32, c_size_t, c_int32, POINTER(c_double), POINTER(c_double), POINTER(c_double)], c_int32),
         # kernels
         "mt_k_gemm_nt": ([p16, c_int64, p16, c_int64, c_void_p, c_int64, p16, c_int64, c_int32, c_int32, c_int32,
@@ -132,6 +134,14 @@ def model_flops(n_params: int, n_layers: int, hidden: int, batch: int, seq: int)
     6 N D + 12 L H T^2 per sequence, with N all parameters, D = batch*seq tokens; full (non-causal)
     attention is counted and recomputation is not."""
     return 6.0 * n_params * batch * seq + 12.0 * n_layers * hidden * float(seq) ** 2 * batch
+
+
+def device_count() -> int:
+    return lib().mt_device_count()
+
+
+def device_synchronize(device_id: int = 0) -> None:
+    check(lib().mt_device_synchronize(device_id))
 
 
 def link_probe(nbytes: int = 256 << 20, reps: int = 4, device_id: int = 0):

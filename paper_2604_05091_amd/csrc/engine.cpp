@@ -989,6 +989,21 @@ mt_status mt_destroy(mt_handle *h) {
     return MT_OK;
 }
 
+int32_t mt_device_count(void) {
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return n;
+}
+
+mt_status mt_device_synchronize(int32_t device_id) {
+    HIPCHK(hipSetDevice(device_id));
+    HIPCHK(hipDeviceSynchronize());
+    return MT_OK;
+}
+
 mt_status mt_link_probe(int32_t device_id, size_t bytes, int32_t reps, double *h2d_gbs, double *d2h_gbs,
                         double *bidir_gbs) {
     if (bytes == 0 || reps <= 0) return fail(MT_ERR_INVALID_ARG, "bytes and reps must be positive");
