@@ -30,20 +30,39 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// cooperative copy of a [ROWS x COLS] bf16 tile (row-major source with leading dimension ld, valid rows
-// < rows_valid, valid columns < cols_valid, both multiples of 8 for columns) into LDS with pitch LDP.
-template <int ROWS, int COLS, int LDP>
-__device__ __forceinline__ void load_tile(bf16_t *dst, const bf16_t *src, int64_t ld, int rows_valid, int cols_valid) {
-    constexpr int CPR = COLS / 8, CHUNKS = ROWS * CPR;
-    static_assert(CHUNKS % 256 == 0, "tile must split evenly over 256 threads");
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+// Register-staged cooperative copy of a [ROWS x COLS] bf16 tile (row-major source, leading dimension ld)
+// into LDS with pitch LDP, by NT threads.  fetch() issues all global loads back to back (out-of-range
+// chunks are redirected to the tile origin, which is always readable, and remembered in a bit mask);
+// commit() writes the registers to LDS, zeros for the out-of-range chunks.  Splitting the two lets the
+// loads of tile t+1 fly while tile t is being multiplied.
+template <int ROWS, int COLS, int LDP, int NT>
+struct TileStage {
+    static constexpr int CPR = COLS / 8, CHUNKS = ROWS * CPR, N = CHUNKS / NT;
+    static_assert(CHUNKS % NT == 0, "tile must split evenly over the threads");
+    u32x4 v[N];
+    uint32_t okmask;
+    __device__ __forceinline__ void fetch(const bf16_t *src, int64_t ld, int rows_valid, int cols_valid) {
+        okmask = 0;
 #pragma unroll
-    for (int j = 0; j < CHUNKS / 256; ++j) {
-        const int chunk = threadIdx.x + 256 * j, r = chunk / CPR, c = (chunk % CPR) * 8;
-        uint4 v = {0u, 0u, 0u, 0u};
-        if (r < rows_valid && c < cols_valid) v = *reinterpret_cast<const uint4 *>(src + (int64_t)r * ld + c);
-        *reinterpret_cast<uint4 *>(dst + r * LDP + c) = v;
+        for (int j = 0; j < N; ++j) {
+            const int chunk = threadIdx.x + NT * j, r = chunk / CPR, c = (chunk % CPR) * 8;
+            const bool ok = r < rows_valid && c < cols_valid;
+            const bf16_t *p = src + (ok ? (int64_t)r * ld + c : 0);
+            v[j] = *reinterpret_cast<const u32x4 *>(p);
+            okmask |= (ok ? 1u : 0u) << j;
+        }
     }
-}
+    __device__ __forceinline__ void commit(bf16_t *dst) const {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const int chunk = threadIdx.x + NT * j, r = chunk / CPR, c = (chunk % CPR) * 8;
+            *reinterpret_cast<u32x4 *>(dst + r * LDP + c) = ((okmask >> j) & 1u) ? v[j] : zero;
+        }
+    }
+};
 
 // A operand whose reduction index follows the accumulator-register permutation: for chunk cch of row block
 // rb the lane reads columns rb*32 + cch*16 + 4 hl + {0..3} and + 8 + {0..3} of its row.
@@ -90,19 +109,19 @@ __device__ __forceinline__ void store_owned_rows(bf16_t *out_row, const f32x16 *
 }
 
 // ------------------------------------------------------------------ forward
-// grid (q blocks of 128 rows, heaviest first; Hq; B); wave w owns 32 queries.
-template <int HD>
-__global__ __launch_bounds__(256) void flash_fwd_kernel(AttnArgs a) {
-    constexpr int LDK = HD + 8, LDV = 64 + 8;
+// grid (q blocks of 32*NW rows, heaviest first; Hq; B); wave w owns 32 queries.  K and V^T tiles of 64
+// keys go through a double-buffered LDS stage, one barrier per tile.
+template <int HD, int NW>
+__global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
+    constexpr int LDK = HD + 8, LDV = 64 + 8, NT = 64 * NW, BQ = 32 * NW;
+    constexpr int STAGE = 64 * LDK + HD * LDV;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-    bf16_t *Ks = smem;              // [64][LDK]   keys of the tile
-    bf16_t *VTs = smem + 64 * LDK;  // [HD][LDV]   values of the tile, transposed
 
     const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int hk = h / (a.Hq / a.Hkv);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
     const int T = a.T;
-    const int q0 = qb * 128 + wave * 32, q = q0 + l32;
+    const int q0 = qb * BQ + wave * 32, q = q0 + l32;
     const bool qok = q < T;
     const int qm = qok ? q : T - 1;  // padded queries behave like the last row; never stored
 
@@ -120,65 +139,92 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(AttnArgs a) {
 
     const bf16_t *kbase = a.k + (int64_t)b * T * a.ldk + (int64_t)hk * HD;
     const bf16_t *vtbase = a.vT + ((int64_t)b * a.Hkv + hk) * HD * (int64_t)T;
-    const int kv_end = min(T, qb * 128 + 128);
+    const int kv_end = min(T, qb * BQ + BQ);
     const int ntiles = (kv_end + 63) / 64;
+
+    TileStage<64, HD, LDK, NT> stK;
+    TileStage<HD, 64, LDV, NT> stV;
+    stK.fetch(kbase, a.ldk, T, HD);
+    stV.fetch(vtbase, T, HD, T);
+    stK.commit(smem);
+    stV.commit(smem + 64 * LDK);
+    __syncthreads();
 
     for (int kt = 0; kt < ntiles; ++kt) {
         const int kv0 = kt * 64;
-        __syncthreads();
-        load_tile<64, HD, LDK>(Ks, kbase + (int64_t)kv0 * a.ldk, a.ldk, T - kv0, HD);
-        load_tile<HD, 64, LDV>(VTs, vtbase + kv0, T, HD, T - kv0);
-        __syncthreads();
-        if (kv0 > q0 + 31) continue;  // the whole tile lies after every query of this wave
-
-        f32x16 sacc[2];
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            sacc[rb] = zero16();
-            const bf16_t *kr = Ks + (rb * 32 + l32) * LDK + hl * 8;
-#pragma unroll
-            for (int ks = 0; ks < HD / 16; ++ks)
-                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(kr + ks * 16),
-                                                                   qf[ks], sacc[rb], 0, 0, 0);
+        const bool more = kt + 1 < ntiles;
+        const bf16_t *Ks = smem + (kt & 1) * STAGE, *VTs = Ks + 64 * LDK;
+        if (more) {
+            stK.fetch(kbase + (int64_t)(kv0 + 64) * a.ldk, a.ldk, T - kv0 - 64, HD);
+            stV.fetch(vtbase + kv0 + 64, T, HD, T - kv0 - 64);
         }
-        float mx = -INFINITY;
+        if (kv0 <= q0 + 31) {  // otherwise the whole tile lies after every query of this wave
+            f32x16 sacc[2];
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+            for (int rb = 0; rb < 2; ++rb) {
+                sacc[rb] = zero16();
+                const bf16_t *kr = Ks + (rb * 32 + l32) * LDK + hl * 8;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kv = kv0 + rb * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
-                const float s = kv > qm ? -INFINITY : sacc[rb][r] * c;
-                sacc[rb][r] = s;
-                mx = fmaxf(mx, s);
+                for (int ks = 0; ks < HD / 16; ++ks)
+                    sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        *reinterpret_cast<const bf16x8 *>(kr + ks * 16), qf[ks], sacc[rb], 0, 0, 0);
             }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m, mx);  // finite: kv0 <= q0 <= qm, so key kv0 is visible to every query
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        float ps = 0.f;
+            float mx = -INFINITY;
+            if (kv0 + 63 > q0) {  // tile touches the diagonal: mask keys after the query
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+                for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(sacc[rb][r] - m_new);
-                sacc[rb][r] = p;
-                ps += p;
+                    for (int r = 0; r < 16; ++r) {
+                        const int kv = kv0 + rb * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
+                        const float sv = kv > qm ? -INFINITY : sacc[rb][r] * c;
+                        sacc[rb][r] = sv;
+                        mx = fmaxf(mx, sv);
+                    }
+            } else {
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float sv = sacc[rb][r] * c;
+                        sacc[rb][r] = sv;
+                        mx = fmaxf(mx, sv);
+                    }
             }
-        lsum = lsum * alpha + ps;
-        m = m_new;
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m, mx);  // finite: kv0 <= q0 <= qm, so key kv0 is visible to every query
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            float ps = 0.f;
 #pragma unroll
-        for (int hb = 0; hb < HD / 32; ++hb)
+            for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[hb][r] *= alpha;
+                for (int r = 0; r < 16; ++r) {
+                    const float pv = __builtin_amdgcn_exp2f(sacc[rb][r] - m_new);
+                    sacc[rb][r] = pv;
+                    ps += pv;
+                }
+            lsum = lsum * alpha + ps;
+            m = m_new;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+            for (int hb = 0; hb < HD / 32; ++hb)
 #pragma unroll
-            for (int cch = 0; cch < 2; ++cch) {
-                const bf16x8 pf = pack_frag(sacc[rb], cch);
+                for (int r = 0; r < 16; ++r) oacc[hb][r] *= alpha;
 #pragma unroll
-                for (int hb = 0; hb < HD / 32; ++hb)
-                    oacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        read_perm_frag(VTs + (hb * 32 + l32) * LDV, rb, cch, hl), pf, oacc[hb], 0, 0, 0);
-            }
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cch = 0; cch < 2; ++cch) {
+                    const bf16x8 pf = pack_frag(sacc[rb], cch);
+#pragma unroll
+                    for (int hb = 0; hb < HD / 32; ++hb)
+                        oacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            read_perm_frag(VTs + (hb * 32 + l32) * LDV, rb, cch, hl), pf, oacc[hb], 0, 0, 0);
+                }
+        }
+        if (more) {
+            bf16_t *nx = smem + ((kt + 1) & 1) * STAGE;
+            stK.commit(nx);
+            stV.commit(nx + 64 * LDK);
+        }
+        __syncthreads();
     }
     lsum += __shfl_xor(lsum, 32, 64);
     if (qok) {
@@ -193,10 +239,6 @@ template <int HD>
 __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
     constexpr int LDK = HD + 8, LDV = 64 + 8;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-    bf16_t *Ks = smem;               // [64][LDK]
-    bf16_t *Vs = Ks + 64 * LDK;      // [64][LDK]
-    bf16_t *KTs = Vs + 64 * LDK;     // [HD][LDV]
-
     const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int hk = h / (a.Hq / a.Hkv);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
@@ -227,43 +269,65 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
     const bf16_t *ktbase = a.kT + ((int64_t)b * a.Hkv + hk) * HD * (int64_t)T;
     const int kv_end = min(T, qb * 128 + 128);
     const int ntiles = (kv_end + 63) / 64;
+    constexpr int STAGE = 2 * 64 * LDK + HD * LDV;
+
+    TileStage<64, HD, LDK, 256> stK, stV;
+    TileStage<HD, 64, LDV, 256> stKT;
+    stK.fetch(kbase, a.ldk, T, HD);
+    stV.fetch(vbase, a.ldv, T, HD);
+    stKT.fetch(ktbase, T, HD, T);
+    stK.commit(smem);
+    stV.commit(smem + 64 * LDK);
+    stKT.commit(smem + 2 * 64 * LDK);
+    __syncthreads();
 
     for (int kt = 0; kt < ntiles; ++kt) {
         const int kv0 = kt * 64;
-        __syncthreads();
-        load_tile<64, HD, LDK>(Ks, kbase + (int64_t)kv0 * a.ldk, a.ldk, T - kv0, HD);
-        load_tile<64, HD, LDK>(Vs, vbase + (int64_t)kv0 * a.ldv, a.ldv, T - kv0, HD);
-        load_tile<HD, 64, LDV>(KTs, ktbase + kv0, T, HD, T - kv0);
-        __syncthreads();
-        if (kv0 > q0 + 31) continue;
-
+        const bool more = kt + 1 < ntiles;
+        const bf16_t *Ks = smem + (kt & 1) * STAGE, *Vs = Ks + 64 * LDK, *KTs = Vs + 64 * LDK;
+        if (more) {
+            stK.fetch(kbase + (int64_t)(kv0 + 64) * a.ldk, a.ldk, T - kv0 - 64, HD);
+            stV.fetch(vbase + (int64_t)(kv0 + 64) * a.ldv, a.ldv, T - kv0 - 64, HD);
+            stKT.fetch(ktbase + kv0 + 64, T, HD, T - kv0 - 64);
+        }
+        if (kv0 <= q0 + 31) {
+            const bool diag = kv0 + 63 > q0;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            f32x16 sacc = zero16(), dpacc = zero16();
-            const bf16_t *kr = Ks + (rb * 32 + l32) * LDK + hl * 8;
-            const bf16_t *vr = Vs + (rb * 32 + l32) * LDK + hl * 8;
+            for (int rb = 0; rb < 2; ++rb) {
+                f32x16 sacc = zero16(), dpacc = zero16();
+                const bf16_t *kr = Ks + (rb * 32 + l32) * LDK + hl * 8;
+                const bf16_t *vr = Vs + (rb * 32 + l32) * LDK + hl * 8;
 #pragma unroll
-            for (int ks = 0; ks < HD / 16; ++ks) {
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(kr + ks * 16), qf[ks],
-                                                               sacc, 0, 0, 0);
-                dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(vr + ks * 16),
-                                                                dof[ks], dpacc, 0, 0, 0);
-            }
+                for (int ks = 0; ks < HD / 16; ++ks) {
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(kr + ks * 16),
+                                                                   qf[ks], sacc, 0, 0, 0);
+                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(vr + ks * 16),
+                                                                    dof[ks], dpacc, 0, 0, 0);
+                }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kv = kv0 + rb * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
-                const float p = kv > qm ? 0.f : __builtin_amdgcn_exp2f(sacc[r] * c - lse2);
-                sacc[r] = p * (dpacc[r] - dlt);  // dS^T
-            }
+                for (int r = 0; r < 16; ++r) {
+                    const int kv = kv0 + rb * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
+                    float p = __builtin_amdgcn_exp2f(sacc[r] * c - lse2);
+                    if (diag && kv > qm) p = 0.f;
+                    sacc[r] = p * (dpacc[r] - dlt);  // dS^T
+                }
 #pragma unroll
-            for (int cch = 0; cch < 2; ++cch) {
-                const bf16x8 dsf = pack_frag(sacc, cch);
+                for (int cch = 0; cch < 2; ++cch) {
+                    const bf16x8 dsf = pack_frag(sacc, cch);
 #pragma unroll
-                for (int hb = 0; hb < HD / 32; ++hb)
-                    dqacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        read_perm_frag(KTs + (hb * 32 + l32) * LDV, rb, cch, hl), dsf, dqacc[hb], 0, 0, 0);
+                    for (int hb = 0; hb < HD / 32; ++hb)
+                        dqacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            read_perm_frag(KTs + (hb * 32 + l32) * LDV, rb, cch, hl), dsf, dqacc[hb], 0, 0, 0);
+                }
             }
         }
+        if (more) {
+            bf16_t *nx = smem + ((kt + 1) & 1) * STAGE;
+            stK.commit(nx);
+            stV.commit(nx + 64 * LDK);
+            stKT.commit(nx + 2 * 64 * LDK);
+        }
+        __syncthreads();
     }
     if (qok) store_owned_rows<HD>(a.dq + ((int64_t)b * T + q) * a.lddq + (int64_t)h * HD, dqacc, a.scale, hl);
 }
@@ -275,13 +339,9 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
 template <int HD>
 __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
     constexpr int LDK = HD + 8, LDV = 64 + 8;
+    // one stage: Q [64][LDK], dO [64][LDK], Q^T [HD][LDV], dO^T [HD][LDV] (bf16), then lse*log2e [64], delta [64] (fp32)
+    constexpr int STAGE_BF = 2 * 64 * LDK + 2 * HD * LDV, STAGE = STAGE_BF + 256;  // in bf16 elements
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-    bf16_t *Qs = smem;                 // [64][LDK]
-    bf16_t *dOs = Qs + 64 * LDK;       // [64][LDK]
-    bf16_t *QTs = dOs + 64 * LDK;      // [HD][LDV]
-    bf16_t *dOTs = QTs + HD * LDV;     // [HD][LDV]
-    float *lses = reinterpret_cast<float *>(dOTs + HD * LDV);  // [64] lse * log2e
-    float *dlts = lses + 64;                                    // [64]
 
     const int kvb = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
     const int G = a.Hq / a.Hkv;
@@ -307,32 +367,46 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
         dkacc[hb] = zero16();
     }
     const float c = a.scale * kLog2e;
-    const int qt_first = (kvb * 128) / 64, qt_end = (T + 63) / 64;
+    const int qt_first = (kvb * 128) / 64, n_qt = (T + 63) / 64 - qt_first;
+    const int total = G * n_qt;  // (query head of the group, query tile) pairs, walked as one pipeline
 
-    for (int g = 0; g < G; ++g) {
-        const int h = hk * G + g;
-        const bf16_t *qbase = a.q + (int64_t)b * T * a.ldq + (int64_t)h * HD;
-        const bf16_t *dobase = a.dout + (int64_t)b * T * a.lddo + (int64_t)h * HD;
-        const bf16_t *qtbase = a.qT + ((int64_t)b * a.Hq + h) * HD * (int64_t)T;
-        const bf16_t *dotbase = a.doT + ((int64_t)b * a.Hq + h) * HD * (int64_t)T;
-        const float *lsebase = a.lse + ((int64_t)b * a.Hq + h) * T;
-        const float *dltbase = a.delta + ((int64_t)b * a.Hq + h) * T;
+    TileStage<64, HD, LDK, 256> stQ, stDO;
+    TileStage<HD, 64, LDV, 256> stQT, stDOT;
+    float stat = 0.f;  // thread < 64: lse * log2e of query (tile row = thread); 64..127: delta
+    auto fetch = [&](int it) {
+        const int h = hk * G + it / n_qt, q0t = (qt_first + it % n_qt) * 64;
+        stQ.fetch(a.q + ((int64_t)b * T + q0t) * a.ldq + (int64_t)h * HD, a.ldq, T - q0t, HD);
+        stDO.fetch(a.dout + ((int64_t)b * T + q0t) * a.lddo + (int64_t)h * HD, a.lddo, T - q0t, HD);
+        stQT.fetch(a.qT + ((int64_t)b * a.Hq + h) * HD * (int64_t)T + q0t, T, HD, T - q0t);
+        stDOT.fetch(a.doT + ((int64_t)b * a.Hq + h) * HD * (int64_t)T + q0t, T, HD, T - q0t);
+        if (threadIdx.x < 128) {
+            const int qq = q0t + (threadIdx.x & 63);
+            const int64_t si = ((int64_t)b * a.Hq + h) * T + (qq < T ? qq : T - 1);
+            stat = threadIdx.x < 64 ? a.lse[si] * kLog2e : a.delta[si];
+        }
+    };
+    auto commit = [&](int buf) {
+        bf16_t *st = smem + buf * STAGE;
+        stQ.commit(st);
+        stDO.commit(st + 64 * LDK);
+        stQT.commit(st + 2 * 64 * LDK);
+        stDOT.commit(st + 2 * 64 * LDK + HD * LDV);
+        if (threadIdx.x < 128) reinterpret_cast<float *>(st + STAGE_BF)[threadIdx.x] = stat;
+    };
+    if (total > 0) {
+        fetch(0);
+        commit(0);
+    }
+    __syncthreads();
 
-        for (int qt = qt_first; qt < qt_end; ++qt) {
-            const int q0t = qt * 64;
-            __syncthreads();
-            load_tile<64, HD, LDK>(Qs, qbase + (int64_t)q0t * a.ldq, a.ldq, T - q0t, HD);
-            load_tile<64, HD, LDK>(dOs, dobase + (int64_t)q0t * a.lddo, a.lddo, T - q0t, HD);
-            load_tile<HD, 64, LDV>(QTs, qtbase + q0t, T, HD, T - q0t);
-            load_tile<HD, 64, LDV>(dOTs, dotbase + q0t, T, HD, T - q0t);
-            if (threadIdx.x < 64) {
-                const int qq = q0t + threadIdx.x;
-                lses[threadIdx.x] = qq < T ? lsebase[qq] * kLog2e : 0.f;
-                dlts[threadIdx.x] = qq < T ? dltbase[qq] : 0.f;
-            }
-            __syncthreads();
-            if (q0t + 63 < kv0w) continue;  // every query of the tile precedes every key of this wave
-
+    for (int it = 0; it < total; ++it) {
+        const int q0t = (qt_first + it % n_qt) * 64;
+        const bool more = it + 1 < total;
+        const bf16_t *Qs = smem + (it & 1) * STAGE, *dOs = Qs + 64 * LDK, *QTs = dOs + 64 * LDK, *dOTs = QTs + HD * LDV;
+        const float *lses = reinterpret_cast<const float *>(Qs + STAGE_BF), *dlts = lses + 64;
+        if (more) fetch(it + 1);
+        if (q0t + 63 >= kv0w) {  // otherwise every query of the tile precedes every key of this wave
+            const bool diag = q0t < kv0w + 31 || q0t + 63 >= T;  // some (query, key) pair masked, or padded queries
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb) {
                 f32x16 sacc = zero16(), dpacc = zero16();
@@ -355,7 +429,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int r = r4 * 4 + e, qq = q0t + qi + e;
-                        const float p = (kv > qq || qq >= T) ? 0.f : __builtin_amdgcn_exp2f(sacc[r] * c - lv[e]);
+                        float p = __builtin_amdgcn_exp2f(sacc[r] * c - lv[e]);
+                        if (diag && (kv > qq || qq >= T)) p = 0.f;
                         pacc[r] = p;
                         sacc[r] = p * (dpacc[r] - dv4[e]);  // dS
                     }
@@ -373,17 +448,13 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
                 }
             }
         }
+        if (more) commit((it + 1) & 1);
+        __syncthreads();
     }
     if (kvok) {
         store_owned_rows<HD>(a.dk + ((int64_t)b * T + kv) * a.lddk + (int64_t)hk * HD, dkacc, a.scale, hl);
         store_owned_rows<HD>(a.dv + ((int64_t)b * T + kv) * a.lddv + (int64_t)hk * HD, dvacc, 1.0f, hl);
     }
-}
-
-template <typename K>
-hipError_t set_lds(K kernel, size_t bytes) {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)bytes);
 }
 
 bool attn_shape_ok(const AttnArgs &a) {
@@ -397,16 +468,32 @@ bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
 }  // namespace
 
+template <typename K>
+hipError_t ensure_lds(K kernel, size_t bytes, bool *done) {
+    if (*done || bytes <= 48 * 1024) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) *done = true;
+    return e;
+}
+
 hipError_t flash_fwd(const AttnArgs &a, hipStream_t s) {
     if (!attn_shape_ok(a) || (a.ldq & 7) || (a.ldk & 7) || (a.ldo & 3)) return hipErrorInvalidValue;
     if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.vT) || ((uintptr_t)a.o & 7)) return hipErrorInvalidValue;
-    const dim3 grid((a.T + 127) / 128, a.Hq, a.B);
+    constexpr int NW = 8;
+    const dim3 grid((a.T + 32 * NW - 1) / (32 * NW), a.Hq, a.B);
     if (a.hd == 128) {
-        constexpr size_t lds = (64 * (128 + 8) + 128 * 72) * sizeof(bf16_t);
-        hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, dim3(256), lds, s, a);
+        constexpr size_t lds = 2 * (64 * (128 + 8) + 128 * 72) * sizeof(bf16_t);
+        static bool done = false;
+        hipError_t e = ensure_lds(&flash_fwd_kernel<128, NW>, lds, &done);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((flash_fwd_kernel<128, NW>), grid, dim3(64 * NW), lds, s, a);
     } else {
-        constexpr size_t lds = (64 * (64 + 8) + 64 * 72) * sizeof(bf16_t);
-        hipLaunchKernelGGL(flash_fwd_kernel<64>, grid, dim3(256), lds, s, a);
+        constexpr size_t lds = 2 * (64 * (64 + 8) + 64 * 72) * sizeof(bf16_t);
+        static bool done = false;
+        hipError_t e = ensure_lds(&flash_fwd_kernel<64, NW>, lds, &done);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((flash_fwd_kernel<64, NW>), grid, dim3(64 * NW), lds, s, a);
     }
     return hipGetLastError();
 }
@@ -419,10 +506,16 @@ hipError_t flash_bwd_dq(const AttnArgs &a, hipStream_t s) {
         return hipErrorInvalidValue;
     const dim3 grid((a.T + 127) / 128, a.Hq, a.B);
     if (a.hd == 128) {
-        constexpr size_t lds = (2 * 64 * (128 + 8) + 128 * 72) * sizeof(bf16_t);
+        constexpr size_t lds = 2 * (2 * 64 * (128 + 8) + 128 * 72) * sizeof(bf16_t);
+        static bool done = false;
+        hipError_t e = ensure_lds(&flash_bwd_dq_kernel<128>, lds, &done);
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, dim3(256), lds, s, a);
     } else {
-        constexpr size_t lds = (2 * 64 * (64 + 8) + 64 * 72) * sizeof(bf16_t);
+        constexpr size_t lds = 2 * (2 * 64 * (64 + 8) + 64 * 72) * sizeof(bf16_t);
+        static bool done = false;
+        hipError_t e = ensure_lds(&flash_bwd_dq_kernel<64>, lds, &done);
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, dim3(256), lds, s, a);
     }
     return hipGetLastError();
@@ -437,16 +530,16 @@ hipError_t flash_bwd_dkdv(const AttnArgs &a, hipStream_t s) {
         return hipErrorInvalidValue;
     const dim3 grid((a.T + 127) / 128, a.Hkv, a.B);
     if (a.hd == 128) {
-        constexpr size_t lds = (2 * 64 * (128 + 8) + 2 * 128 * 72) * sizeof(bf16_t) + 128 * sizeof(float);
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = set_lds(&flash_bwd_dkdv_kernel<128>, lds);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        constexpr size_t lds = 2 * ((2 * 64 * (128 + 8) + 2 * 128 * 72) * sizeof(bf16_t) + 512);
+        static bool done = false;
+        hipError_t e = ensure_lds(&flash_bwd_dkdv_kernel<128>, lds, &done);
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL(flash_bwd_dkdv_kernel<128>, grid, dim3(256), lds, s, a);
     } else {
-        constexpr size_t lds = (2 * 64 * (64 + 8) + 2 * 64 * 72) * sizeof(bf16_t) + 128 * sizeof(float);
+        constexpr size_t lds = 2 * ((2 * 64 * (64 + 8) + 2 * 64 * 72) * sizeof(bf16_t) + 512);
+        static bool done = false;
+        hipError_t e = ensure_lds(&flash_bwd_dkdv_kernel<64>, lds, &done);
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL(flash_bwd_dkdv_kernel<64>, grid, dim3(256), lds, s, a);
     }
     return hipGetLastError();
