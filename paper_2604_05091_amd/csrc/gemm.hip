@@ -10,9 +10,10 @@
 // Tiling: a workgroup of 4 waves (2 x 2) owns a BM x BN tile of C; each wave owns a
 // (BM/2) x (BN/2) sub-tile made of 32x32 MFMA blocks (v_mfma_f32_32x32x16_bf16,
 // 16 fp32 accumulators per lane per block).  K is walked in steps of 64 through a
-// double-buffered LDS stage: while the matrix cores consume stage s, the global
-// loads of stage s+1 are already in flight in registers and are written to the other
-// LDS buffer after the MFMAs were issued, so one barrier per step suffices.
+// double-buffered LDS stage fed from two register stages: while the matrix cores
+// consume step s from LDS, the loads of step s+1 are landing in registers and those of
+// step s+2 are being issued; step s+1 is written to the other LDS buffer after the
+// MFMAs of step s were issued, so one barrier per step suffices.
 // LDS rows are padded to 72 elements (144 B) which makes the 16-byte fragment reads
 // of 8 consecutive lanes hit 32 distinct banks.
 //
@@ -73,7 +74,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(GemmArgs g, int
     for (int j = 0; j < NA; ++j) aoff[j] = (uint32_t)(min(lrow + RS * j, g.M - 1 - m0) * (int)g.lda + lkc);
 #pragma unroll
     for (int j = 0; j < NB; ++j) boff[j] = (uint32_t)(min(lrow + RS * j, g.N - 1 - n0) * (int)g.ldb + lkc);
-    u32x4 ra[NA], rb[NB];  // native vectors: selects below stay value selects (no address-taking)
+    // Two register stages (native vectors, so the selects below stay value selects): while the matrix
+    // cores work on k-step t out of LDS, the loads of step t+1 are landing in one stage and the loads of
+    // step t+2 are being issued into the other, i.e. every global load has two compute phases to arrive.
+    u32x4 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
+    bool kok0 = true, kok1 = true;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
     f32x16 acc[TM][TN];
@@ -84,62 +89,63 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(GemmArgs g, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nk = (g.K + BK - 1) / BK;
     // K tail: a chunk at or beyond K is read from column 0 of its row instead (always in bounds) and
-    // replaced by zeros when it is written to LDS.  kok describes the chunk currently held in ra/rb.
-    bool kok = lkc < g.K;
-    {
-        const bf16_t *ak = abase + (kok ? 0 : -lkc), *bk = bbase + (kok ? 0 : -lkc);
-#pragma unroll
-        for (int j = 0; j < NA; ++j) ra[j] = *reinterpret_cast<const u32x4 *>(ak + aoff[j]);
-#pragma unroll
-        for (int j = 0; j < NB; ++j) rb[j] = *reinterpret_cast<const u32x4 *>(bk + boff[j]);
-        bf16_t *as = smem + lrow * LDT + lkc;
-        bf16_t *bs = as + A_ELEMS;
-#pragma unroll
-        for (int j = 0; j < NA; ++j) *reinterpret_cast<u32x4 *>(as + RS * j * LDT) = kok ? ra[j] : zero4;
-#pragma unroll
-        for (int j = 0; j < NB; ++j) *reinterpret_cast<u32x4 *>(bs + RS * j * LDT) = kok ? rb[j] : zero4;
+    // replaced by zeros when it is written to LDS.
+#define MT_GEMM_LOAD(RA, RB, KOK, K0)                                                                   \
+    {                                                                                                   \
+        KOK = ((K0) + lkc) < g.K;                                                                       \
+        const bf16_t *ak_ = abase + (KOK ? (K0) : -lkc), *bk_ = bbase + (KOK ? (K0) : -lkc);            \
+        _Pragma("unroll") for (int j = 0; j < NA; ++j) RA[j] = *reinterpret_cast<const u32x4 *>(ak_ + aoff[j]); \
+        _Pragma("unroll") for (int j = 0; j < NB; ++j) RB[j] = *reinterpret_cast<const u32x4 *>(bk_ + boff[j]); \
     }
+#define MT_GEMM_COMMIT(RA, RB, KOK, BUF)                                                                \
+    {                                                                                                   \
+        bf16_t *ws_ = smem + (BUF) * STAGE + lrow * LDT + lkc;                                          \
+        bf16_t *wb_ = ws_ + A_ELEMS;                                                                    \
+        _Pragma("unroll") for (int j = 0; j < NA; ++j)                                                  \
+            *reinterpret_cast<u32x4 *>(ws_ + RS * j * LDT) = KOK ? RA[j] : zero4;                       \
+        _Pragma("unroll") for (int j = 0; j < NB; ++j)                                                  \
+            *reinterpret_cast<u32x4 *>(wb_ + RS * j * LDT) = KOK ? RB[j] : zero4;                       \
+    }
+#define MT_GEMM_COMPUTE(BUF)                                                                            \
+    {                                                                                                   \
+        const bf16_t *as_ = smem + (BUF) * STAGE + (wm * WM + l32) * LDT + hl * 8;                      \
+        const bf16_t *bs_ = smem + (BUF) * STAGE + A_ELEMS + (wn * WN + l32) * LDT + hl * 8;            \
+        _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                        \
+            bf16x8 af[TM], bfr[TN];                                                                     \
+            _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
+                af[i] = *reinterpret_cast<const bf16x8 *>(as_ + i * 32 * LDT + ks * 16);                \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                              \
+                bfr[j] = *reinterpret_cast<const bf16x8 *>(bs_ + j * 32 * LDT + ks * 16);               \
+            _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
+                _Pragma("unroll") for (int j = 0; j < TN; ++j)                                          \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0); \
+        }                                                                                               \
+    }
+
+    const int nk = (g.K + BK - 1) / BK;
+    MT_GEMM_LOAD(ra0, rb0, kok0, 0);
+    MT_GEMM_COMMIT(ra0, rb0, kok0, 0);
+    if (nk > 1) MT_GEMM_LOAD(ra1, rb1, kok1, BK);
     __syncthreads();
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < nk;
-        if (more) {
-            const int k0 = (kt + 1) * BK;
-            kok = (k0 + lkc) < g.K;
-            const bf16_t *ak = abase + (kok ? k0 : -lkc), *bk = bbase + (kok ? k0 : -lkc);
-#pragma unroll
-            for (int j = 0; j < NA; ++j) ra[j] = *reinterpret_cast<const u32x4 *>(ak + aoff[j]);
-#pragma unroll
-            for (int j = 0; j < NB; ++j) rb[j] = *reinterpret_cast<const u32x4 *>(bk + boff[j]);
-        }
-        const bf16_t *as = smem + cur * STAGE + (wm * WM + l32) * LDT + hl * 8;
-        const bf16_t *bs = smem + cur * STAGE + A_ELEMS + (wn * WN + l32) * LDT + hl * 8;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[TM], bfr[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8 *>(as + i * 32 * LDT + ks * 16);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) bfr[j] = *reinterpret_cast<const bf16x8 *>(bs + j * 32 * LDT + ks * 16);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) {
-            bf16_t *ws = smem + (cur ^ 1) * STAGE + lrow * LDT + lkc;
-            bf16_t *wb = ws + A_ELEMS;
-#pragma unroll
-            for (int j = 0; j < NA; ++j) *reinterpret_cast<u32x4 *>(ws + RS * j * LDT) = kok ? ra[j] : zero4;
-#pragma unroll
-            for (int j = 0; j < NB; ++j) *reinterpret_cast<u32x4 *>(wb + RS * j * LDT) = kok ? rb[j] : zero4;
-        }
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        // even step: LDS[0] holds step kt, stage 1 holds step kt+1 (in flight)
+        if (kt + 2 < nk) MT_GEMM_LOAD(ra0, rb0, kok0, (kt + 2) * BK);
+        MT_GEMM_COMPUTE(0);
+        MT_GEMM_COMMIT(ra1, rb1, kok1, 1);
+        __syncthreads();
+        // odd step: LDS[1] holds step kt+1, stage 0 holds step kt+2 (in flight)
+        if (kt + 3 < nk) MT_GEMM_LOAD(ra1, rb1, kok1, (kt + 3) * BK);
+        MT_GEMM_COMPUTE(1);
+        if (kt + 2 < nk) MT_GEMM_COMMIT(ra0, rb0, kok0, 0);
         __syncthreads();
     }
+    if (kt < nk) MT_GEMM_COMPUTE(0);  // odd number of steps: the last one is already in LDS[0]
+#undef MT_GEMM_LOAD
+#undef MT_GEMM_COMMIT
+#undef MT_GEMM_COMPUTE
 
     // ---- epilogue: lane holds C[row = 8 (r/4) + 4 hl + r%4][col = l32] of each 32x32 block
     const int row_w = m0 + wm * WM + hl * 4, col_w = n0 + wn * WN + l32;
