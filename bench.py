@@ -148,6 +148,7 @@ def main() -> int:
     cls_ms = np.sum([s["class_ms"] for s in per_step], axis=0)
     cls_fl = np.sum([s["class_flops"] for s in per_step], axis=0)
     cls_n = np.sum([s["class_launches"] for s in per_step], axis=0)
+    cls_by = np.sum([s["class_bytes"] for s in per_step], axis=0)
     names = ["gemm_nt_kernel (bf16 MFMA GEMM)", "flash_fwd_kernel", "flash_bwd_dkdv_kernel + flash_bwd_dq_kernel"]
     dom = int(np.argmax(cls_ms))
     achieved = cls_fl[dom] / (cls_ms[dom] * 1e-3) / 1e12 if cls_ms[dom] > 0 else 0.0
@@ -162,6 +163,8 @@ def main() -> int:
                 "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
                 "launches_per_step": int(cls_n[dom] / args.steps),
                 "avg_launch_ms": float(cls_ms[dom] / max(cls_n[dom], 1)),
+                "algorithmic_bytes_per_launch": float(cls_by[dom] / max(cls_n[dom], 1)),
+                "algorithmic_flops_per_launch": float(cls_fl[dom] / max(cls_n[dom], 1)),
                 "share_of_compute_busy": float(cls_ms[dom] / args.steps / max(mean("compute_busy_ms"), 1e-9)),
                 "classes": {names[i]: {"ms_per_step": float(cls_ms[i] / args.steps),
                                        "tflops": float(cls_fl[i] / max(cls_ms[i] * 1e-3, 1e-12) / 1e12)}

@@ -108,10 +108,12 @@ typedef struct {
      *   0 = matrix-core GEMM (all projections, their input/weight gradients, LM head)
      *   1 = flash-attention forward (including recompute)   2 = flash-attention backward (dK/dV + dQ kernels)
      * class_ms: summed launch durations from HIP events on the compute stream; class_flops: executed
-     * FLOPs (2MNK per GEMM; causal tile products for attention); class_launches: bracketed launches. */
+     * FLOPs (2MNK per GEMM; causal tile products for attention); class_launches: bracketed launches;
+     * class_bytes: algorithmic HBM bytes (every operand and result once). */
     double class_ms[3];
     double class_flops[3];
     uint64_t class_launches[3];
+    double class_bytes[3];
 } mt_stats;
 
 /* Number of parameter tensors (9 n_layers + 3) for this configuration. */

@@ -52,7 +52,7 @@ class Stats(ctypes.Structure):
                 ("h2d_bytes", c_uint64), ("d2h_bytes", c_uint64),
                 ("device_arena_bytes", c_uint64), ("host_pinned_bytes", c_uint64), ("host_pageable_bytes", c_uint64),
                 ("n_params", c_uint64), ("steps_done", c_uint64),
-                ("class_ms", c_double * 3), ("class_flops", c_double * 3), ("class_launches", c_uint64 * 3)]
+                ("class_ms", c_double * 3), ("class_flops", c_double * 3), ("class_launches", c_uint64 * 3), ("class_bytes", c_double * 3)]
 
     def dict(self):
         out = {}

@@ -181,7 +181,7 @@ struct mt_handle {
     int resident[2] = {-1, -1};
 
     // optional per-kernel-class timing (MT_FLAG_KERNEL_TIMING): event pairs around launches on S_comp
-    struct Span { hipEvent_t a, b; int cls; double flops; };
+    struct Span { hipEvent_t a, b; int cls; double flops, bytes; };
     std::vector<Span> spans;
     size_t spans_used = 0;
     bool timing = false;
@@ -207,16 +207,17 @@ enum { CLS_GEMM = 0, CLS_ATTN_FWD = 1, CLS_ATTN_BWD = 2, CLS_COUNT = 3 };
 struct Timed {
     mt_handle *h;
     mt_handle::Span *sp = nullptr;
-    Timed(mt_handle *h_, int cls, double flops) : h(h_) {
+    Timed(mt_handle *h_, int cls, double flops, double bytes) : h(h_) {
         if (!h->timing) return;
         if (h->spans_used == h->spans.size()) {
-            mt_handle::Span n{nullptr, nullptr, 0, 0.0};
+            mt_handle::Span n{nullptr, nullptr, 0, 0.0, 0.0};
             if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess) return;
             h->spans.push_back(n);
         }
         sp = &h->spans[h->spans_used++];
         sp->cls = cls;
         sp->flops = flops;
+        sp->bytes = bytes;
         (void)hipEventRecord(sp->a, h->s_comp);
     }
     ~Timed() {
@@ -237,7 +238,10 @@ hipError_t gemm_raw(hipStream_t s, const uint16_t *A, int64_t lda, const uint16_
 hipError_t gemm(mt_handle *h, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, void *C, int64_t ldc,
                 int64_t M, int64_t N, int64_t K, bool out_fp32 = false, bool accumulate = false,
                 const uint16_t *R = nullptr, int64_t ldr = 0) {
-    Timed t(h, CLS_GEMM, 2.0 * (double)M * (double)N * (double)K);
+    // algorithmic bytes: both operands once, the result once (plus the residual / the accumulated-into result read)
+    const double out_b = out_fp32 ? 4.0 : 2.0;
+    const double bytes = 2.0 * ((double)M * K + (double)N * K) + (double)M * N * (out_b + (R ? 2.0 : 0.0) + (accumulate ? 4.0 : 0.0));
+    Timed t(h, CLS_GEMM, 2.0 * (double)M * (double)N * (double)K, bytes);
     return gemm_raw(h->s_comp, A, lda, B, ldb, C, ldc, M, N, K, out_fp32, accumulate, R, ldr);
 }
 
@@ -299,7 +303,8 @@ mt_status layer_forward(mt_handle *h, const LayerW &w, const uint16_t *x, uint16
     KCHK(transpose_heads(s, h->qkv + D.Nq + D.Nkv, D.Nqkv, h->vT, B, T, D.Hkv, D.hd));
     const AttnArgs a = attn_args(h, B, T);
     {
-        Timed t(h, CLS_ATTN_FWD, 2.0 * (double)B * D.Hq * D.hd * (double)T * ((double)T + 1.0));
+        Timed t(h, CLS_ATTN_FWD, 2.0 * (double)B * D.Hq * D.hd * (double)T * ((double)T + 1.0),
+                2.0 * (double)B * T * (2.0 * D.Nq + 2.0 * D.Nkv));
         KCHK(flash_fwd(a, s));
     }
     KCHK(gemm(h, h->att, D.Nq, w.wo, D.Nq, h->h1, D.d, n, D.d, D.Nq, false, false, x, D.d));
@@ -346,7 +351,8 @@ mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t
     KCHK(attn_delta(h->delta, h->datt, D.Nq, h->att, D.Nq, B, T, D.Hq, D.hd, s));
     {
         // 7 tile products (4 in the dK/dV kernel, 3 in the dQ kernel), causal half of T^2
-        Timed t(h, CLS_ATTN_BWD, 7.0 * (double)B * D.Hq * D.hd * (double)T * ((double)T + 1.0));
+        Timed t(h, CLS_ATTN_BWD, 7.0 * (double)B * D.Hq * D.hd * (double)T * ((double)T + 1.0),
+                2.0 * (double)B * T * (4.0 * D.Nq + 4.0 * D.Nkv));
         KCHK(flash_bwd_dkdv(a, s));
         KCHK(flash_bwd_dq(a, s));
     }
@@ -924,6 +930,7 @@ mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labe
     for (int c = 0; c < 3; ++c) {
         S.class_ms[c] = 0;
         S.class_flops[c] = 0;
+        S.class_bytes[c] = 0;
         S.class_launches[c] = 0;
     }
     for (size_t i = 0; i < h->spans_used; ++i) {
@@ -935,6 +942,7 @@ mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labe
         }
         S.class_ms[sp.cls] += ms;
         S.class_flops[sp.cls] += sp.flops;
+        S.class_bytes[sp.cls] += sp.bytes;
         S.class_launches[sp.cls] += 1;
     }
     S.compute_busy_ms = S.h2d_busy_ms = S.d2h_busy_ms = S.h2d_hidden_ms = S.d2h_hidden_ms = 0;
