@@ -151,6 +151,15 @@ mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labe
  * successful mt_train_step, MT_ERR_INVALID_ARG for step < 1. */
 mt_status mt_adam_step(mt_handle *h, float lr, float beta1, float beta2, float eps, float wd, int64_t step);
 
+/* mt_train_step and mt_adam_step in one call, with the optimizer overlapped: the Adam update of each
+ * unit (same arithmetic as mt_adam_step, same arguments) runs on host threads as soon as that unit's
+ * gradient block has landed, while the GPU continues with the remaining blocks (Algorithm 1,
+ * "CPU-side optimizer update (asynchronous)"; Section 3.3).  Returns after both the step and every
+ * update have finished.  On MT_OK the gradient tensors hold this step's gradients and the parameters,
+ * moments and bf16 copy are updated.  With MT_FLAG_COMPUTE_ONLY / MT_FLAG_COPY_ONLY no update is applied. */
+mt_status mt_train_step_adam(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
+                             float *loss, float lr, float beta1, float beta2, float eps, float wd, int64_t step);
+
 /* Rebuild the bf16 copy from the caller's fp32 parameters (after the caller edited them). */
 mt_status mt_refresh_shadow(mt_handle *h);
 

@@ -28,9 +28,14 @@
 #include <stdlib.h>
 #include <string.h>
 #include <algorithm>
+#include <memory>
 #include <chrono>
 #include <string>
 #include <vector>
+#include <condition_variable>
+#include <deque>
+#include <mutex>
+#include <thread>
 
 #include "../../include/megatrain.h"
 #include "common.h"
@@ -450,6 +455,88 @@ double overlap_with_union(const std::vector<Iv> &xs, std::vector<Iv> busy) {
     return tot;
 }
 
+struct AdamHyper {
+    float lr, beta1, beta2, eps, wd;
+    int64_t step;
+};
+
+void adam_unit(mt_handle *h, int unit, const AdamHyper &hp) {
+    for (int i = 0; i < h->n_tensors; ++i) {
+        const TensorRef &t = h->tref[i];
+        if (t.unit != unit) continue;
+        Unit &u = h->units[unit];
+        host_adam(h->params[i], u.h_grad + t.off, h->adam_m[unit] + t.off, h->adam_v[unit] + t.off, u.h_shadow + t.off,
+                  t.numel, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.wd, hp.step);
+    }
+}
+
+// Host optimizer running beside the GPU (Algorithm 1, "CPU-side optimizer update (asynchronous)";
+// Section 3.3: a background CPU thread applies the update as gradient blocks land).  The step pushes
+// (gradient block r, unit u) right after enqueueing the block's device-to-host copy; the worker waits
+// for that copy's event and updates the unit.  A unit's weights are never streamed again in the same
+// step once its gradients exist, so updating its master copy and bf16 copy in place is safe.
+class AdamWorker {
+  public:
+    AdamWorker(mt_handle *h, const AdamHyper &hp) : h_(h), hp_(hp), th_([this] { run(); }) {}
+    ~AdamWorker() { finish(true); }
+    void push(int r, int unit) {
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            q_.emplace_back(r, unit);
+        }
+        cv_.notify_one();
+    }
+    // abort = true drops whatever has not started yet
+    double finish(bool abort) {
+        if (th_.joinable()) {
+            {
+                std::lock_guard<std::mutex> lk(mu_);
+                done_ = true;
+                abort_ = abort_ || abort;
+            }
+            cv_.notify_one();
+            th_.join();
+        }
+        return busy_ms_;
+    }
+    bool failed() const { return failed_; }
+
+  private:
+    void run() {
+        if (hipSetDevice(h_->cfg.device_id) != hipSuccess) failed_ = true;
+        for (;;) {
+            std::pair<int, int> item;
+            {
+                std::unique_lock<std::mutex> lk(mu_);
+                cv_.wait(lk, [this] { return done_ || !q_.empty(); });
+                if (abort_ || (q_.empty() && done_)) return;
+                item = q_.front();
+                q_.pop_front();
+            }
+            if (failed_) continue;
+            if (hipEventSynchronize(h_->g_free[item.first]) != hipSuccess) {
+                (void)hipGetLastError();
+                failed_ = true;
+                continue;
+            }
+            const double t0 = now_ms();
+            adam_unit(h_, item.second, hp_);
+            busy_ms_ += now_ms() - t0;
+        }
+    }
+    mt_handle *h_;
+    AdamHyper hp_;
+    std::mutex mu_;
+    std::condition_variable cv_;
+    std::deque<std::pair<int, int>> q_;
+    bool done_ = false, abort_ = false, failed_ = false;
+    double busy_ms_ = 0;
+    std::thread th_;
+};
+
+mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
+                          float *loss, const AdamHyper *opt);
+
 }  // namespace
 
 // ====================================================================== C ABI
@@ -723,6 +810,22 @@ mt_status mt_refresh_shadow(mt_handle *h) {
 
 mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
                         float *loss) {
+    return train_step_core(h, tokens, labels, batch, seq, loss, nullptr);
+}
+
+mt_status mt_train_step_adam(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
+                             float *loss, float lr, float beta1, float beta2, float eps, float wd, int64_t step) {
+    if (step < 1) return fail(MT_ERR_INVALID_ARG, "step must be >= 1");
+    const AdamHyper hp = {lr, beta1, beta2, eps, wd, step};
+    return train_step_core(h, tokens, labels, batch, seq, loss, &hp);
+}
+
+}  // extern "C"
+
+namespace {
+
+mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
+                          float *loss, const AdamHyper *opt) {
     if (!h || !tokens || !labels || !loss) return fail(MT_ERR_INVALID_ARG, "NULL argument");
     if (batch <= 0 || seq <= 0) return fail(MT_ERR_SHAPE, "batch and seq must be positive");
     const Dims &D = h->D;
@@ -796,6 +899,8 @@ mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labe
         return MT_OK;
     };
     std::vector<char> grad_issued(D.L + 2, 0);
+    std::unique_ptr<AdamWorker> worker;
+    if (opt && !no_copy && !no_kern) worker.reset(new AdamWorker(h, *opt));
     auto issue_offload = [&](int r, int u) -> mt_status {
         HIPCHK(hipEventRecord(h->g_ready[r], sc));
         if (no_copy) return MT_OK;
@@ -805,6 +910,7 @@ mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labe
         HIPCHK(hipEventRecord(h->g_free[r], sd));
         grad_issued[r] = 1;
         d2h_bytes += h->units[u].numel * 4;
+        if (worker) worker->push(r, u);
         if (serial) HIPCHK(hipDeviceSynchronize());
         return MT_OK;
     };
@@ -887,6 +993,10 @@ mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labe
 #undef STEP
     *loss = no_kern ? 0.f : h->loss_host[0];
     h->have_grads = true;
+    if (worker) {
+        h->stats.adam_ms = worker->finish(false);
+        if (worker->failed()) return fail(MT_ERR_HIP, "the host optimizer thread could not wait for a gradient copy");
+    }
 
     // ---- statistics from event timestamps
     mt_stats &S = h->stats;
@@ -955,6 +1065,10 @@ mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labe
     }
     return MT_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 mt_status mt_adam_step(mt_handle *h, float lr, float beta1, float beta2, float eps, float wd, int64_t step) {
     if (!h) return fail(MT_ERR_INVALID_ARG, "handle is NULL");

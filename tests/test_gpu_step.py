@@ -104,6 +104,26 @@ def test_pipelined_equals_serial_and_is_reproducible(orc64):
     assert s1["n_params"] == n
 
 
+def test_overlapped_adam_equals_separate_calls_bitwise():
+    """mt_train_step_adam (update of each unit as its gradients land) == mt_train_step + mt_adam_step."""
+    shape = ModelShape(3, 128, 4, 2, 64, 344, 520)
+    params = mt_inputs.make_params(shape, seed=11, std=0.05)
+    tok, lab = mt_inputs.make_batch(shape.vocab, 2, 64, seed=12)
+    pa, pb = [p.copy() for p in params], [p.copy() for p in params]
+    with mt.TrainHandle(make_cfg(shape, 2, 64), pa) as ha, mt.TrainHandle(make_cfg(shape, 2, 64), pb) as hb:
+        for step in (1, 2, 3):
+            la = ha.train_step(tok, lab)
+            ha.adam_step(3e-4, wd=0.01, step=step)
+            lb = hb.train_step_adam(tok, lab, 3e-4, wd=0.01, step=step)
+            assert la == lb
+            for i, (a, b) in enumerate(zip(pa, pb)):
+                assert np.array_equal(a, b), (step, i)
+                assert np.array_equal(ha.tensor(i, KIND_ADAM_V), hb.tensor(i, KIND_ADAM_V))
+                assert np.array_equal(ha.tensor(i), hb.tensor(i))
+        assert hb.stats()["adam_ms"] > 0
+    assert not np.array_equal(pa[1], params[1])
+
+
 def test_smaller_batch_than_capacity_and_error_paths(orc64):
     shape = ModelShape(2, 128, 2, 2, 64, 264, 520)
     params = mt_inputs.make_params(shape, seed=7, std=0.05)
