@@ -79,20 +79,19 @@ int32_t mt_k_cross_entropy(float *loss_rows, uint16_t *dlogits, const float *log
 int32_t mt_k_reduce_sum(float *out, const float *in, int64_t n, float scale, int32_t accumulate, void *stream);
 
 /* Causal attention forward.  Rows of q/k/v/o are tokens (b*T + t); head h occupies columns
- * [h*hd, (h+1)*hd) after the given pointer.  hd in {64, 128}, T % 8 == 0, Hq % Hkv == 0.
- * vT: per-head transposed values [B, Hkv, hd, T] (made with mt_k_transpose).
- * o bf16, lse fp32 [B, Hq, T] = log sum_u exp(q_t.k_u * scale). */
+ * [h*hd, (h+1)*hd) after the given pointer.  hd in {64, 128}, T % 8 == 0, Hq % Hkv == 0; query head h
+ * reads KV head h / (Hq/Hkv).  o bf16, lse fp32 [B, Hq, T] = log sum_u exp(q_t.k_u * scale). */
 int32_t mt_k_flash_fwd(uint16_t *o, int64_t ldo, float *lse, const uint16_t *q, int64_t ldq, const uint16_t *k,
-                       int64_t ldk, const uint16_t *vT, int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t hd,
-                       float scale, void *stream);
-/* Causal attention backward: dq, dk, dv from dout, the forward's inputs, o and lse.
- * qT, kT [B,H,hd,T] are transposed copies of q, k; doT [B,Hq,hd,T] and delta [B,Hq,T] fp32 are
- * scratch written by this call (sizes B*Hq*hd*T bf16 and B*Hq*T fp32). */
+                       int64_t ldk, const uint16_t *v, int64_t ldv, int32_t B, int32_t T, int32_t Hq, int32_t Hkv,
+                       int32_t hd, float scale, void *stream);
+/* Causal attention backward: dq, dk, dv from dout, the forward's inputs, o and lse.  dk, dv of a KV head are
+ * summed over the query heads of its group.  delta [B,Hq,T] fp32 is scratch written by this call
+ * (delta = rowsum(dout * o)).  Deterministic: no atomics. */
 int32_t mt_k_flash_bwd(uint16_t *dq, int64_t lddq, uint16_t *dk, int64_t lddk, uint16_t *dv, int64_t lddv,
                        const uint16_t *dout, int64_t lddo, const uint16_t *q, int64_t ldq, const uint16_t *k,
                        int64_t ldk, const uint16_t *v, int64_t ldv, const uint16_t *o, int64_t ldo, const float *lse,
-                       const uint16_t *qT, const uint16_t *kT, uint16_t *doT, float *delta, int32_t B, int32_t T,
-                       int32_t Hq, int32_t Hkv, int32_t hd, float scale, void *stream);
+                       float *delta, int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, float scale,
+                       void *stream);
 
 /* Host Adam on one array (the arithmetic of mt_adam_step; all HOST pointers).  shadow may be
  * NULL, otherwise it receives the updated parameters rounded to bf16 (nearest even). */

@@ -110,11 +110,11 @@ def lib():
         "mt_k_embed_scatter": ([pf, p16, pi, pi, c_int32, c_int32, c_void_p], c_int32),
         "mt_k_cross_entropy": ([pf, p16, pf, pi, c_int64, c_int32, c_float, c_void_p], c_int32),
         "mt_k_reduce_sum": ([pf, pf, c_int64, c_float, c_int32, c_void_p], c_int32),
-        "mt_k_flash_fwd": ([p16, c_int64, pf, p16, c_int64, p16, c_int64, p16, c_int32, c_int32, c_int32, c_int32,
-                            c_int32, c_float, c_void_p], c_int32),
+        "mt_k_flash_fwd": ([p16, c_int64, pf, p16, c_int64, p16, c_int64, p16, c_int64, c_int32, c_int32, c_int32,
+                            c_int32, c_int32, c_float, c_void_p], c_int32),
         "mt_k_flash_bwd": ([p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, p16,
-                            c_int64, p16, c_int64, pf, p16, p16, p16, pf, c_int32, c_int32, c_int32, c_int32, c_int32,
-                            c_float, c_void_p], c_int32),
+                            c_int64, p16, c_int64, pf, pf, c_int32, c_int32, c_int32, c_int32, c_int32, c_float,
+                            c_void_p], c_int32),
         "mt_k_host_adam": ([pf, pf, pf, pf, p16, c_size_t, c_float, c_float, c_float, c_float, c_float, c_int64], c_int32),
         "mt_k_host_f32_to_bf16": ([p16, pf, c_size_t], c_int32),
     }

@@ -13,13 +13,14 @@
 //       (max, sum, lse, delta) are per-lane scalars; the only cross-lane step is one
 //       exchange with lane l^32.  P^T in registers is already a valid B operand for
 //       O^T = V^T P^T and dQ^T = K^T dS^T (the reduction index of an MFMA may be
-//       permuted freely as long as both operands use the same permutation; the A
-//       operand is read from a transposed tile with that permutation).
+//       permuted freely as long as both operands use the same permutation).
 //   dK/dV kernel:        S = Q K^T, so a lane owns one key; dV^T = dO^T P and
 //       dK^T = Q^T dS take P and dS from registers in the same way.
 //
-// Transposed operands (V^T, K^T, Q^T, dO^T, each [B,H,hd,T]) are produced beforehand
-// by the transpose kernel, so every tile load here is a plain 16-byte row copy.
+// The A operands of those second products (V^T, K^T, dO^T, Q^T) are never built in memory:
+// they are read from the natural row-major LDS tiles with the gfx950 transposing LDS read
+// (ds_read_b64_tr_b16), which hands each lane four consecutive rows of one column; two such
+// reads give exactly the eight reduction indices of the accumulator permutation.
 // dQ and dK/dV are separate kernels: no atomics, results are bit-reproducible.
 #include "common.h"
 
@@ -64,14 +65,27 @@ struct TileStage {
     }
 };
 
-// A operand whose reduction index follows the accumulator-register permutation: for chunk cch of row block
-// rb the lane reads columns rb*32 + cch*16 + 4 hl + {0..3} and + 8 + {0..3} of its row.
-__device__ __forceinline__ bf16x8 read_perm_frag(const bf16_t *row_ptr, int rb, int cch, int hl) {
-    const bf16_t *p = row_ptr + rb * 32 + cch * 16 + hl * 4;
-    const uint2 lo = *reinterpret_cast<const uint2 *>(p);
-    const uint2 hi = *reinterpret_cast<const uint2 *>(p + 8);
-    const uint4 u = {lo.x, lo.y, hi.x, hi.y};
-    return __builtin_bit_cast(bf16x8, u);
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// Transposing fragment read.  `tile` is a natural-layout LDS tile [reduction index][LDP] (e.g. V[kv][hd]).
+// The result is the A operand of an MFMA whose output rows are the tile's columns col0 .. col0+31 (lane
+// l%32 <-> column) and whose eight reduction slots of lane-half hl are the tile rows
+// row0 + 4 hl + {0..3} and row0 + 8 + 4 hl + {0..3}: the order in which a lane holds the matching
+// accumulator registers of a 32x32 block.  ds_read_b64_tr_b16 works on groups of 16 lanes: lane r' of a
+// group supplies the address of 4 consecutive columns of one row; lane i receives column i of the 4 x 16
+// block so formed, rows 0..3.  lane_off is tr_lane_offset(lane, LDP), hoisted out of the loops.
+__device__ __forceinline__ int tr_lane_offset(int lane, int ldp) {
+    const int g = lane >> 4, i = lane & 15;
+    return ((g >> 1) * 4 + (i >> 2)) * ldp + (g & 1) * 16 + (i & 3) * 4;
+}
+__device__ __forceinline__ bf16x8 read_tr_frag(const bf16_t *tile, int lane_off, int ldp, int row0, int col0) {
+    typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
+    const bf16_t *p = tile + lane_off + row0 * ldp + col0;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * ldp));
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
 }
 
 __device__ __forceinline__ bf16x8 pack_frag(const f32x16 &v, int cch) {
@@ -108,18 +122,30 @@ __device__ __forceinline__ void store_owned_rows(bf16_t *out_row, const f32x16 *
         }
 }
 
+// acc[hb] += X^T (columns hb*32.. of the natural tile X, reduction rows rb*32 + cch*16 ..) * frag, for all hb
+template <int HD, int LDP>
+__device__ __forceinline__ void mfma_tr_accumulate(f32x16 *acc, const bf16_t *tile, int tr_off, int rb, int cch,
+                                                   const bf16x8 &frag) {
+    bf16x8 a[HD / 32];
+#pragma unroll
+    for (int hb = 0; hb < HD / 32; ++hb) a[hb] = read_tr_frag(tile, tr_off, LDP, rb * 32 + cch * 16, hb * 32);
+#pragma unroll
+    for (int hb = 0; hb < HD / 32; ++hb) acc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[hb], frag, acc[hb], 0, 0, 0);
+}
+
 // ------------------------------------------------------------------ forward
-// grid (q blocks of 32*NW rows, heaviest first; Hq; B); wave w owns 32 queries.  K and V^T tiles of 64
+// grid (q blocks of 32*NW rows, heaviest first; Hq; B); wave w owns 32 queries.  K and V tiles of 64
 // keys go through a double-buffered LDS stage, one barrier per tile.
 template <int HD, int NW>
 __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
-    constexpr int LDK = HD + 8, LDV = 64 + 8, NT = 64 * NW, BQ = 32 * NW;
-    constexpr int STAGE = 64 * LDK + HD * LDV;
+    constexpr int LDK = HD + 8, NT = 64 * NW, BQ = 32 * NW;
+    constexpr int STAGE = 2 * 64 * LDK;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
 
     const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int hk = h / (a.Hq / a.Hkv);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int tr_off = tr_lane_offset(lane, LDK);
     const int T = a.T;
     const int q0 = qb * BQ + wave * 32, q = q0 + l32;
     const bool qok = q < T;
@@ -138,14 +164,13 @@ __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
     const float c = a.scale * kLog2e;
 
     const bf16_t *kbase = a.k + (int64_t)b * T * a.ldk + (int64_t)hk * HD;
-    const bf16_t *vtbase = a.vT + ((int64_t)b * a.Hkv + hk) * HD * (int64_t)T;
+    const bf16_t *vbase = a.v + (int64_t)b * T * a.ldv + (int64_t)hk * HD;
     const int kv_end = min(T, qb * BQ + BQ);
     const int ntiles = (kv_end + 63) / 64;
 
-    TileStage<64, HD, LDK, NT> stK;
-    TileStage<HD, 64, LDV, NT> stV;
+    TileStage<64, HD, LDK, NT> stK, stV;
     stK.fetch(kbase, a.ldk, T, HD);
-    stV.fetch(vtbase, T, HD, T);
+    stV.fetch(vbase, a.ldv, T, HD);
     stK.commit(smem);
     stV.commit(smem + 64 * LDK);
     __syncthreads();
@@ -153,21 +178,32 @@ __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
     for (int kt = 0; kt < ntiles; ++kt) {
         const int kv0 = kt * 64;
         const bool more = kt + 1 < ntiles;
-        const bf16_t *Ks = smem + (kt & 1) * STAGE, *VTs = Ks + 64 * LDK;
+        const bf16_t *Ks = smem + (kt & 1) * STAGE, *Vs = Ks + 64 * LDK;
         if (more) {
             stK.fetch(kbase + (int64_t)(kv0 + 64) * a.ldk, a.ldk, T - kv0 - 64, HD);
-            stV.fetch(vtbase + kv0 + 64, T, HD, T - kv0 - 64);
+            stV.fetch(vbase + (int64_t)(kv0 + 64) * a.ldv, a.ldv, T - kv0 - 64, HD);
         }
         if (kv0 <= q0 + 31) {  // otherwise the whole tile lies after every query of this wave
-            f32x16 sacc[2];
+            // S^T = K Q^T for the two 32-key row blocks: fragments are read in batches of 4 k-steps ahead of
+            // the MFMAs, and the two independent accumulation chains are interleaved
+            f32x16 sacc[2] = {zero16(), zero16()};
+            {
+                const bf16_t *kr0 = Ks + l32 * LDK + hl * 8, *kr1 = kr0 + 32 * LDK;
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-                sacc[rb] = zero16();
-                const bf16_t *kr = Ks + (rb * 32 + l32) * LDK + hl * 8;
+                for (int half = 0; half < HD / 64; ++half) {
+                    bf16x8 k0[4], k1[4];
 #pragma unroll
-                for (int ks = 0; ks < HD / 16; ++ks)
-                    sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        *reinterpret_cast<const bf16x8 *>(kr + ks * 16), qf[ks], sacc[rb], 0, 0, 0);
+                    for (int j = 0; j < 4; ++j) {
+                        k0[j] = *reinterpret_cast<const bf16x8 *>(kr0 + (half * 4 + j) * 16);
+                        k1[j] = *reinterpret_cast<const bf16x8 *>(kr1 + (half * 4 + j) * 16);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);  // keep the batch of reads ahead of the MFMAs
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[j], qf[half * 4 + j], sacc[0], 0, 0, 0);
+                        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1[j], qf[half * 4 + j], sacc[1], 0, 0, 0);
+                    }
+                }
             }
             float mx = -INFINITY;
             if (kv0 + 63 > q0) {  // tile touches the diagonal: mask keys after the query
@@ -208,16 +244,10 @@ __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
             for (int hb = 0; hb < HD / 32; ++hb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[hb][r] *= alpha;
+            // O^T += V^T P^T
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cch = 0; cch < 2; ++cch) {
-                    const bf16x8 pf = pack_frag(sacc[rb], cch);
-#pragma unroll
-                    for (int hb = 0; hb < HD / 32; ++hb)
-                        oacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            read_perm_frag(VTs + (hb * 32 + l32) * LDV, rb, cch, hl), pf, oacc[hb], 0, 0, 0);
-                }
+            for (int ch = 0; ch < 4; ++ch)
+                mfma_tr_accumulate<HD, LDK>(oacc, Vs, tr_off, ch >> 1, ch & 1, pack_frag(sacc[ch >> 1], ch & 1));
         }
         if (more) {
             bf16_t *nx = smem + ((kt + 1) & 1) * STAGE;
@@ -237,11 +267,14 @@ __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
 // Same ownership as the forward: a lane owns one query, loops over key tiles <= q.
 template <int HD>
 __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
-    constexpr int LDK = HD + 8, LDV = 64 + 8;
+    constexpr int LDK = HD + 8;
+    constexpr int STAGE = 2 * 64 * LDK;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+
     const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int hk = h / (a.Hq / a.Hkv);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int tr_off = tr_lane_offset(lane, LDK);
     const int T = a.T;
     const int q0 = qb * 128 + wave * 32, q = q0 + l32;
     const bool qok = q < T;
@@ -266,29 +299,23 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
 
     const bf16_t *kbase = a.k + (int64_t)b * T * a.ldk + (int64_t)hk * HD;
     const bf16_t *vbase = a.v + (int64_t)b * T * a.ldv + (int64_t)hk * HD;
-    const bf16_t *ktbase = a.kT + ((int64_t)b * a.Hkv + hk) * HD * (int64_t)T;
     const int kv_end = min(T, qb * 128 + 128);
     const int ntiles = (kv_end + 63) / 64;
-    constexpr int STAGE = 2 * 64 * LDK + HD * LDV;
 
     TileStage<64, HD, LDK, 256> stK, stV;
-    TileStage<HD, 64, LDV, 256> stKT;
     stK.fetch(kbase, a.ldk, T, HD);
     stV.fetch(vbase, a.ldv, T, HD);
-    stKT.fetch(ktbase, T, HD, T);
     stK.commit(smem);
     stV.commit(smem + 64 * LDK);
-    stKT.commit(smem + 2 * 64 * LDK);
     __syncthreads();
 
     for (int kt = 0; kt < ntiles; ++kt) {
         const int kv0 = kt * 64;
         const bool more = kt + 1 < ntiles;
-        const bf16_t *Ks = smem + (kt & 1) * STAGE, *Vs = Ks + 64 * LDK, *KTs = Vs + 64 * LDK;
+        const bf16_t *Ks = smem + (kt & 1) * STAGE, *Vs = Ks + 64 * LDK;
         if (more) {
             stK.fetch(kbase + (int64_t)(kv0 + 64) * a.ldk, a.ldk, T - kv0 - 64, HD);
             stV.fetch(vbase + (int64_t)(kv0 + 64) * a.ldv, a.ldv, T - kv0 - 64, HD);
-            stKT.fetch(ktbase + kv0 + 64, T, HD, T - kv0 - 64);
         }
         if (kv0 <= q0 + 31) {
             const bool diag = kv0 + 63 > q0;
@@ -298,11 +325,19 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
                 const bf16_t *kr = Ks + (rb * 32 + l32) * LDK + hl * 8;
                 const bf16_t *vr = Vs + (rb * 32 + l32) * LDK + hl * 8;
 #pragma unroll
-                for (int ks = 0; ks < HD / 16; ++ks) {
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(kr + ks * 16),
-                                                                   qf[ks], sacc, 0, 0, 0);
-                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(vr + ks * 16),
-                                                                    dof[ks], dpacc, 0, 0, 0);
+                for (int half = 0; half < HD / 64; ++half) {
+                    bf16x8 kk[4], vv[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        kk[j] = *reinterpret_cast<const bf16x8 *>(kr + (half * 4 + j) * 16);
+                        vv[j] = *reinterpret_cast<const bf16x8 *>(vr + (half * 4 + j) * 16);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk[j], qf[half * 4 + j], sacc, 0, 0, 0);
+                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv[j], dof[half * 4 + j], dpacc, 0, 0, 0);
+                    }
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -311,21 +346,16 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
                     if (diag && kv > qm) p = 0.f;
                     sacc[r] = p * (dpacc[r] - dlt);  // dS^T
                 }
+                // dQ^T += K^T dS^T
 #pragma unroll
-                for (int cch = 0; cch < 2; ++cch) {
-                    const bf16x8 dsf = pack_frag(sacc, cch);
-#pragma unroll
-                    for (int hb = 0; hb < HD / 32; ++hb)
-                        dqacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            read_perm_frag(KTs + (hb * 32 + l32) * LDV, rb, cch, hl), dsf, dqacc[hb], 0, 0, 0);
-                }
+                for (int cch = 0; cch < 2; ++cch)
+                    mfma_tr_accumulate<HD, LDK>(dqacc, Ks, tr_off, rb, cch, pack_frag(sacc, cch));
             }
         }
         if (more) {
             bf16_t *nx = smem + ((kt + 1) & 1) * STAGE;
             stK.commit(nx);
             stV.commit(nx + 64 * LDK);
-            stKT.commit(nx + 2 * 64 * LDK);
         }
         __syncthreads();
     }
@@ -338,14 +368,15 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
 // tiles >= the key block.
 template <int HD>
 __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
-    constexpr int LDK = HD + 8, LDV = 64 + 8;
-    // one stage: Q [64][LDK], dO [64][LDK], Q^T [HD][LDV], dO^T [HD][LDV] (bf16), then lse*log2e [64], delta [64] (fp32)
-    constexpr int STAGE_BF = 2 * 64 * LDK + 2 * HD * LDV, STAGE = STAGE_BF + 256;  // in bf16 elements
+    constexpr int LDK = HD + 8;
+    // one stage: Q [64][LDK], dO [64][LDK] (bf16), then lse*log2e [64], delta [64] (fp32)
+    constexpr int STAGE_BF = 2 * 64 * LDK, STAGE = STAGE_BF + 256;  // in bf16 elements
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
 
     const int kvb = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
     const int G = a.Hq / a.Hkv;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int tr_off = tr_lane_offset(lane, LDK);
     const int T = a.T;
     const int kv0w = kvb * 128 + wave * 32, kv = kv0w + l32;
     const bool kvok = kv < T;
@@ -371,14 +402,11 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
     const int total = G * n_qt;  // (query head of the group, query tile) pairs, walked as one pipeline
 
     TileStage<64, HD, LDK, 256> stQ, stDO;
-    TileStage<HD, 64, LDV, 256> stQT, stDOT;
     float stat = 0.f;  // thread < 64: lse * log2e of query (tile row = thread); 64..127: delta
     auto fetch = [&](int it) {
         const int h = hk * G + it / n_qt, q0t = (qt_first + it % n_qt) * 64;
         stQ.fetch(a.q + ((int64_t)b * T + q0t) * a.ldq + (int64_t)h * HD, a.ldq, T - q0t, HD);
         stDO.fetch(a.dout + ((int64_t)b * T + q0t) * a.lddo + (int64_t)h * HD, a.lddo, T - q0t, HD);
-        stQT.fetch(a.qT + ((int64_t)b * a.Hq + h) * HD * (int64_t)T + q0t, T, HD, T - q0t);
-        stDOT.fetch(a.doT + ((int64_t)b * a.Hq + h) * HD * (int64_t)T + q0t, T, HD, T - q0t);
         if (threadIdx.x < 128) {
             const int qq = q0t + (threadIdx.x & 63);
             const int64_t si = ((int64_t)b * a.Hq + h) * T + (qq < T ? qq : T - 1);
@@ -389,8 +417,6 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
         bf16_t *st = smem + buf * STAGE;
         stQ.commit(st);
         stDO.commit(st + 64 * LDK);
-        stQT.commit(st + 2 * 64 * LDK);
-        stDOT.commit(st + 2 * 64 * LDK + HD * LDV);
         if (threadIdx.x < 128) reinterpret_cast<float *>(st + STAGE_BF)[threadIdx.x] = stat;
     };
     if (total > 0) {
@@ -402,7 +428,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
     for (int it = 0; it < total; ++it) {
         const int q0t = (qt_first + it % n_qt) * 64;
         const bool more = it + 1 < total;
-        const bf16_t *Qs = smem + (it & 1) * STAGE, *dOs = Qs + 64 * LDK, *QTs = dOs + 64 * LDK, *dOTs = QTs + HD * LDV;
+        const bf16_t *Qs = smem + (it & 1) * STAGE, *dOs = Qs + 64 * LDK;
         const float *lses = reinterpret_cast<const float *>(Qs + STAGE_BF), *dlts = lses + 64;
         if (more) fetch(it + 1);
         if (q0t + 63 >= kv0w) {  // otherwise every query of the tile precedes every key of this wave
@@ -413,11 +439,19 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
                 const bf16_t *qr = Qs + (rb * 32 + l32) * LDK + hl * 8;
                 const bf16_t *dor = dOs + (rb * 32 + l32) * LDK + hl * 8;
 #pragma unroll
-                for (int ks = 0; ks < HD / 16; ++ks) {
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(qr + ks * 16),
-                                                                   kf[ks], sacc, 0, 0, 0);
-                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(dor + ks * 16),
-                                                                    vf[ks], dpacc, 0, 0, 0);
+                for (int half = 0; half < HD / 64; ++half) {
+                    bf16x8 qq4[4], dd4[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        qq4[j] = *reinterpret_cast<const bf16x8 *>(qr + (half * 4 + j) * 16);
+                        dd4[j] = *reinterpret_cast<const bf16x8 *>(dor + (half * 4 + j) * 16);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq4[j], kf[half * 4 + j], sacc, 0, 0, 0);
+                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dd4[j], vf[half * 4 + j], dpacc, 0, 0, 0);
+                    }
                 }
                 f32x16 pacc;
 #pragma unroll
@@ -435,16 +469,11 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
                         sacc[r] = p * (dpacc[r] - dv4[e]);  // dS
                     }
                 }
+                // dV^T += dO^T P,  dK^T += Q^T dS
 #pragma unroll
                 for (int cch = 0; cch < 2; ++cch) {
-                    const bf16x8 pf = pack_frag(pacc, cch), dsf = pack_frag(sacc, cch);
-#pragma unroll
-                    for (int hb = 0; hb < HD / 32; ++hb) {
-                        dvacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            read_perm_frag(dOTs + (hb * 32 + l32) * LDV, rb, cch, hl), pf, dvacc[hb], 0, 0, 0);
-                        dkacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            read_perm_frag(QTs + (hb * 32 + l32) * LDV, rb, cch, hl), dsf, dkacc[hb], 0, 0, 0);
-                    }
+                    mfma_tr_accumulate<HD, LDK>(dvacc, dOs, tr_off, rb, cch, pack_frag(pacc, cch));
+                    mfma_tr_accumulate<HD, LDK>(dkacc, Qs, tr_off, rb, cch, pack_frag(sacc, cch));
                 }
             }
         }
@@ -469,7 +498,7 @@ bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 }  // namespace
 
 template <typename K>
-hipError_t ensure_lds(K kernel, size_t bytes, bool *done) {
+static hipError_t ensure_lds(K kernel, size_t bytes, bool *done) {
     if (*done || bytes <= 48 * 1024) return hipSuccess;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
@@ -478,18 +507,18 @@ hipError_t ensure_lds(K kernel, size_t bytes, bool *done) {
 }
 
 hipError_t flash_fwd(const AttnArgs &a, hipStream_t s) {
-    if (!attn_shape_ok(a) || (a.ldq & 7) || (a.ldk & 7) || (a.ldo & 3)) return hipErrorInvalidValue;
-    if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.vT) || ((uintptr_t)a.o & 7)) return hipErrorInvalidValue;
+    if (!attn_shape_ok(a) || (a.ldq & 7) || (a.ldk & 7) || (a.ldv & 7) || (a.ldo & 3)) return hipErrorInvalidValue;
+    if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || ((uintptr_t)a.o & 7)) return hipErrorInvalidValue;
     constexpr int NW = 8;
     const dim3 grid((a.T + 32 * NW - 1) / (32 * NW), a.Hq, a.B);
     if (a.hd == 128) {
-        constexpr size_t lds = 2 * (64 * (128 + 8) + 128 * 72) * sizeof(bf16_t);
+        constexpr size_t lds = 2 * (2 * 64 * (128 + 8)) * sizeof(bf16_t);
         static bool done = false;
         hipError_t e = ensure_lds(&flash_fwd_kernel<128, NW>, lds, &done);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL((flash_fwd_kernel<128, NW>), grid, dim3(64 * NW), lds, s, a);
     } else {
-        constexpr size_t lds = 2 * (64 * (64 + 8) + 64 * 72) * sizeof(bf16_t);
+        constexpr size_t lds = 2 * (2 * 64 * (64 + 8)) * sizeof(bf16_t);
         static bool done = false;
         hipError_t e = ensure_lds(&flash_fwd_kernel<64, NW>, lds, &done);
         if (e != hipSuccess) return e;
@@ -501,18 +530,17 @@ hipError_t flash_fwd(const AttnArgs &a, hipStream_t s) {
 hipError_t flash_bwd_dq(const AttnArgs &a, hipStream_t s) {
     if (!attn_shape_ok(a) || (a.ldq & 7) || (a.ldk & 7) || (a.ldv & 7) || (a.lddo & 7) || (a.lddq & 3))
         return hipErrorInvalidValue;
-    if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.kT) || !aligned16(a.dout) ||
-        ((uintptr_t)a.dq & 7))
+    if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.dout) || ((uintptr_t)a.dq & 7))
         return hipErrorInvalidValue;
     const dim3 grid((a.T + 127) / 128, a.Hq, a.B);
     if (a.hd == 128) {
-        constexpr size_t lds = 2 * (2 * 64 * (128 + 8) + 128 * 72) * sizeof(bf16_t);
+        constexpr size_t lds = 2 * (2 * 64 * (128 + 8)) * sizeof(bf16_t);
         static bool done = false;
         hipError_t e = ensure_lds(&flash_bwd_dq_kernel<128>, lds, &done);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, dim3(256), lds, s, a);
     } else {
-        constexpr size_t lds = 2 * (2 * 64 * (64 + 8) + 64 * 72) * sizeof(bf16_t);
+        constexpr size_t lds = 2 * (2 * 64 * (64 + 8)) * sizeof(bf16_t);
         static bool done = false;
         hipError_t e = ensure_lds(&flash_bwd_dq_kernel<64>, lds, &done);
         if (e != hipSuccess) return e;
@@ -525,18 +553,18 @@ hipError_t flash_bwd_dkdv(const AttnArgs &a, hipStream_t s) {
     if (!attn_shape_ok(a) || (a.ldq & 7) || (a.ldk & 7) || (a.ldv & 7) || (a.lddo & 7) || (a.lddk & 3) ||
         (a.lddv & 3))
         return hipErrorInvalidValue;
-    if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.qT) || !aligned16(a.doT) ||
-        !aligned16(a.dout) || ((uintptr_t)a.dk & 7) || ((uintptr_t)a.dv & 7))
+    if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.dout) || ((uintptr_t)a.dk & 7) ||
+        ((uintptr_t)a.dv & 7))
         return hipErrorInvalidValue;
     const dim3 grid((a.T + 127) / 128, a.Hkv, a.B);
     if (a.hd == 128) {
-        constexpr size_t lds = 2 * ((2 * 64 * (128 + 8) + 2 * 128 * 72) * sizeof(bf16_t) + 512);
+        constexpr size_t lds = 2 * ((2 * 64 * (128 + 8)) * sizeof(bf16_t) + 512);
         static bool done = false;
         hipError_t e = ensure_lds(&flash_bwd_dkdv_kernel<128>, lds, &done);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(flash_bwd_dkdv_kernel<128>, grid, dim3(256), lds, s, a);
     } else {
-        constexpr size_t lds = 2 * ((2 * 64 * (64 + 8) + 2 * 64 * 72) * sizeof(bf16_t) + 512);
+        constexpr size_t lds = 2 * ((2 * 64 * (64 + 8)) * sizeof(bf16_t) + 512);
         static bool done = false;
         hipError_t e = ensure_lds(&flash_bwd_dkdv_kernel<64>, lds, &done);
         if (e != hipSuccess) return e;

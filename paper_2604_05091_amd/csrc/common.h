@@ -94,7 +94,6 @@ hipError_t reduce_sum(float *out, const float *in, int64_t n, float scale, int a
 
 // Flash attention (causal, grouped KV heads).  q/k/v/o rows are tokens (b*T + t); head h occupies
 // columns [h*hd, (h+1)*hd) from the given base pointer with the given leading dimension.
-// kT / vT / qT / doT are per-head transposed copies [B, H, hd, T].
 // lse [B, Hq, T] fp32 = log sum_u exp(s_tu) of the scaled scores.
 struct AttnArgs {
     int32_t B, T, Hq, Hkv, hd;
@@ -102,12 +101,10 @@ struct AttnArgs {
     const bf16_t *q; int64_t ldq;
     const bf16_t *k; int64_t ldk;
     const bf16_t *v; int64_t ldv;
-    const bf16_t *qT, *kT, *vT;
     bf16_t *o; int64_t ldo;
     float *lse;
     // backward only
     const bf16_t *dout; int64_t lddo;
-    const bf16_t *doT;
     const float *delta;  // [B,Hq,T] rowsum(do * o)
     bf16_t *dq; int64_t lddq;
     bf16_t *dk; int64_t lddk;

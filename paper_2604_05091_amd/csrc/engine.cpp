@@ -170,7 +170,7 @@ struct mt_handle {
     uint16_t *Wbuf[2] = {nullptr, nullptr};
     float *Gbuf[2] = {nullptr, nullptr};
     std::vector<uint16_t *> anchors;  // h_0..h_L
-    uint16_t *xn, *yn, *qkv, *att, *h1, *gu, *sact, *vT, *qT, *kT, *doT;
+    uint16_t *xn, *yn, *qkv, *att, *h1, *gu, *sact;
     uint16_t *dsact, *dgu, *dyn, *dh1, *datt, *dqkv, *dxn, *gA, *gB, *tA, *tB, *wT;
     uint16_t *dlogits, *dlT;
     float *lse, *delta, *logits, *loss_rows, *loss_dev, *norm_ws, *rope_cos, *rope_sin;
@@ -259,16 +259,6 @@ hipError_t transpose2d(hipStream_t s, const uint16_t *in, uint16_t *out, int64_t
     return transpose_bf16(t, s);
 }
 
-// per-head transpose of a [B*T, ld] activation slice (H heads of hd columns) into [B, H, hd, T]
-hipError_t transpose_heads(hipStream_t s, const uint16_t *in, int64_t ld, uint16_t *out, int B, int T, int H, int hd) {
-    TransposeArgs t;
-    t.in = in; t.out = out; t.rows = T; t.cols = hd; t.ld_in = ld; t.ld_out = T;
-    t.nb0 = B; t.nb1 = H;
-    t.in_s0 = (int64_t)T * ld; t.in_s1 = hd;
-    t.out_s0 = (int64_t)H * hd * T; t.out_s1 = (int64_t)hd * T;
-    return transpose_bf16(t, s);
-}
-
 struct LayerW {
     const uint16_t *wqkv, *wo, *wgu, *wd, *g1, *g2;
 };
@@ -285,11 +275,9 @@ AttnArgs attn_args(const mt_handle *h, int B, int T) {
     a.q = h->qkv; a.ldq = D.Nqkv;
     a.k = h->qkv + D.Nq; a.ldk = D.Nqkv;
     a.v = h->qkv + D.Nq + D.Nkv; a.ldv = D.Nqkv;
-    a.qT = h->qT; a.kT = h->kT; a.vT = h->vT;
     a.o = h->att; a.ldo = D.Nq;
     a.lse = h->lse;
     a.dout = h->datt; a.lddo = D.Nq;
-    a.doT = h->doT;
     a.delta = h->delta;
     a.dq = h->dqkv; a.lddq = D.Nqkv;
     a.dk = h->dqkv + D.Nq; a.lddk = D.Nqkv;
@@ -305,7 +293,6 @@ mt_status layer_forward(mt_handle *h, const LayerW &w, const uint16_t *x, uint16
     KCHK(rmsnorm_fwd(h->xn, x, w.g1, n, D.d, h->cfg.rms_eps, s));
     KCHK(gemm(h, h->xn, D.d, w.wqkv, D.d, h->qkv, D.Nqkv, n, D.Nqkv, D.d));
     KCHK(rope_inplace(h->qkv, D.Nqkv, n, T, D.Hq + D.Hkv, D.hd, h->rope_cos, h->rope_sin, +1, s));
-    KCHK(transpose_heads(s, h->qkv + D.Nq + D.Nkv, D.Nqkv, h->vT, B, T, D.Hkv, D.hd));
     const AttnArgs a = attn_args(h, B, T);
     {
         Timed t(h, CLS_ATTN_FWD, 2.0 * (double)B * D.Hq * D.hd * (double)T * ((double)T + 1.0),
@@ -350,9 +337,6 @@ mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t
     KCHK(gemm(h, h->dh1, D.d, h->wT, D.d, h->datt, D.Nq, n, D.Nq, D.d));
     // attention
     const AttnArgs a = attn_args(h, B, T);
-    KCHK(transpose_heads(s, h->qkv, D.Nqkv, h->qT, B, T, D.Hq, D.hd));
-    KCHK(transpose_heads(s, h->qkv + D.Nq, D.Nqkv, h->kT, B, T, D.Hkv, D.hd));
-    KCHK(transpose_heads(s, h->datt, D.Nq, h->doT, B, T, D.Hq, D.hd));
     KCHK(attn_delta(h->delta, h->datt, D.Nq, h->att, D.Nq, B, T, D.Hq, D.hd, s));
     {
         // 7 tile products (4 in the dK/dV kernel, 3 in the dQ kernel), causal half of T^2
@@ -645,7 +629,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     const size_t wT_elems = std::max<size_t>(std::max<size_t>((size_t)2 * D.F * D.d, (size_t)D.Nqkv * D.d),
                                             std::max<size_t>((size_t)D.V * D.d, (size_t)D.d * D.Nq));
     struct Plan {
-        size_t W[2], G[2], anchors, xn, yn, qkv, att, h1, gu, sact, vT, qT, kT, doT, dsact, dgu, dyn, dh1, datt, dqkv,
+        size_t W[2], G[2], anchors, xn, yn, qkv, att, h1, gu, sact, dsact, dgu, dyn, dh1, datt, dqkv,
             dxn, gA, gB, tA, tB, wT, dlogits, dlT, lse, delta, logits, loss_rows, loss_dev, norm_ws, rope_cos, rope_sin,
             tok, lab, rowstart, order;
     } P;
@@ -655,7 +639,6 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     P.xn = plan(n * D.d * e2); P.yn = plan(n * D.d * e2);
     P.qkv = plan(n * D.Nqkv * e2); P.att = plan(n * D.Nq * e2); P.h1 = plan(n * D.d * e2);
     P.gu = plan(n * 2 * D.F * e2); P.sact = plan(n * D.F * e2);
-    P.vT = plan(n * D.Nkv * e2); P.qT = plan(n * D.Nq * e2); P.kT = plan(n * D.Nkv * e2); P.doT = plan(n * D.Nq * e2);
     P.dsact = plan(n * D.F * e2); P.dgu = plan(n * 2 * D.F * e2);
     P.dyn = plan(n * D.d * e2); P.dh1 = plan(n * D.d * e2); P.datt = plan(n * D.Nq * e2);
     P.dqkv = plan(n * D.Nqkv * e2); P.dxn = plan(n * D.d * e2);
@@ -711,8 +694,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     for (int i = 0; i <= D.L; ++i) h->anchors[i] = (uint16_t *)(A + P.anchors) + (size_t)i * n * D.d;
     h->xn = (uint16_t *)(A + P.xn); h->yn = (uint16_t *)(A + P.yn); h->qkv = (uint16_t *)(A + P.qkv);
     h->att = (uint16_t *)(A + P.att); h->h1 = (uint16_t *)(A + P.h1); h->gu = (uint16_t *)(A + P.gu);
-    h->sact = (uint16_t *)(A + P.sact); h->vT = (uint16_t *)(A + P.vT); h->qT = (uint16_t *)(A + P.qT);
-    h->kT = (uint16_t *)(A + P.kT); h->doT = (uint16_t *)(A + P.doT); h->dsact = (uint16_t *)(A + P.dsact);
+    h->sact = (uint16_t *)(A + P.sact); h->dsact = (uint16_t *)(A + P.dsact);
     h->dgu = (uint16_t *)(A + P.dgu); h->dyn = (uint16_t *)(A + P.dyn); h->dh1 = (uint16_t *)(A + P.dh1);
     h->datt = (uint16_t *)(A + P.datt); h->dqkv = (uint16_t *)(A + P.dqkv); h->dxn = (uint16_t *)(A + P.dxn);
     h->gA = (uint16_t *)(A + P.gA); h->gB = (uint16_t *)(A + P.gB); h->tA = (uint16_t *)(A + P.tA);

@@ -105,39 +105,32 @@ int32_t mt_k_reduce_sum(float *out, const float *in, int64_t n, float scale, int
 }
 
 int32_t mt_k_flash_fwd(uint16_t *o, int64_t ldo, float *lse, const uint16_t *q, int64_t ldq, const uint16_t *k,
-                       int64_t ldk, const uint16_t *vT, int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t hd,
-                       float scale, void *stream) {
-    if (!o || !lse || !q || !k || !vT) return MT_ERR_INVALID_ARG;
+                       int64_t ldk, const uint16_t *v, int64_t ldv, int32_t B, int32_t T, int32_t Hq, int32_t Hkv,
+                       int32_t hd, float scale, void *stream) {
+    if (!o || !lse || !q || !k || !v) return MT_ERR_INVALID_ARG;
     AttnArgs a = {};
     a.B = B; a.T = T; a.Hq = Hq; a.Hkv = Hkv; a.hd = hd; a.scale = scale;
-    a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.vT = vT; a.o = o; a.ldo = ldo; a.lse = lse;
+    a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.v = v; a.ldv = ldv; a.o = o; a.ldo = ldo; a.lse = lse;
     return to_status(flash_fwd(a, S(stream)));
 }
 
 int32_t mt_k_flash_bwd(uint16_t *dq, int64_t lddq, uint16_t *dk, int64_t lddk, uint16_t *dv, int64_t lddv,
                        const uint16_t *dout, int64_t lddo, const uint16_t *q, int64_t ldq, const uint16_t *k,
                        int64_t ldk, const uint16_t *v, int64_t ldv, const uint16_t *o, int64_t ldo, const float *lse,
-                       const uint16_t *qT, const uint16_t *kT, uint16_t *doT, float *delta, int32_t B, int32_t T,
-                       int32_t Hq, int32_t Hkv, int32_t hd, float scale, void *stream) {
-    if (!dq || !dk || !dv || !dout || !q || !k || !v || !o || !lse || !qT || !kT || !doT || !delta)
-        return MT_ERR_INVALID_ARG;
+                       float *delta, int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, float scale,
+                       void *stream) {
+    if (!dq || !dk || !dv || !dout || !q || !k || !v || !o || !lse || !delta) return MT_ERR_INVALID_ARG;
     if (B <= 0 || T <= 0 || Hq <= 0 || (hd != 64 && hd != 128) || (T & 7) || (lddo & 7) || (ldo & 7) || !al16(dout) ||
-        !al16(o) || !al16(doT))
+        !al16(o))
         return MT_ERR_INVALID_ARG;
     AttnArgs a = {};
     a.B = B; a.T = T; a.Hq = Hq; a.Hkv = Hkv; a.hd = hd; a.scale = scale;
-    a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.v = v; a.ldv = ldv; a.qT = qT; a.kT = kT;
+    a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.v = v; a.ldv = ldv;
     a.o = const_cast<uint16_t *>(o); a.ldo = ldo; a.lse = const_cast<float *>(lse);
-    a.dout = dout; a.lddo = lddo; a.doT = doT; a.delta = delta;
+    a.dout = dout; a.lddo = lddo; a.delta = delta;
     a.dq = dq; a.lddq = lddq; a.dk = dk; a.lddk = lddk; a.dv = dv; a.lddv = lddv;
     hipStream_t s = S(stream);
-    TransposeArgs t;
-    t.in = dout; t.out = doT; t.rows = T; t.cols = hd; t.ld_in = lddo; t.ld_out = T;
-    t.nb0 = B; t.nb1 = Hq; t.in_s0 = (int64_t)T * lddo; t.in_s1 = hd;
-    t.out_s0 = (int64_t)Hq * hd * T; t.out_s1 = (int64_t)hd * T;
-    hipError_t e = transpose_bf16(t, s);
-    if (e != hipSuccess) return to_status(e);
-    e = attn_delta(delta, dout, lddo, o, ldo, B, T, Hq, hd, s);
+    hipError_t e = attn_delta(delta, dout, lddo, o, ldo, B, T, Hq, hd, s);
     if (e != hipSuccess) return to_status(e);
     e = flash_bwd_dkdv(a, s);
     if (e != hipSuccess) return to_status(e);

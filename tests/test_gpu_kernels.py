@@ -224,11 +224,9 @@ def _attention_case(orc64, B, T, Hq, Hkv, hd, seed):
     scale = 1.0 / np.sqrt(hd)
     QKV = dev_bf16(qkv)
     pq, pk, pv = QKV.data_ptr(), QKV.data_ptr() + 2 * nq, QKV.data_ptr() + 2 * (nq + nkv)
-    VT = torch.empty((B, Hkv, hd, T), dtype=torch.bfloat16, device="cuda")
-    ok(L.mt_k_transpose(pv, VT.data_ptr(), T, hd, ld, T, B, Hkv, T * ld, hd, Hkv * hd * T, hd * T, None))
     O = torch.zeros((B * T, nq), dtype=torch.bfloat16, device="cuda")
     LSE = torch.zeros((B, Hq, T), dtype=torch.float32, device="cuda")
-    ok(L.mt_k_flash_fwd(O.data_ptr(), nq, LSE.data_ptr(), pq, ld, pk, ld, VT.data_ptr(), B, T, Hq, Hkv, hd, scale, None))
+    ok(L.mt_k_flash_fwd(O.data_ptr(), nq, LSE.data_ptr(), pq, ld, pk, ld, pv, ld, B, T, Hq, Hkv, hd, scale, None))
     a_ref = orc64.attention_fwd(q, k, v, B, T, Hq, Hkv, hd)
     assert rel_l2(host(O), a_ref) < BF16_TOL
     # log-sum-exp of the first and last row of head 0: lse_0 = s_00, lse_last from the definition
@@ -239,17 +237,11 @@ def _attention_case(orc64, B, T, Hq, Hkv, hd, seed):
     dout = bf16_round(rng.standard_normal((B * T, nq)))
     dq_ref, dk_ref, dv_ref = orc64.attention_bwd(dout, q, k, v, B, T, Hq, Hkv, hd)
     DO = dev_bf16(dout)
-    QT = torch.empty((B, Hq, hd, T), dtype=torch.bfloat16, device="cuda")
-    KT = torch.empty((B, Hkv, hd, T), dtype=torch.bfloat16, device="cuda")
-    ok(L.mt_k_transpose(pq, QT.data_ptr(), T, hd, ld, T, B, Hq, T * ld, hd, Hq * hd * T, hd * T, None))
-    ok(L.mt_k_transpose(pk, KT.data_ptr(), T, hd, ld, T, B, Hkv, T * ld, hd, Hkv * hd * T, hd * T, None))
-    DOT = torch.empty((B, Hq, hd, T), dtype=torch.bfloat16, device="cuda")
     DELTA = torch.empty((B, Hq, T), dtype=torch.float32, device="cuda")
     DQKV = torch.zeros((B * T, ld), dtype=torch.bfloat16, device="cuda")
     pdq, pdk, pdv = DQKV.data_ptr(), DQKV.data_ptr() + 2 * nq, DQKV.data_ptr() + 2 * (nq + nkv)
     ok(L.mt_k_flash_bwd(pdq, ld, pdk, ld, pdv, ld, DO.data_ptr(), nq, pq, ld, pk, ld, pv, ld, O.data_ptr(), nq,
-                        LSE.data_ptr(), QT.data_ptr(), KT.data_ptr(), DOT.data_ptr(), DELTA.data_ptr(), B, T, Hq, Hkv,
-                        hd, scale, None))
+                        LSE.data_ptr(), DELTA.data_ptr(), B, T, Hq, Hkv, hd, scale, None))
     got = host(DQKV)
     # the backward reads O and P in bf16, so its error is a few bf16 roundings deep
     assert rel_l2(got[:, :nq], dq_ref) < 2e-2 and cosine(got[:, :nq], dq_ref) > 0.9995
@@ -267,6 +259,6 @@ def test_flash_attention_rejects_bad_shapes():
     x = torch.zeros(4096, dtype=torch.bfloat16, device="cuda")
     f = torch.zeros(4096, dtype=torch.float32, device="cuda")
     p = x.data_ptr()
-    assert L.mt_k_flash_fwd(p, 64, f.data_ptr(), p, 64, p, 64, p, 1, 12, 1, 1, 64, 0.125, None) == -1   # T % 8
-    assert L.mt_k_flash_fwd(p, 96, f.data_ptr(), p, 96, p, 96, p, 1, 8, 1, 1, 96, 0.1, None) == -1      # head_dim
-    assert L.mt_k_flash_fwd(p, 64, f.data_ptr(), p, 64, p, 64, p, 1, 8, 3, 2, 64, 0.125, None) == -1    # Hq % Hkv
+    assert L.mt_k_flash_fwd(p, 64, f.data_ptr(), p, 64, p, 64, p, 64, 1, 12, 1, 1, 64, 0.125, None) == -1   # T % 8
+    assert L.mt_k_flash_fwd(p, 96, f.data_ptr(), p, 96, p, 96, p, 96, 1, 8, 1, 1, 96, 0.1, None) == -1      # head_dim
+    assert L.mt_k_flash_fwd(p, 64, f.data_ptr(), p, 64, p, 64, p, 64, 1, 8, 3, 2, 64, 0.125, None) == -1    # Hq % Hkv
