@@ -368,7 +368,10 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
 // tiles >= the key block.
 template <int HD>
 __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
-    constexpr int LDK = HD + 8;
+#ifndef MT_DKDV_KB
+#define MT_DKDV_KB 2
+#endif
+    constexpr int LDK = HD + 8, KB = MT_DKDV_KB;  // KB: k-steps whose fragments are read ahead of their MFMAs
     // one stage: Q [64][LDK], dO [64][LDK] (bf16), then lse*log2e [64], delta [64] (fp32)
     constexpr int STAGE_BF = 2 * 64 * LDK, STAGE = STAGE_BF + 256;  // in bf16 elements
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
@@ -439,18 +442,18 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
                 const bf16_t *qr = Qs + (rb * 32 + l32) * LDK + hl * 8;
                 const bf16_t *dor = dOs + (rb * 32 + l32) * LDK + hl * 8;
 #pragma unroll
-                for (int half = 0; half < HD / 64; ++half) {
-                    bf16x8 qq4[4], dd4[4];
+                for (int part = 0; part < HD / (16 * KB); ++part) {
+                    bf16x8 qq4[KB], dd4[KB];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        qq4[j] = *reinterpret_cast<const bf16x8 *>(qr + (half * 4 + j) * 16);
-                        dd4[j] = *reinterpret_cast<const bf16x8 *>(dor + (half * 4 + j) * 16);
+                    for (int j = 0; j < KB; ++j) {
+                        qq4[j] = *reinterpret_cast<const bf16x8 *>(qr + (part * KB + j) * 16);
+                        dd4[j] = *reinterpret_cast<const bf16x8 *>(dor + (part * KB + j) * 16);
                     }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq4[j], kf[half * 4 + j], sacc, 0, 0, 0);
-                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dd4[j], vf[half * 4 + j], dpacc, 0, 0, 0);
+                    for (int j = 0; j < KB; ++j) {
+                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq4[j], kf[part * KB + j], sacc, 0, 0, 0);
+                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dd4[j], vf[part * KB + j], dpacc, 0, 0, 0);
                     }
                 }
                 f32x16 pacc;

@@ -33,6 +33,12 @@ constexpr int BK = 64;
 constexpr int LDT = BK + 8;
 constexpr int kXcd = 8;
 constexpr int kGroupM = 8;
+#ifndef MT_GX_SETPRIO
+#define MT_GX_SETPRIO 0
+#endif
+#ifndef MT_GX_STAGES
+#define MT_GX_STAGES 1
+#endif
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 template <int BM, int BN, int WGM, int WGN>
@@ -107,23 +113,36 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(GemmArgs g, int
         _Pragma("unroll") for (int j = 0; j < NB; ++j)                                                  \
             *reinterpret_cast<u32x4 *>(wb_ + RS * j * LDT) = KOK ? RB[j] : zero4;                       \
     }
+    // Fragments of k-substep ks+1 are read while the MFMAs of substep ks run (two fragment sets); the
+    // scheduling barrier keeps the compiler from sinking the reads back next to their first use.
+#define MT_GEMM_READ_FRAGS(SET, KS)                                                                     \
+    {                                                                                                   \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                  \
+            af[SET][i] = *reinterpret_cast<const bf16x8 *>(as_ + i * 32 * LDT + (KS) * 16);             \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                  \
+            bfr[SET][j] = *reinterpret_cast<const bf16x8 *>(bs_ + j * 32 * LDT + (KS) * 16);            \
+    }
 #define MT_GEMM_COMPUTE(BUF)                                                                            \
     {                                                                                                   \
         const bf16_t *as_ = smem + (BUF) * STAGE + (wm * WM + l32) * LDT + hl * 8;                      \
         const bf16_t *bs_ = smem + (BUF) * STAGE + A_ELEMS + (wn * WN + l32) * LDT + hl * 8;            \
+        bf16x8 af[2][TM], bfr[2][TN];                                                                   \
+        MT_GEMM_READ_FRAGS(0, 0);                                                                       \
         _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                        \
-            bf16x8 af[TM], bfr[TN];                                                                     \
-            _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
-                af[i] = *reinterpret_cast<const bf16x8 *>(as_ + i * 32 * LDT + ks * 16);                \
-            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                              \
-                bfr[j] = *reinterpret_cast<const bf16x8 *>(bs_ + j * 32 * LDT + ks * 16);               \
+            if (ks + 1 < BK / 16) MT_GEMM_READ_FRAGS((ks + 1) & 1, ks + 1);                             \
+            __builtin_amdgcn_sched_barrier(0);                                                          \
+            if (MT_GX_SETPRIO) __builtin_amdgcn_s_setprio(1);                                           \
             _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
                 _Pragma("unroll") for (int j = 0; j < TN; ++j)                                          \
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0); \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j],  \
+                                                                        acc[i][j], 0, 0, 0);            \
+            if (MT_GX_SETPRIO) __builtin_amdgcn_s_setprio(0);                                           \
+            __builtin_amdgcn_sched_barrier(0);                                                          \
         }                                                                                               \
     }
 
     const int nk = (g.K + BK - 1) / BK;
+#if MT_GX_STAGES == 2
     MT_GEMM_LOAD(ra0, rb0, kok0, 0);
     MT_GEMM_COMMIT(ra0, rb0, kok0, 0);
     if (nk > 1) MT_GEMM_LOAD(ra1, rb1, kok1, BK);
@@ -143,9 +162,28 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(GemmArgs g, int
         __syncthreads();
     }
     if (kt < nk) MT_GEMM_COMPUTE(0);  // odd number of steps: the last one is already in LDS[0]
+#else
+    (void)ra1; (void)rb1; (void)kok1;
+    MT_GEMM_LOAD(ra0, rb0, kok0, 0);
+    MT_GEMM_COMMIT(ra0, rb0, kok0, 0);
+    __syncthreads();
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        MT_GEMM_LOAD(ra0, rb0, kok0, (kt + 1) * BK);
+        MT_GEMM_COMPUTE(0);
+        MT_GEMM_COMMIT(ra0, rb0, kok0, 1);
+        __syncthreads();
+        if (kt + 2 < nk) MT_GEMM_LOAD(ra0, rb0, kok0, (kt + 2) * BK);
+        MT_GEMM_COMPUTE(1);
+        if (kt + 2 < nk) MT_GEMM_COMMIT(ra0, rb0, kok0, 0);
+        __syncthreads();
+    }
+    if (kt < nk) MT_GEMM_COMPUTE(0);
+#endif
 #undef MT_GEMM_LOAD
 #undef MT_GEMM_COMMIT
 #undef MT_GEMM_COMPUTE
+#undef MT_GEMM_READ_FRAGS
 
     // ---- epilogue: lane holds C[row = 8 (r/4) + 4 hl + r%4][col = l32] of each 32x32 block
     const int row_w = m0 + wm * WM + hl * 4, col_w = n0 + wn * WN + l32;
