@@ -75,6 +75,10 @@ typedef int32_t mt_status;
                                    D2H copies are skipped inside the step (gradients stay on the device).
                                    For timing the compute stream alone; results on the host are stale. */
 #define MT_FLAG_COPY_ONLY 4u    /* only the copies of a step are issued, no kernels. For timing the link. */
+#define MT_FLAG_GRAD_SLABS 16u   /* force the gradient slab pool (Section 3.3): gradient blocks in pageable memory, device-to-host
+                                   copies through 4 recycled pinned slabs folded in by a host thread.  Chosen automatically
+                                   when pinning every gradient block would exceed the pinned-memory budget (56 GiB, or
+                                   MT_PINNED_BUDGET_GB in the environment). */
 #define MT_FLAG_KERNEL_TIMING 8u /* bracket every GEMM and attention launch with HIP events on the compute
                                    stream and report per-class time, FLOPs and launch counts in mt_stats */
 
@@ -128,8 +132,8 @@ mt_status mt_tensor_info(const mt_model_cfg *cfg, int32_t idx, int64_t *rows, in
  * caller, must outlive the handle, may be pageable memory and are modified only by
  * mt_adam_step.  The library allocates: a pinned bf16 copy of every unit's weights laid out
  * as one contiguous 4 KiB-aligned block per unit (Section 3.3 layer-contiguous tiling: one DMA
- * per unit), pinned fp32 gradient blocks, Adam moments (zero), the device arena, three
- * streams and the events.  Fails with MT_ERR_DEVICE_OOM / MT_ERR_HOST_OOM without leaking. */
+ * per unit), fp32 gradient blocks (pinned, or pageable behind a pool of pinned slabs, see
+ * MT_FLAG_GRAD_SLABS), Adam moments (zero), the device arena, three streams and the events.  Fails with MT_ERR_DEVICE_OOM / MT_ERR_HOST_OOM without leaking. */
 mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_handle **out);
 
 /* One training step without the optimizer (Algorithm 1, phases 1-3).

@@ -66,6 +66,8 @@ class Oracle:
         L.orc_rope.argtypes = [vp, i64, i64, i64, i64, dbl, ctypes.c_int]
         L.orc_attention_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64]
         L.orc_attention_bwd.argtypes = [vp] * 7 + [i64] * 5
+        L.orc_attention_row.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64]
+        L.orc_attention_row.restype = None
         L.orc_swiglu_fwd.argtypes = [vp, vp, vp, i64]
         L.orc_swiglu_bwd.argtypes = [vp, vp, vp, vp, vp, i64]
         L.orc_cross_entropy.argtypes = [vp, vp, vp, vp, i64, i64]
@@ -139,6 +141,14 @@ class Oracle:
         self.lib.orc_attention_bwd(dq.ctypes.data, dk.ctypes.data, dv.ctypes.data, da.ctypes.data, q.ctypes.data,
                                    k.ctypes.data, v.ctypes.data, B, T, Hq, Hkv, hd)
         return dq, dk, dv
+
+    def attention_row(self, q, da, k, v):
+        """One query row: q, da [hd]; k, v [n_keys, hd] (the keys visible to it).  Returns (a, dq)."""
+        q, da, k, v = self.arr(q), self.arr(da), self.arr(k), self.arr(v)
+        a, dq = np.empty_like(q), np.empty_like(q)
+        self.lib.orc_attention_row(a.ctypes.data, dq.ctypes.data, q.ctypes.data, da.ctypes.data, k.ctypes.data,
+                                   v.ctypes.data, k.shape[0], k.shape[1])
+        return a, dq
 
     def swiglu_fwd(self, gate, up):
         gate, up = self.arr(gate), self.arr(up)

@@ -258,6 +258,50 @@ void orc_attention_bwd(real *dq, real *dk, real *dv, const real *da, const real 
         }
 }
 
+/* One query row of the causal attention above, and the gradient with respect to that query:
+ * a = sum_u p_u v_u with p = softmax_u(q.k_u / sqrt(hd)) over the n_keys visible keys (k, v are
+ * [n_keys, hd] contiguous); dq = sum_u p_u (dp_u - sum_w p_w dp_w) k_u / sqrt(hd), dp_u = da.v_u.
+ * Used to check single rows of very long sequences, where the full O(T^2) routine is out of reach. */
+void orc_attention_row(real *a, real *dq, const real *q, const real *da, const real *k, const real *v, int64_t n_keys,
+                       int64_t hd) {
+    const real scale = (real)(1.0 / sqrt((double)hd));
+    real *p = (real *)malloc(sizeof(real) * (size_t)n_keys);
+    real mx = -INFINITY;
+    for (int64_t u = 0; u < n_keys; ++u) {
+        real s = 0;
+        for (int64_t j = 0; j < hd; ++j) s += q[j] * k[u * hd + j];
+        p[u] = s * scale;
+        if (p[u] > mx) mx = p[u];
+    }
+    real den = 0;
+    for (int64_t u = 0; u < n_keys; ++u) {
+        p[u] = (real)exp((double)(p[u] - mx));
+        den += p[u];
+    }
+    for (int64_t j = 0; j < hd; ++j) a[j] = 0;
+    for (int64_t u = 0; u < n_keys; ++u) {
+        p[u] /= den;
+        for (int64_t j = 0; j < hd; ++j) a[j] += p[u] * v[u * hd + j];
+    }
+    if (dq && da) {
+        real pdp = 0;
+        real *dp = (real *)malloc(sizeof(real) * (size_t)n_keys);
+        for (int64_t u = 0; u < n_keys; ++u) {
+            real s = 0;
+            for (int64_t j = 0; j < hd; ++j) s += da[j] * v[u * hd + j];
+            dp[u] = s;
+            pdp += p[u] * s;
+        }
+        for (int64_t j = 0; j < hd; ++j) dq[j] = 0;
+        for (int64_t u = 0; u < n_keys; ++u) {
+            const real ds = p[u] * (dp[u] - pdp) * scale;
+            for (int64_t j = 0; j < hd; ++j) dq[j] += ds * k[u * hd + j];
+        }
+        free(dp);
+    }
+    free(p);
+}
+
 /* ------------------------------------------------------------------ SwiGLU
  * s = gate * sigmoid(gate) * up */
 void orc_swiglu_fwd(real *s, const real *gate, const real *up, int64_t n) {

@@ -80,7 +80,7 @@ struct TensorRef {
 struct Unit {
     size_t numel = 0;
     uint16_t *h_shadow = nullptr;  // pinned bf16 block
-    float *h_grad = nullptr;       // pinned fp32 block
+    float *h_grad = nullptr;       // fp32 gradient block: pinned, or pageable when the slab pool is in use
 };
 
 // element offsets inside a block unit
@@ -176,6 +176,13 @@ struct mt_handle {
     float *lse, *delta, *logits, *loss_rows, *loss_dev, *norm_ws, *rope_cos, *rope_sin;
     int32_t *tok_dev, *lab_dev, *rowstart_dev, *order_dev;
     int64_t ce_chunk = 0;
+    // gradient slab pool (Section 3.3 / Appendix A.3): when the fp32 gradient blocks cannot all be pinned,
+    // they live in pageable memory and every device-to-host copy lands in one of n_slabs pinned slabs of
+    // P_max floats first; a host thread then folds the slab into the unit's gradient block and recycles it.
+    bool grad_slabs = false;
+    int n_slabs = 0;
+    std::vector<float *> slabs;
+
     // pinned staging
     int32_t *tok_host = nullptr;  // tokens | labels | row_start | order
     float *loss_host = nullptr;
@@ -411,8 +418,13 @@ void free_handle(mt_handle *h) {
     if (h->arena) (void)hipFree(h->arena);
     for (auto &u : h->units) {
         if (u.h_shadow) (void)hipHostFree(u.h_shadow);
-        if (u.h_grad) (void)hipHostFree(u.h_grad);
+        if (u.h_grad) {
+            if (h->grad_slabs) free(u.h_grad);
+            else (void)hipHostFree(u.h_grad);
+        }
     }
+    for (auto p : h->slabs)
+        if (p) (void)hipHostFree(p);
     for (auto p : h->adam_m) free(p);
     for (auto p : h->adam_v) free(p);
     if (h->tok_host) (void)hipHostFree(h->tok_host);
@@ -459,14 +471,26 @@ void adam_unit(mt_handle *h, int unit, const AdamHyper &hp) {
 // (gradient block r, unit u) right after enqueueing the block's device-to-host copy; the worker waits
 // for that copy's event and updates the unit.  A unit's weights are never streamed again in the same
 // step once its gradients exist, so updating its master copy and bf16 copy in place is safe.
-class AdamWorker {
+class HostWorker {
   public:
-    AdamWorker(mt_handle *h, const AdamHyper &hp) : h_(h), hp_(hp), th_([this] { run(); }) {}
-    ~AdamWorker() { finish(true); }
-    void push(int r, int unit) {
+    // opt == nullptr: no optimizer, the worker only drains gradient slabs
+    HostWorker(mt_handle *h, const AdamHyper *opt) : h_(h), has_opt_(opt != nullptr), slab_busy_(h->n_slabs, 0) {
+        if (opt) hp_ = *opt;
+        th_ = std::thread([this] { run(); });
+    }
+    ~HostWorker() { finish(true); }
+    // main thread, slab mode: block until the slab is drained; false if the worker failed or was aborted
+    bool acquire_slab(int slab) {
+        std::unique_lock<std::mutex> lk(mu_);
+        cv_main_.wait(lk, [&] { return !slab_busy_[slab] || failed_ || abort_; });
+        if (failed_ || abort_) return false;
+        slab_busy_[slab] = 1;
+        return true;
+    }
+    void push(int r, int unit, int slab) {
         {
             std::lock_guard<std::mutex> lk(mu_);
-            q_.emplace_back(r, unit);
+            q_.push_back({r, unit, slab});
         }
         cv_.notify_one();
     }
@@ -479,6 +503,7 @@ class AdamWorker {
                 abort_ = abort_ || abort;
             }
             cv_.notify_one();
+            cv_main_.notify_all();
             th_.join();
         }
         return busy_ms_;
@@ -486,10 +511,11 @@ class AdamWorker {
     bool failed() const { return failed_; }
 
   private:
+    struct Item { int r, unit, slab; };
     void run() {
-        if (hipSetDevice(h_->cfg.device_id) != hipSuccess) failed_ = true;
+        if (hipSetDevice(h_->cfg.device_id) != hipSuccess) set_failed();
         for (;;) {
-            std::pair<int, int> item;
+            Item item;
             {
                 std::unique_lock<std::mutex> lk(mu_);
                 cv_.wait(lk, [this] { return done_ || !q_.empty(); });
@@ -498,21 +524,42 @@ class AdamWorker {
                 q_.pop_front();
             }
             if (failed_) continue;
-            if (hipEventSynchronize(h_->g_free[item.first]) != hipSuccess) {
+            if (hipEventSynchronize(h_->g_free[item.r]) != hipSuccess) {
                 (void)hipGetLastError();
-                failed_ = true;
+                set_failed();
                 continue;
             }
             const double t0 = now_ms();
-            adam_unit(h_, item.second, hp_);
+            if (item.slab >= 0) {
+                // "Acc" of the paper's slab pool: fold the slab into the master gradient store, then recycle it
+                Unit &u = h_->units[item.unit];
+                const char *src = reinterpret_cast<const char *>(h_->slabs[item.slab]);
+                char *dst = reinterpret_cast<char *>(u.h_grad);
+                parallel_for(u.numel * sizeof(float), 1 << 22, [&](size_t b, size_t e) { memcpy(dst + b, src + b, e - b); });
+                {
+                    std::lock_guard<std::mutex> lk(mu_);
+                    slab_busy_[item.slab] = 0;
+                }
+                cv_main_.notify_all();
+            }
+            if (has_opt_) adam_unit(h_, item.unit, hp_);
             busy_ms_ += now_ms() - t0;
         }
     }
+    void set_failed() {
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            failed_ = true;
+        }
+        cv_main_.notify_all();
+    }
     mt_handle *h_;
-    AdamHyper hp_;
+    bool has_opt_;
+    AdamHyper hp_ = {};
     std::mutex mu_;
-    std::condition_variable cv_;
-    std::deque<std::pair<int, int>> q_;
+    std::condition_variable cv_, cv_main_;
+    std::deque<Item> q_;
+    std::vector<char> slab_busy_;
     bool done_ = false, abort_ = false, failed_ = false;
     double busy_ms_ = 0;
     std::thread th_;
@@ -730,14 +777,45 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
 
     // ---- host state
     size_t pinned = 0, pageable = 0;
+    {
+        // Pin every gradient block when that fits the pinned-memory budget; otherwise use the slab pool.
+        size_t want = 0;
+        for (auto &u : h->units) want += align_up(u.numel * e2, 4096) + align_up(u.numel * e4, 4096);
+        size_t budget = (size_t)56 << 30;
+        if (const char *e = getenv("MT_PINNED_BUDGET_GB")) budget = (size_t)atoll(e) << 30;
+        h->grad_slabs = (cfg->flags & MT_FLAG_GRAD_SLABS) || want > budget;
+        h->n_slabs = h->grad_slabs ? 4 : 0;
+    }
     for (auto &u : h->units) {
-        if (hipHostMalloc((void **)&u.h_shadow, align_up(u.numel * e2, 4096), hipHostMallocDefault) != hipSuccess ||
-            hipHostMalloc((void **)&u.h_grad, align_up(u.numel * e4, 4096), hipHostMallocDefault) != hipSuccess) {
+        bool ok = hipHostMalloc((void **)&u.h_shadow, align_up(u.numel * e2, 4096), hipHostMallocDefault) == hipSuccess;
+        pinned += align_up(u.numel * e2, 4096);
+        if (ok) {
+            if (h->grad_slabs) {
+                void *pg = nullptr;
+                ok = posix_memalign(&pg, 4096, align_up(u.numel * e4, 4096)) == 0;
+                u.h_grad = (float *)pg;
+                pageable += align_up(u.numel * e4, 4096);
+            } else {
+                ok = hipHostMalloc((void **)&u.h_grad, align_up(u.numel * e4, 4096), hipHostMallocDefault) == hipSuccess;
+                pinned += align_up(u.numel * e4, 4096);
+            }
+        }
+        if (!ok) {
             (void)hipGetLastError();
             free_handle(h);
-            return fail(MT_ERR_HOST_OOM, "pinned host allocation failed");
+            return fail(MT_ERR_HOST_OOM, "host allocation of a unit's bf16 / gradient block failed (pinned so far: %zu bytes)",
+                        pinned);
         }
-        pinned += align_up(u.numel * e2, 4096) + align_up(u.numel * e4, 4096);
+    }
+    h->slabs.assign(h->n_slabs, nullptr);
+    for (int i = 0; i < h->n_slabs; ++i) {
+        if (hipHostMalloc((void **)&h->slabs[i], align_up(h->pmax * e4, 4096), hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            free_handle(h);
+            return fail(MT_ERR_HOST_OOM, "pinned gradient slab allocation failed");
+        }
+        host_zero(h->slabs[i], align_up(h->pmax * e4, 4096));
+        pinned += align_up(h->pmax * e4, 4096);
     }
     h->adam_m.assign(h->units.size(), nullptr);
     h->adam_v.assign(h->units.size(), nullptr);
@@ -881,18 +959,27 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
         return MT_OK;
     };
     std::vector<char> grad_issued(D.L + 2, 0);
-    std::unique_ptr<AdamWorker> worker;
-    if (opt && !no_copy && !no_kern) worker.reset(new AdamWorker(h, *opt));
+    std::unique_ptr<HostWorker> worker;
+    const bool apply_opt = opt && !no_copy && !no_kern;
+    if (apply_opt || (h->grad_slabs && !no_copy)) worker.reset(new HostWorker(h, apply_opt ? opt : nullptr));
     auto issue_offload = [&](int r, int u) -> mt_status {
         HIPCHK(hipEventRecord(h->g_ready[r], sc));
         if (no_copy) return MT_OK;
         HIPCHK(hipStreamWaitEvent(sd, h->g_ready[r], 0));
         HIPCHK(hipEventRecord(h->d2h_start[r], sd));
-        HIPCHK(hipMemcpyAsync(h->units[u].h_grad, h->Gbuf[r & 1], h->units[u].numel * 4, hipMemcpyDeviceToHost, sd));
+        int slab = -1;
+        float *dst = h->units[u].h_grad;
+        if (h->grad_slabs) {
+            // back-pressure of the slab pool: wait (on the host) until the slab's previous content is folded away
+            slab = r % h->n_slabs;
+            if (!worker->acquire_slab(slab)) return fail(MT_ERR_HIP, "the host worker failed while draining a gradient slab");
+            dst = h->slabs[slab];
+        }
+        HIPCHK(hipMemcpyAsync(dst, h->Gbuf[r & 1], h->units[u].numel * 4, hipMemcpyDeviceToHost, sd));
         HIPCHK(hipEventRecord(h->g_free[r], sd));
         grad_issued[r] = 1;
         d2h_bytes += h->units[u].numel * 4;
-        if (worker) worker->push(r, u);
+        if (worker) worker->push(r, u, slab);
         if (serial) HIPCHK(hipDeviceSynchronize());
         return MT_OK;
     };
@@ -976,8 +1063,9 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     *loss = no_kern ? 0.f : h->loss_host[0];
     h->have_grads = true;
     if (worker) {
-        h->stats.adam_ms = worker->finish(false);
-        if (worker->failed()) return fail(MT_ERR_HIP, "the host optimizer thread could not wait for a gradient copy");
+        const double busy = worker->finish(false);
+        if (apply_opt) h->stats.adam_ms = busy;
+        if (worker->failed()) return fail(MT_ERR_HIP, "the host worker thread could not wait for a gradient copy");
     }
 
     // ---- statistics from event timestamps

@@ -124,6 +124,28 @@ def test_overlapped_adam_equals_separate_calls_bitwise():
     assert not np.array_equal(pa[1], params[1])
 
 
+def test_gradient_slab_pool_equals_fully_pinned_gradients():
+    """Gradient blocks in pageable memory behind 4 recycled pinned slabs (the paper's slab pool) must give
+    the same bytes as the fully pinned layout, with and without the overlapped optimizer."""
+    shape = ModelShape(6, 128, 2, 2, 64, 264, 520)          # 8 gradient blocks > 4 slabs: slabs are recycled
+    params = mt_inputs.make_params(shape, seed=21, std=0.05)
+    tok, lab = mt_inputs.make_batch(shape.vocab, 2, 64, seed=22)
+    la, ga, _ = gpu_step(shape, 2, 64, params, tok, lab)
+    lb, gb, sb = gpu_step(shape, 2, 64, params, tok, lab, flags=mt.FLAG_GRAD_SLABS)
+    assert la == lb
+    for a, b in zip(ga, gb):
+        assert np.array_equal(a, b)
+    pa, pb = [p.copy() for p in params], [p.copy() for p in params]
+    with mt.TrainHandle(make_cfg(shape, 2, 64), pa) as ha, \
+            mt.TrainHandle(make_cfg(shape, 2, 64, flags=mt.FLAG_GRAD_SLABS), pb) as hb:
+        assert hb.stats()["host_pinned_bytes"] < ha.stats()["host_pinned_bytes"]
+        for step in (1, 2):
+            assert ha.train_step_adam(tok, lab, 1e-3, step=step) == hb.train_step_adam(tok, lab, 1e-3, step=step)
+        for i, (a, b) in enumerate(zip(pa, pb)):
+            assert np.array_equal(a, b), i
+            assert np.array_equal(ha.tensor(i), hb.tensor(i))
+
+
 def test_smaller_batch_than_capacity_and_error_paths(orc64):
     shape = ModelShape(2, 128, 2, 2, 64, 264, 520)
     params = mt_inputs.make_params(shape, seed=7, std=0.05)

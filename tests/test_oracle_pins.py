@@ -209,6 +209,19 @@ def test_attention_matches_torch_sdpa_and_its_autograd(orc64):
     assert np.allclose(dv, tv.grad.reshape(B * T, -1).numpy(), rtol=1e-10, atol=1e-13)
 
 
+def test_single_row_attention_matches_torch_sdpa_and_autograd(orc64):
+    rng = np.random.default_rng(21)
+    T, hd = 37, 16
+    q, k, v, da = (rng.standard_normal((T, hd)) for _ in range(4))
+    tq = torch.tensor(q[None, None], requires_grad=True)
+    ta = F.scaled_dot_product_attention(tq, torch.tensor(k[None, None]), torch.tensor(v[None, None]), is_causal=True)
+    ta.backward(torch.tensor(da[None, None]))
+    for t in (0, 1, 17, T - 1):
+        a, dq = orc64.attention_row(q[t], da[t], k[: t + 1], v[: t + 1])
+        assert np.allclose(a, ta[0, 0, t].detach().numpy(), rtol=1e-11, atol=1e-13)
+        assert np.allclose(dq, tq.grad[0, 0, t].numpy(), rtol=1e-10, atol=1e-13)
+
+
 def test_gqa_equals_mha_with_replicated_kv_weights(orc64):
     gqa = ModelShape(1, 16, 4, 2, 8, 24, 20)
     mha = ModelShape(1, 16, 4, 4, 8, 24, 20)
