@@ -95,10 +95,10 @@ __device__ __forceinline__ bf16x8 pack_frag(const f32x16 &v, int cch) {
     return __builtin_bit_cast(bf16x8, u);
 }
 
-__device__ __forceinline__ bf16x8 load_frag_global(const bf16_t *p, bool ok) {
-    uint4 u = {0u, 0u, 0u, 0u};
-    if (ok) u = *reinterpret_cast<const uint4 *>(p);
-    return __builtin_bit_cast(bf16x8, u);
+// Unconditional 16-byte load (callers clamp the row to the last valid one, so the loads of a fragment set
+// are issued back to back instead of one branch per load; rows past the end are never stored).
+__device__ __forceinline__ bf16x8 load_frag_global(const bf16_t *p) {
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p));
 }
 
 __device__ __forceinline__ f32x16 zero16() {
@@ -133,6 +133,20 @@ __device__ __forceinline__ void mfma_tr_accumulate(f32x16 *acc, const bf16_t *ti
     for (int hb = 0; hb < HD / 32; ++hb) acc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[hb], frag, acc[hb], 0, 0, 0);
 }
 
+// Workgroup -> (batch, KV head, item) mapping shared by the three kernels.  Consecutive workgroup ids are
+// dealt round-robin to the 8 XCDs; all workgroups that read the same K/V (or Q/dO) stream are given ids
+// congruent modulo 8 and adjacent in dispatch order, so they run together on one XCD and the stream is
+// fetched into that XCD's L2 once.  per_set = workgroups per (batch, KV head); returns false for the
+// padding workgroups of the last, partial round.
+constexpr int kXcds = 8;
+__device__ __forceinline__ bool decode_block(int per_set, int n_sets, int *set, int *inner) {
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    *set = (slot / per_set) * kXcds + xcd;
+    *inner = slot % per_set;
+    return *set < n_sets;
+}
+inline unsigned grid_blocks(int per_set, int n_sets) { return (unsigned)(((n_sets + kXcds - 1) / kXcds) * kXcds * per_set); }
+
 // ------------------------------------------------------------------ forward
 // grid (q blocks of 32*NW rows, heaviest first; Hq; B); wave w owns 32 queries.  K and V tiles of 64
 // keys go through a double-buffered LDS stage, one barrier per tile.
@@ -142,20 +156,22 @@ __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
     constexpr int STAGE = 2 * 64 * LDK;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
 
-    const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int hk = h / (a.Hq / a.Hkv);
+    const int T = a.T, G = a.Hq / a.Hkv, nqb = (T + BQ - 1) / BQ;
+    int set, inner;
+    if (!decode_block(G * nqb, a.B * a.Hkv, &set, &inner)) return;
+    const int b = set / a.Hkv, hk = set % a.Hkv, h = hk * G + inner / nqb;
+    const int qb = nqb - 1 - inner % nqb;  // heaviest query block first
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
     const int tr_off = tr_lane_offset(lane, LDK);
-    const int T = a.T;
     const int q0 = qb * BQ + wave * 32, q = q0 + l32;
     const bool qok = q < T;
     const int qm = qok ? q : T - 1;  // padded queries behave like the last row; never stored
 
     bf16x8 qf[HD / 16];
     {
-        const bf16_t *qp = a.q + ((int64_t)b * T + q) * a.ldq + (int64_t)h * HD + hl * 8;
+        const bf16_t *qp = a.q + ((int64_t)b * T + qm) * a.ldq + (int64_t)h * HD + hl * 8;
 #pragma unroll
-        for (int ks = 0; ks < HD / 16; ++ks) qf[ks] = load_frag_global(qp + ks * 16, qok);
+        for (int ks = 0; ks < HD / 16; ++ks) qf[ks] = load_frag_global(qp + ks * 16);
     }
     f32x16 oacc[HD / 32];
 #pragma unroll
@@ -271,23 +287,25 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
     constexpr int STAGE = 2 * 64 * LDK;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
 
-    const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int hk = h / (a.Hq / a.Hkv);
+    const int T = a.T, G = a.Hq / a.Hkv, nqb = (T + 127) / 128;
+    int set, inner;
+    if (!decode_block(G * nqb, a.B * a.Hkv, &set, &inner)) return;
+    const int b = set / a.Hkv, hk = set % a.Hkv, h = hk * G + inner / nqb;
+    const int qb = nqb - 1 - inner % nqb;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
     const int tr_off = tr_lane_offset(lane, LDK);
-    const int T = a.T;
     const int q0 = qb * 128 + wave * 32, q = q0 + l32;
     const bool qok = q < T;
     const int qm = qok ? q : T - 1;
 
     bf16x8 qf[HD / 16], dof[HD / 16];
     {
-        const bf16_t *qp = a.q + ((int64_t)b * T + q) * a.ldq + (int64_t)h * HD + hl * 8;
-        const bf16_t *dp = a.dout + ((int64_t)b * T + q) * a.lddo + (int64_t)h * HD + hl * 8;
+        const bf16_t *qp = a.q + ((int64_t)b * T + qm) * a.ldq + (int64_t)h * HD + hl * 8;
+        const bf16_t *dp = a.dout + ((int64_t)b * T + qm) * a.lddo + (int64_t)h * HD + hl * 8;
 #pragma unroll
         for (int ks = 0; ks < HD / 16; ++ks) {
-            qf[ks] = load_frag_global(qp + ks * 16, qok);
-            dof[ks] = load_frag_global(dp + ks * 16, qok);
+            qf[ks] = load_frag_global(qp + ks * 16);
+            dof[ks] = load_frag_global(dp + ks * 16);
         }
     }
     const int64_t stat = ((int64_t)b * a.Hq + h) * T + qm;
@@ -376,22 +394,24 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
     constexpr int STAGE_BF = 2 * 64 * LDK, STAGE = STAGE_BF + 256;  // in bf16 elements
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
 
-    const int kvb = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
-    const int G = a.Hq / a.Hkv;
+    const int T = a.T, G = a.Hq / a.Hkv;
+    int set, kvb;  // key block 0 is the heaviest and comes first
+    if (!decode_block((T + 127) / 128, a.B * a.Hkv, &set, &kvb)) return;
+    const int b = set / a.Hkv, hk = set % a.Hkv;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
     const int tr_off = tr_lane_offset(lane, LDK);
-    const int T = a.T;
     const int kv0w = kvb * 128 + wave * 32, kv = kv0w + l32;
     const bool kvok = kv < T;
 
     bf16x8 kf[HD / 16], vf[HD / 16];
     {
-        const bf16_t *kp = a.k + ((int64_t)b * T + kv) * a.ldk + (int64_t)hk * HD + hl * 8;
-        const bf16_t *vp = a.v + ((int64_t)b * T + kv) * a.ldv + (int64_t)hk * HD + hl * 8;
+        const int kvc = kvok ? kv : T - 1;  // padded keys read the last row; their dK/dV are never stored
+        const bf16_t *kp = a.k + ((int64_t)b * T + kvc) * a.ldk + (int64_t)hk * HD + hl * 8;
+        const bf16_t *vp = a.v + ((int64_t)b * T + kvc) * a.ldv + (int64_t)hk * HD + hl * 8;
 #pragma unroll
         for (int ks = 0; ks < HD / 16; ++ks) {
-            kf[ks] = load_frag_global(kp + ks * 16, kvok);
-            vf[ks] = load_frag_global(vp + ks * 16, kvok);
+            kf[ks] = load_frag_global(kp + ks * 16);
+            vf[ks] = load_frag_global(vp + ks * 16);
         }
     }
     f32x16 dvacc[HD / 32], dkacc[HD / 32];
@@ -493,7 +513,7 @@ bool attn_shape_ok(const AttnArgs &a) {
     if (a.B <= 0 || a.T <= 0 || a.Hq <= 0 || a.Hkv <= 0 || a.Hq % a.Hkv) return false;
     if (a.hd != 64 && a.hd != 128) return false;
     if (a.T & 7) return false;
-    if (a.Hq > 65535 || a.B > 65535) return false;
+    if ((int64_t)a.B * a.Hq * ((a.T + 127) / 128) > (int64_t)1 << 30) return false;
     return true;
 }
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
@@ -513,7 +533,7 @@ hipError_t flash_fwd(const AttnArgs &a, hipStream_t s) {
     if (!attn_shape_ok(a) || (a.ldq & 7) || (a.ldk & 7) || (a.ldv & 7) || (a.ldo & 3)) return hipErrorInvalidValue;
     if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || ((uintptr_t)a.o & 7)) return hipErrorInvalidValue;
     constexpr int NW = 8;
-    const dim3 grid((a.T + 32 * NW - 1) / (32 * NW), a.Hq, a.B);
+    const dim3 grid(grid_blocks((a.Hq / a.Hkv) * ((a.T + 32 * NW - 1) / (32 * NW)), a.B * a.Hkv));
     if (a.hd == 128) {
         constexpr size_t lds = 2 * (2 * 64 * (128 + 8)) * sizeof(bf16_t);
         static bool done = false;
@@ -535,7 +555,7 @@ hipError_t flash_bwd_dq(const AttnArgs &a, hipStream_t s) {
         return hipErrorInvalidValue;
     if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.dout) || ((uintptr_t)a.dq & 7))
         return hipErrorInvalidValue;
-    const dim3 grid((a.T + 127) / 128, a.Hq, a.B);
+    const dim3 grid(grid_blocks((a.Hq / a.Hkv) * ((a.T + 127) / 128), a.B * a.Hkv));
     if (a.hd == 128) {
         constexpr size_t lds = 2 * (2 * 64 * (128 + 8)) * sizeof(bf16_t);
         static bool done = false;
@@ -559,7 +579,7 @@ hipError_t flash_bwd_dkdv(const AttnArgs &a, hipStream_t s) {
     if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.dout) || ((uintptr_t)a.dk & 7) ||
         ((uintptr_t)a.dv & 7))
         return hipErrorInvalidValue;
-    const dim3 grid((a.T + 127) / 128, a.Hkv, a.B);
+    const dim3 grid(grid_blocks((a.T + 127) / 128, a.B * a.Hkv));
     if (a.hd == 128) {
         constexpr size_t lds = 2 * ((2 * 64 * (128 + 8)) * sizeof(bf16_t) + 512);
         static bool done = false;
