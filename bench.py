@@ -29,7 +29,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
-SAMPLE_TOKENS = {"tiny": 256, "1.3B": 256, "7B": 128, "14B": 96, "7B-128k": 128}
+SAMPLE_TOKENS = {"tiny": 256, "1.3B": 2048, "7B": 1024, "14B": 768, "7B-128k": 1024}
 
 
 def mem_available_gb() -> float:

@@ -243,6 +243,219 @@ hipError_t launch(const GemmArgs &g, hipStream_t s) {
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// 4-wave variant for large problems with K % 64 == 0: the same 256 x 256 x 64 tile and LDS layout,
+// but every wave owns a 128 x 128 quadrant (4 x 4 MFMA blocks, 256 accumulators in AGPRs), which
+// halves the LDS bytes read per MFMA, and the whole k-step is software-pipelined inside the wave:
+//   phase p = 0..2 : MFMAs of k-slice p  ||  LDS reads of slice p+1  ||  a third of the staged
+//                    registers of step t+1 written to the other LDS buffer, each register refilled
+//                    at once by the global load of step t+2
+//   barrier        : all waves have read buffer t%2 and written step t+1
+//   phase 3        : MFMAs of slice 3  ||  LDS reads of slice 0 of step t+1
+// so neither the LDS writes nor the global loads ever sit between two MFMAs of one wave.  The
+// barrier is issued without a memory fence: a fence would also wait for the global loads in flight.
+constexpr int W4_BM = 256, W4_BN = 256, W4_NT = 256;
+constexpr int W4_A_BYTES = W4_BM * LDT * 2, W4_STAGE_BYTES = 2 * W4_A_BYTES;
+
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+__global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    constexpr int BM = W4_BM, BN = W4_BN;
+    const int nb = tiles_m * tiles_n;
+    int pid = blockIdx.x;
+    {
+        const int q = nb / kXcd, r = nb % kXcd, x = pid % kXcd;
+        pid = x * q + (x < r ? x : r) + pid / kXcd;
+    }
+    const int group = kGroupM * tiles_n;
+    const int first_m = (pid / group) * kGroupM;
+    const int gsz = min(tiles_m - first_m, kGroupM);
+    const int tm = first_m + (pid % group) % gsz;
+    const int tn = (pid % group) / gsz;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, hl = lane >> 5;
+
+    // loader: thread owns 16-byte chunk (tid & 7) of rows (tid >> 3) + 32 j, j < 8, of A and of B
+    const int lrow = tid >> 3, lkc = (tid & 7) * 8;
+    const bf16_t *abase = g.A + (int64_t)m0 * g.lda;
+    const bf16_t *bbase = g.B + (int64_t)n0 * g.ldb;
+    uint32_t off[16];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        off[j] = (uint32_t)(min(lrow + 32 * j, g.M - 1 - m0) * (int)g.lda + lkc);
+        off[8 + j] = (uint32_t)(min(lrow + 32 * j, g.N - 1 - n0) * (int)g.ldb + lkc);
+    }
+    u32x4 st[16];
+    bf16x8 fr[2][8];   // [set][A block 0..3 | B block 0..3]
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    char *const lds = reinterpret_cast<char *>(smem);
+    const uint32_t wr_off = (uint32_t)((lrow * LDT + lkc) * 2);
+    const uint32_t rda_off = (uint32_t)(((wm * 128 + l32) * LDT + hl * 8) * 2);
+    const uint32_t rdb_off = (uint32_t)(W4_A_BYTES + ((wn * 128 + l32) * LDT + hl * 8) * 2);
+    uint32_t cur = 0;   // byte offset of the LDS buffer holding the current step
+
+#define W4_LOAD(J, K0) st[J] = *reinterpret_cast<const u32x4 *>(((J) < 8 ? abase : bbase) + (K0) + off[J]);
+#define W4_WRITE(J, BUFOFF)                                                                             \
+    *reinterpret_cast<u32x4 *>(lds + (BUFOFF) + wr_off + ((J) < 8 ? 0 : W4_A_BYTES) + ((J) & 7) * 32 * LDT * 2) = st[J];
+#define W4_READ(SET, BUFOFF, KS)                                                                        \
+    {                                                                                                   \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
+            fr[SET][i] = *reinterpret_cast<const bf16x8 *>(lds + (BUFOFF) + rda_off + i * 32 * LDT * 2 + (KS) * 32); \
+            fr[SET][4 + i] = *reinterpret_cast<const bf16x8 *>(lds + (BUFOFF) + rdb_off + i * 32 * LDT * 2 + (KS) * 32); \
+        }                                                                                               \
+    }
+#define W4_MMA(SET)                                                                                     \
+    {                                                                                                   \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                   \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[SET][4 + j], fr[SET][i], acc[i][j], 0, 0, 0); \
+    }
+    // phase P of step kt: chunks [C0, C1) of the staged registers move on
+#define W4_PHASE(P, SET, C0, C1, COMMIT, LOAD)                                                          \
+    {                                                                                                   \
+        W4_READ((SET) ^ 1, cur, (P) + 1);                                                               \
+        _Pragma("unroll") for (int c = C0; c < C1; ++c) {                                               \
+            if (COMMIT) W4_WRITE(c, nxt);                                                               \
+            if (LOAD) W4_LOAD(c, (kt + 2) * BK);                                                        \
+        }                                                                                               \
+        W4_MMA(SET);                                                                                    \
+        _Pragma("unroll") for (int c = 0; c < 8; ++c) {                                                 \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                          \
+        }                                                                                               \
+        _Pragma("unroll") for (int c = C0; c < C1; ++c) {                                               \
+            if (COMMIT) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                              \
+            if (LOAD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                          \
+        }                                                                                               \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8 - ((C1) - (C0)), 0);                              \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+    }
+#define W4_STEP(COMMIT, LOAD)                                                                           \
+    {                                                                                                   \
+        const uint32_t nxt = W4_STAGE_BYTES - cur;                                                      \
+        W4_PHASE(0, 0, 0, 6, COMMIT, LOAD);                                                             \
+        W4_PHASE(1, 1, 6, 11, COMMIT, LOAD);                                                            \
+        W4_PHASE(2, 0, 11, 16, COMMIT, LOAD);                                                           \
+        lds_barrier();                                                                                  \
+        if (COMMIT) W4_READ(0, nxt, 0);                                                                 \
+        W4_MMA(1);                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        cur = nxt;                                                                                      \
+    }
+
+    const int nk = g.K / BK;
+    // prologue: step 0 into LDS buffer 0, step 1 into the staged registers
+#pragma unroll
+    for (int c = 0; c < 16; ++c) W4_LOAD(c, 0);
+#pragma unroll
+    for (int c = 0; c < 16; ++c) W4_WRITE(c, 0);
+    if (nk > 1) {
+#pragma unroll
+        for (int c = 0; c < 16; ++c) W4_LOAD(c, BK);
+    }
+    lds_barrier();
+    W4_READ(0, 0, 0);
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) W4_STEP(true, true);
+    if (kt + 1 < nk) {
+        W4_STEP(true, false);
+        ++kt;
+    }
+    W4_STEP(false, false);
+#undef W4_LOAD
+#undef W4_WRITE
+#undef W4_READ
+#undef W4_MMA
+#undef W4_PHASE
+#undef W4_STEP
+
+    // ---- epilogue.  The MFMAs were issued with the operands swapped (B fragment first), so each
+    // 32x32 block holds C transposed: the lane owns row l32 of the block and, per group q = r/4, the
+    // four consecutive columns 8 q + 4 hl + (0..3): one 8-byte (bf16) or 16-byte (fp32) store each.
+    const int row_l = m0 + wm * 128 + l32, col_l = n0 + wn * 128 + hl * 4;
+    const bool full = (m0 + BM <= g.M) && (n0 + BN <= g.N);
+    const bool vec = full && !(g.ldc & 3) && !((uintptr_t)g.C & 15) && (!g.R || (!(g.ldr & 3) && !((uintptr_t)g.R & 7)));
+    if (g.out_fp32) {
+        float *cw = reinterpret_cast<float *>(g.C);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = row_l + i * 32;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = col_l + j * 32 + q * 8;
+                    float *cp = cw + (int64_t)row * g.ldc + col;
+                    if (vec) {
+                        f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                        if (g.accumulate) v += *reinterpret_cast<const f32x4 *>(cp);
+                        *reinterpret_cast<f32x4 *>(cp) = v;
+                    } else if (row < g.M) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < g.N) cp[e] = acc[i][j][4 * q + e] + (g.accumulate ? cp[e] : 0.f);
+                    }
+                }
+        }
+    } else {
+        bf16_t *cw = reinterpret_cast<bf16_t *>(g.C);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = row_l + i * 32;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = col_l + j * 32 + q * 8;
+                    bf16_t *cp = cw + (int64_t)row * g.ldc + col;
+                    const bf16_t *rp = g.R ? g.R + (int64_t)row * g.ldr + col : nullptr;
+                    if (vec) {
+                        float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2],
+                              v3 = acc[i][j][4 * q + 3];
+                        if (rp) {
+                            const uint2 rv = *reinterpret_cast<const uint2 *>(rp);
+                            v0 += bflo(rv.x); v1 += bfhi(rv.x); v2 += bflo(rv.y); v3 += bfhi(rv.y);
+                        }
+                        uint2 o;
+                        o.x = pack2bf(v0, v1);
+                        o.y = pack2bf(v2, v3);
+                        *reinterpret_cast<uint2 *>(cp) = o;
+                    } else if (row < g.M) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < g.N) cp[e] = f2bf(acc[i][j][4 * q + e] + (rp ? bf2f(rp[e]) : 0.f));
+                    }
+                }
+        }
+    }
+}
+
+hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
+    constexpr size_t lds = (size_t)2 * W4_STAGE_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_w4_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = (g.N + W4_BN - 1) / W4_BN;
+    hipLaunchKernelGGL(gemm_nt_w4_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(W4_NT), lds, s, g, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
 int variant_override() {
     static int v = [] {
         const char *e = getenv("MT_GEMM_VARIANT");
@@ -268,9 +481,10 @@ hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
         case 3: return launch<128, 128, 2, 2>(g, s);
         case 4: return launch<256, 128, 2, 2>(g, s);
         case 5: return launch<256, 128, 4, 2>(g, s);
+        case 6: if (g.K % BK == 0) return launch_w4(g, s); break;
         default: break;
     }
-    if (big_tiles >= 192) return launch<256, 256, 2, 4>(g, s);
+    if (big_tiles >= 192) return (g.K % BK == 0) ? launch_w4(g, s) : launch<256, 256, 2, 4>(g, s);
     return launch<128, 128, 2, 2>(g, s);
 }
 

@@ -62,6 +62,28 @@ def test_gemm_nt_residual_strides_fp32_accumulate(orc64):
     assert rel_l2(host(C32), 2 * ref) < 2e-6
 
 
+@pytest.mark.parametrize("M,N,K", [(4100, 3080, 192), (3840, 3328, 64), (256 * 14, 256 * 14, 320)])
+def test_gemm_large_grid_kernel_all_epilogues(orc64, M, N, K):
+    """Problems with >= 192 tiles of 256 x 256 and K % 64 == 0 take the 4-wave pipelined kernel: ragged
+    and exact edges, odd and even step counts, bf16 with residual and strides, fp32 with accumulate."""
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    lda, ldb, ldc, ldr = K + 8, K + 16, N + 8, N + 24
+    a_full, b_full = bf16_round(rng.standard_normal((M, lda))), bf16_round(rng.standard_normal((N, ldb)))
+    r_full = bf16_round(rng.standard_normal((M, ldr)))
+    ref = orc64.linear_fwd(a_full[:, :K], b_full[:, :K])
+    A, B, R = dev_bf16(a_full), dev_bf16(b_full), dev_bf16(r_full)
+    C = torch.zeros((M, ldc), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_gemm_nt(A.data_ptr(), lda, B.data_ptr(), ldb, C.data_ptr(), ldc, R.data_ptr(), ldr, M, N, K, 0, 0, None))
+    got = host(C)
+    assert rel_l2(got[:, :N], ref + r_full[:, :N]) < BF16_TOL
+    assert np.all(got[:, N:] == 0)
+    C32 = torch.full((M, N), 3.0, dtype=torch.float32, device="cuda")
+    ok(L.mt_k_gemm_nt(A.data_ptr(), lda, B.data_ptr(), ldb, C32.data_ptr(), N, None, 0, M, N, K, 1, 0, None))
+    assert rel_l2(host(C32), ref) < 2e-6
+    ok(L.mt_k_gemm_nt(A.data_ptr(), lda, B.data_ptr(), ldb, C32.data_ptr(), N, None, 0, M, N, K, 1, 1, None))
+    assert rel_l2(host(C32), 2 * ref) < 2e-6
+
+
 def test_gemm_weight_gradient_form_long_reduction(orc64):
     """dW[out,in] = sum_t dy[t,out] x[t,in]: both operands transposed first, fp32 result."""
     rng = np.random.default_rng(2)
