@@ -342,15 +342,33 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
         __builtin_amdgcn_sched_group_barrier(0x008, 8 - ((C1) - (C0)), 0);                              \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
+#define W4_MMA_ROWS(SET, I0, I1)                                                                        \
+    {                                                                                                   \
+        _Pragma("unroll") for (int i = I0; i < I1; ++i)                                                 \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[SET][4 + j], fr[SET][i], acc[i][j], 0, 0, 0); \
+    }
 #define W4_STEP(COMMIT, LOAD)                                                                           \
     {                                                                                                   \
         const uint32_t nxt = W4_STAGE_BYTES - cur;                                                      \
-        W4_PHASE(0, 0, 0, 6, COMMIT, LOAD);                                                             \
-        W4_PHASE(1, 1, 6, 11, COMMIT, LOAD);                                                            \
-        W4_PHASE(2, 0, 11, 16, COMMIT, LOAD);                                                           \
+        W4_PHASE(0, 0, 0, 4, COMMIT, LOAD);                                                             \
+        W4_PHASE(1, 1, 4, 8, COMMIT, LOAD);                                                             \
+        W4_PHASE(2, 0, 8, 12, COMMIT, LOAD);                                                            \
+        _Pragma("unroll") for (int c = 12; c < 16; ++c) {                                               \
+            if (COMMIT) W4_WRITE(c, nxt);                                                               \
+            if (LOAD) W4_LOAD(c, (kt + 2) * BK);                                                        \
+        }                                                                                               \
+        W4_MMA_ROWS(1, 0, 3);                                                                           \
+        _Pragma("unroll") for (int c = 12; c < 16; ++c) {                                               \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                          \
+            if (COMMIT) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                              \
+            if (LOAD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                \
+        }                                                                                               \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
         lds_barrier();                                                                                  \
         if (COMMIT) W4_READ(0, nxt, 0);                                                                 \
-        W4_MMA(1);                                                                                      \
+        W4_MMA_ROWS(1, 3, 4);                                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                              \
         cur = nxt;                                                                                      \
     }
@@ -378,6 +396,7 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
 #undef W4_WRITE
 #undef W4_READ
 #undef W4_MMA
+#undef W4_MMA_ROWS
 #undef W4_PHASE
 #undef W4_STEP
 
