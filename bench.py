@@ -57,14 +57,14 @@ def pick_config(name: str):
 
 
 def cpu_baseline(name: str) -> dict:
-    """The oracle as it stands (fp32 build) on a bounded sample: same layer shapes, one block,
+    """The oracle as it stands (fp32 build) on a bounded sample: same layer shapes, one or two blocks,
     one short sequence; reported in the metric's unit (model TFLOP/s by the same formula)."""
     import mt_inputs
     import oracle
     import paper_2604_05091_amd as mt
     oracle.build()
     shape, _, T = mt_inputs.CONFIGS[name]
-    Ls = 2 if name == "tiny" else 1
+    Ls = 2 if name in ("tiny", "1.3B") else 1
     Ts = min(T, SAMPLE_TOKENS[name])
     Bs = 2 if name == "tiny" else 1
     s1 = replace(shape, n_layers=Ls)
