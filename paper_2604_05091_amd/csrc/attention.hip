@@ -55,6 +55,22 @@ struct TileStage {
             okmask |= (ok ? 1u : 0u) << j;
         }
     }
+    // Rows past rows_valid re-read the last valid row instead of becoming zeros (callers that mask those
+    // rows anyway); no select on the way to LDS, so the values never have to pass through the VALU.
+    __device__ __forceinline__ void fetch_clamped(const bf16_t *src, int64_t ld, int rows_valid) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const int chunk = threadIdx.x + NT * j, r = min(chunk / CPR, rows_valid - 1), c = (chunk % CPR) * 8;
+            v[j] = *reinterpret_cast<const u32x4 *>(src + (int64_t)r * ld + c);
+        }
+    }
+    __device__ __forceinline__ void commit_plain(bf16_t *dst) const {
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const int chunk = threadIdx.x + NT * j, r = chunk / CPR, c = (chunk % CPR) * 8;
+            *reinterpret_cast<u32x4 *>(dst + r * LDP + c) = v[j];
+        }
+    }
     __device__ __forceinline__ void commit(bf16_t *dst) const {
         const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
@@ -357,12 +373,17 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
                         dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv[j], dof[half * 4 + j], dpacc, 0, 0, 0);
                     }
                 }
+                if (diag) {  // wave-uniform: only tiles that touch the diagonal pay for the mask
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kv = kv0 + rb * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
-                    float p = __builtin_amdgcn_exp2f(sacc[r] * c - lse2);
-                    if (diag && kv > qm) p = 0.f;
-                    sacc[r] = p * (dpacc[r] - dlt);  // dS^T
+                    for (int r = 0; r < 16; ++r) {
+                        const int kv = kv0 + rb * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
+                        const float p = kv > qm ? 0.f : __builtin_amdgcn_exp2f(sacc[r] * c - lse2);
+                        sacc[r] = p * (dpacc[r] - dlt);  // dS^T
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        sacc[r] = __builtin_amdgcn_exp2f(sacc[r] * c - lse2) * (dpacc[r] - dlt);
                 }
                 // dQ^T += K^T dS^T
 #pragma unroll
@@ -428,8 +449,9 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
     float stat = 0.f;  // thread < 64: lse * log2e of query (tile row = thread); 64..127: delta
     auto fetch = [&](int it) {
         const int h = hk * G + it / n_qt, q0t = (qt_first + it % n_qt) * 64;
-        stQ.fetch(a.q + ((int64_t)b * T + q0t) * a.ldq + (int64_t)h * HD, a.ldq, T - q0t, HD);
-        stDO.fetch(a.dout + ((int64_t)b * T + q0t) * a.lddo + (int64_t)h * HD, a.lddo, T - q0t, HD);
+        // query rows past T repeat row T-1; the mask below zeroes their P and dS
+        stQ.fetch_clamped(a.q + ((int64_t)b * T + q0t) * a.ldq + (int64_t)h * HD, a.ldq, T - q0t);
+        stDO.fetch_clamped(a.dout + ((int64_t)b * T + q0t) * a.lddo + (int64_t)h * HD, a.lddo, T - q0t);
         if (threadIdx.x < 128) {
             const int qq = q0t + (threadIdx.x & 63);
             const int64_t si = ((int64_t)b * a.Hq + h) * T + (qq < T ? qq : T - 1);
@@ -438,8 +460,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
     };
     auto commit = [&](int buf) {
         bf16_t *st = smem + buf * STAGE;
-        stQ.commit(st);
-        stDO.commit(st + 64 * LDK);
+        stQ.commit_plain(st);
+        stDO.commit_plain(st + 64 * LDK);
         if (threadIdx.x < 128) reinterpret_cast<float *>(st + STAGE_BF)[threadIdx.x] = stat;
     };
     if (total > 0) {
@@ -483,13 +505,22 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
                     const float4 l4 = *reinterpret_cast<const float4 *>(lses + qi);
                     const float4 d4 = *reinterpret_cast<const float4 *>(dlts + qi);
                     const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+                    if (diag) {  // wave-uniform: only tiles on the diagonal or with padded queries pay for the mask
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int r = r4 * 4 + e, qq = q0t + qi + e;
-                        float p = __builtin_amdgcn_exp2f(sacc[r] * c - lv[e]);
-                        if (diag && (kv > qq || qq >= T)) p = 0.f;
-                        pacc[r] = p;
-                        sacc[r] = p * (dpacc[r] - dv4[e]);  // dS
+                        for (int e = 0; e < 4; ++e) {
+                            const int r = r4 * 4 + e, qq = q0t + qi + e;
+                            const float p = (kv > qq || qq >= T) ? 0.f : __builtin_amdgcn_exp2f(sacc[r] * c - lv[e]);
+                            pacc[r] = p;
+                            sacc[r] = p * (dpacc[r] - dv4[e]);  // dS
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int r = r4 * 4 + e;
+                            const float p = __builtin_amdgcn_exp2f(sacc[r] * c - lv[e]);
+                            pacc[r] = p;
+                            sacc[r] = p * (dpacc[r] - dv4[e]);  // dS
+                        }
                     }
                 }
                 // dV^T += dO^T P,  dK^T += Q^T dS
