@@ -147,6 +147,17 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
 mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
                         float *loss);
 
+/* One more micro-batch of the same optimizer step: same as mt_train_step, but every host gradient
+ * tensor ends up holding (previous content + this micro-batch's gradient), one fp32 addition per element
+ * on the host (Section 3.1 keeps "accumulated gradients" in host memory; Appendix A.3: a background
+ * thread folds each returned gradient slab into the master gradient store).  The device-to-host copies
+ * of such a step land in a pool of 4 pinned slabs of the largest unit's size (allocated at the first
+ * call; MT_ERR_HOST_OOM if that fails) and a host thread adds each slab to its gradient block while the
+ * GPU continues.  *loss is this micro-batch's mean loss; no rescaling is applied to either side.
+ * Errors: MT_ERR_STATE before the first mt_train_step; otherwise as mt_train_step. */
+mt_status mt_train_step_accumulate(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch,
+                                   int32_t seq, float *loss);
+
 /* Host Adam with decoupled weight decay on every parameter (Algorithm 1, last line), t = step >= 1:
  *   p <- p (1 - lr wd);  m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
  *   p <- p - lr (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps)

@@ -84,6 +84,7 @@ def lib():
         "mt_adam_step": ([c_void_p, c_float, c_float, c_float, c_float, c_float, c_int64], c_int32),
         "mt_train_step_adam": ([c_void_p, c_void_p, c_void_p, c_int32, c_int32, POINTER(c_float), c_float, c_float,
                                 c_float, c_float, c_float, c_int64], c_int32),
+        "mt_train_step_accumulate": ([c_void_p, c_void_p, c_void_p, c_int32, c_int32, POINTER(c_float)], c_int32),
         "mt_refresh_shadow": ([c_void_p], c_int32),
         "mt_get_tensor": ([c_void_p, c_int32, c_int32, POINTER(c_void_p), POINTER(c_size_t)], c_int32),
         "mt_get_stats": ([c_void_p, POINTER(Stats)], c_int32),
@@ -176,6 +177,15 @@ class TrainHandle:
         loss = c_float()
         check(lib().mt_train_step(self._h, tokens.ctypes.data, labels.ctypes.data, tokens.shape[0], tokens.shape[1],
                                   ctypes.byref(loss)))
+        return loss.value
+
+    def train_step_accumulate(self, tokens: np.ndarray, labels: np.ndarray) -> float:
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        labels = np.ascontiguousarray(labels, dtype=np.int32)
+        assert tokens.shape == labels.shape and tokens.ndim == 2
+        loss = c_float()
+        check(lib().mt_train_step_accumulate(self._h, tokens.ctypes.data, labels.ctypes.data, tokens.shape[0],
+                                             tokens.shape[1], ctypes.byref(loss)))
         return loss.value
 
     def train_step_adam(self, tokens: np.ndarray, labels: np.ndarray, lr, beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0,

@@ -487,10 +487,11 @@ class HostWorker {
         slab_busy_[slab] = 1;
         return true;
     }
-    void push(int r, int unit, int slab) {
+    // add = true: the slab is added to the gradient block instead of replacing it (micro-batch accumulation)
+    void push(int r, int unit, int slab, bool add) {
         {
             std::lock_guard<std::mutex> lk(mu_);
-            q_.push_back({r, unit, slab});
+            q_.push_back({r, unit, slab, add});
         }
         cv_.notify_one();
     }
@@ -511,7 +512,7 @@ class HostWorker {
     bool failed() const { return failed_; }
 
   private:
-    struct Item { int r, unit, slab; };
+    struct Item { int r, unit, slab; bool add; };
     void run() {
         if (hipSetDevice(h_->cfg.device_id) != hipSuccess) set_failed();
         for (;;) {
@@ -535,7 +536,15 @@ class HostWorker {
                 Unit &u = h_->units[item.unit];
                 const char *src = reinterpret_cast<const char *>(h_->slabs[item.slab]);
                 char *dst = reinterpret_cast<char *>(u.h_grad);
-                parallel_for(u.numel * sizeof(float), 1 << 22, [&](size_t b, size_t e) { memcpy(dst + b, src + b, e - b); });
+                if (item.add) {
+                    const float *sf = h_->slabs[item.slab];
+                    float *df = u.h_grad;
+                    parallel_for(u.numel, 1 << 20, [&](size_t b, size_t e) {
+                        for (size_t i = b; i < e; ++i) df[i] += sf[i];
+                    });
+                } else {
+                    parallel_for(u.numel * sizeof(float), 1 << 22, [&](size_t b, size_t e) { memcpy(dst + b, src + b, e - b); });
+                }
                 {
                     std::lock_guard<std::mutex> lk(mu_);
                     slab_busy_[item.slab] = 0;
@@ -566,7 +575,8 @@ class HostWorker {
 };
 
 mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
-                          float *loss, const AdamHyper *opt);
+                          float *loss, const AdamHyper *opt, bool accumulate);
+mt_status ensure_slabs(mt_handle *h);
 
 }  // namespace
 
@@ -870,22 +880,50 @@ mt_status mt_refresh_shadow(mt_handle *h) {
 
 mt_status mt_train_step(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
                         float *loss) {
-    return train_step_core(h, tokens, labels, batch, seq, loss, nullptr);
+    return train_step_core(h, tokens, labels, batch, seq, loss, nullptr, false);
+}
+
+mt_status mt_train_step_accumulate(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch,
+                                   int32_t seq, float *loss) {
+    if (h && !h->have_grads) return fail(MT_ERR_STATE, "mt_train_step_accumulate before the first mt_train_step");
+    return train_step_core(h, tokens, labels, batch, seq, loss, nullptr, true);
 }
 
 mt_status mt_train_step_adam(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
                              float *loss, float lr, float beta1, float beta2, float eps, float wd, int64_t step) {
     if (step < 1) return fail(MT_ERR_INVALID_ARG, "step must be >= 1");
     const AdamHyper hp = {lr, beta1, beta2, eps, wd, step};
-    return train_step_core(h, tokens, labels, batch, seq, loss, &hp);
+    return train_step_core(h, tokens, labels, batch, seq, loss, &hp, false);
 }
 
 }  // extern "C"
 
 namespace {
 
+// The pinned slabs of the gradient pool, allocated on first use (at create in slab mode, at the first
+// accumulating step otherwise).
+mt_status ensure_slabs(mt_handle *h) {
+    if (h->n_slabs > 0) return MT_OK;
+    const size_t bytes = align_up(h->pmax * sizeof(float), 4096);
+    std::vector<float *> v(4, nullptr);
+    for (auto &p : v) {
+        if (hipHostMalloc((void **)&p, bytes, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            for (auto q : v)
+                if (q) (void)hipHostFree(q);
+            return fail(MT_ERR_HOST_OOM, "pinned gradient slab allocation failed");
+        }
+        host_zero(p, bytes);
+    }
+    h->slabs = v;
+    h->n_slabs = 4;
+    h->pinned_bytes += 4 * bytes;
+    h->stats.host_pinned_bytes = h->pinned_bytes;
+    return MT_OK;
+}
+
 mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
-                          float *loss, const AdamHyper *opt) {
+                          float *loss, const AdamHyper *opt, bool accumulate) {
     if (!h || !tokens || !labels || !loss) return fail(MT_ERR_INVALID_ARG, "NULL argument");
     if (batch <= 0 || seq <= 0) return fail(MT_ERR_SHAPE, "batch and seq must be positive");
     const Dims &D = h->D;
@@ -961,7 +999,13 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     std::vector<char> grad_issued(D.L + 2, 0);
     std::unique_ptr<HostWorker> worker;
     const bool apply_opt = opt && !no_copy && !no_kern;
-    if (apply_opt || (h->grad_slabs && !no_copy)) worker.reset(new HostWorker(h, apply_opt ? opt : nullptr));
+    // accumulation needs a host-side add, so the copies of such a step go through the slab pool too
+    const bool use_slabs = (h->grad_slabs || accumulate) && !no_copy;
+    if (use_slabs) {
+        const mt_status es = ensure_slabs(h);
+        if (es != MT_OK) return es;
+    }
+    if (apply_opt || use_slabs) worker.reset(new HostWorker(h, apply_opt ? opt : nullptr));
     auto issue_offload = [&](int r, int u) -> mt_status {
         HIPCHK(hipEventRecord(h->g_ready[r], sc));
         if (no_copy) return MT_OK;
@@ -969,7 +1013,7 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
         HIPCHK(hipEventRecord(h->d2h_start[r], sd));
         int slab = -1;
         float *dst = h->units[u].h_grad;
-        if (h->grad_slabs) {
+        if (use_slabs) {
             // back-pressure of the slab pool: wait (on the host) until the slab's previous content is folded away
             slab = r % h->n_slabs;
             if (!worker->acquire_slab(slab)) return fail(MT_ERR_HIP, "the host worker failed while draining a gradient slab");
@@ -979,7 +1023,7 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
         HIPCHK(hipEventRecord(h->g_free[r], sd));
         grad_issued[r] = 1;
         d2h_bytes += h->units[u].numel * 4;
-        if (worker) worker->push(r, u, slab);
+        if (worker) worker->push(r, u, slab, accumulate);
         if (serial) HIPCHK(hipDeviceSynchronize());
         return MT_OK;
     };

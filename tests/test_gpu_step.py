@@ -146,6 +146,48 @@ def test_gradient_slab_pool_equals_fully_pinned_gradients():
             assert np.array_equal(ha.tensor(i), hb.tensor(i))
 
 
+@pytest.mark.parametrize("flags", [0, mt.FLAG_GRAD_SLABS])
+def test_micro_batch_accumulation_adds_gradients(orc64, flags):
+    """mt_train_step then mt_train_step_accumulate on a second (differently shaped) micro-batch: every
+    gradient tensor is the fp32 sum of the two separately computed gradients, bit for bit, and matches
+    the sum of the oracle's two gradients; Adam afterwards uses the accumulated gradient."""
+    shape = ModelShape(5, 128, 2, 2, 64, 264, 520)           # 7 gradient blocks > 4 slabs
+    params = mt_inputs.make_params(shape, seed=31, std=0.05)
+    t1, l1 = mt_inputs.make_batch(shape.vocab, 2, 64, seed=32)
+    t2, l2 = mt_inputs.make_batch(shape.vocab, 1, 48, seed=33)
+    _, g1, _ = gpu_step(shape, 2, 64, params, t1, l1)
+    loss2, g2, _ = gpu_step(shape, 2, 64, params, t2, l2)
+    ps = [p.copy() for p in params]
+    with mt.TrainHandle(make_cfg(shape, 2, 64, flags=flags), ps) as h:
+        with pytest.raises(mt.MtError) as e:
+            h.train_step_accumulate(t2, l2)
+        assert e.value.status == -8
+        h.train_step(t1, l1)
+        assert h.train_step_accumulate(t2, l2) == loss2
+        acc = [g.copy() for g in h.grads()]
+        for i, (a, x, y) in enumerate(zip(acc, g1, g2)):
+            assert np.array_equal(a, x + y), i
+        ref1 = orc64.train_step(shape, params, t1, l1, mode=1)[1]
+        ref2 = orc64.train_step(shape, params, t2, l2, mode=1)[1]
+        for i, (a, x, y) in enumerate(zip(acc, ref1, ref2)):
+            r = (x + y).ravel()
+            g = a.astype(np.float64).ravel()
+            assert np.dot(g, r) / (np.linalg.norm(g) * np.linalg.norm(r)) > 0.999, i
+            assert np.linalg.norm(g - r) / np.linalg.norm(r) < 3e-2, i
+        # a fresh mt_train_step starts a new window (overwrites)
+        h.train_step(t1, l1)
+        for a, x in zip(h.grads(), g1):
+            assert np.array_equal(a, x)
+        # the optimizer consumes the accumulated gradient
+        h.train_step_accumulate(t2, l2)
+        h.adam_step(1e-3, step=1)
+        for i, (p, p0, g) in enumerate(zip(ps, params, acc)):
+            m = 0.1 * g.astype(np.float64)
+            v = 0.001 * g.astype(np.float64) ** 2
+            want = p0 - 1e-3 * (m / 0.1) / (np.sqrt(v / 0.001) + 1e-8)
+            assert np.max(np.abs(p - want)) < 1e-6, i
+
+
 def test_smaller_batch_than_capacity_and_error_paths(orc64):
     shape = ModelShape(2, 128, 2, 2, 64, 264, 520)
     params = mt_inputs.make_params(shape, seed=7, std=0.05)
