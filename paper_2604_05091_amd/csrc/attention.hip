@@ -22,6 +22,8 @@
 // (ds_read_b64_tr_b16), which hands each lane four consecutive rows of one column; two such
 // reads give exactly the eight reduction indices of the accumulator permutation.
 // dQ and dK/dV are separate kernels: no atomics, results are bit-reproducible.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace mt {
@@ -166,9 +168,19 @@ inline unsigned grid_blocks(int per_set, int n_sets) { return (unsigned)(((n_set
 // ------------------------------------------------------------------ forward
 // grid (q blocks of 32*NW rows, heaviest first; Hq; B); wave w owns 32 queries.  K and V tiles of 64
 // keys go through a double-buffered LDS stage, one barrier per tile.
+#ifndef MT_FWD_PAD
+#define MT_FWD_PAD 40
+#endif
+#ifndef MT_DQ_PAD
+#define MT_DQ_PAD 40
+#endif
+#ifndef MT_DQ_WAVES
+#define MT_DQ_WAVES 8
+#endif
+constexpr int kFwdPad = MT_FWD_PAD, kDqPad = MT_DQ_PAD;
 template <int HD, int NW>
 __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
-    constexpr int LDK = HD + 8, NT = 64 * NW, BQ = 32 * NW;
+    constexpr int LDK = HD + kFwdPad, NT = 64 * NW, BQ = 32 * NW;
     constexpr int STAGE = 2 * 64 * LDK;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
 
@@ -297,20 +309,21 @@ __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
 
 // ------------------------------------------------------------------ backward: dQ
 // Same ownership as the forward: a lane owns one query, loops over key tiles <= q.
-template <int HD>
-__global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
-    constexpr int LDK = HD + 8;
+template <int HD, int NW>
+__global__ __launch_bounds__(64 * NW) void flash_bwd_dq_kernel(AttnArgs a) {
+    constexpr int BQ = 32 * NW, NT = 64 * NW;
+    constexpr int LDK = HD + kDqPad;
     constexpr int STAGE = 2 * 64 * LDK;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
 
-    const int T = a.T, G = a.Hq / a.Hkv, nqb = (T + 127) / 128;
+    const int T = a.T, G = a.Hq / a.Hkv, nqb = (T + BQ - 1) / BQ;
     int set, inner;
     if (!decode_block(G * nqb, a.B * a.Hkv, &set, &inner)) return;
     const int b = set / a.Hkv, hk = set % a.Hkv, h = hk * G + inner / nqb;
     const int qb = nqb - 1 - inner % nqb;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
     const int tr_off = tr_lane_offset(lane, LDK);
-    const int q0 = qb * 128 + wave * 32, q = q0 + l32;
+    const int q0 = qb * BQ + wave * 32, q = q0 + l32;
     const bool qok = q < T;
     const int qm = qok ? q : T - 1;
 
@@ -333,10 +346,10 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(AttnArgs a) {
 
     const bf16_t *kbase = a.k + (int64_t)b * T * a.ldk + (int64_t)hk * HD;
     const bf16_t *vbase = a.v + (int64_t)b * T * a.ldv + (int64_t)hk * HD;
-    const int kv_end = min(T, qb * 128 + 128);
+    const int kv_end = min(T, qb * BQ + BQ);
     const int ntiles = (kv_end + 63) / 64;
 
-    TileStage<64, HD, LDK, 256> stK, stV;
+    TileStage<64, HD, LDK, NT> stK, stV;
     stK.fetch(kbase, a.ldk, T, HD);
     stV.fetch(vbase, a.ldv, T, HD);
     stK.commit(smem);
@@ -540,6 +553,192 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
     }
 }
 
+// ------------------------------------------------------------------ backward: dK, dV, software-pipelined
+// Same ownership and arithmetic as flash_bwd_dkdv_kernel; the work is cut into units u = (query tile,
+// 32-query half) and every wave runs a three-stage pipeline over them so that the matrix cores and the
+// vector ALU work at the same time although only one wave fits on a SIMD:
+//     slot t :   A(t+1)  S = Q K^T, dP = dO V^T          16 MFMAs  -> accumulator set (t+1)&1
+//                B(t)    P = exp2(S c - lse), dS = P (dP - delta), packed to bf16     VALU
+//                C(t-1)  dV^T += dO^T P, dK^T += Q^T dS   16 MFMAs  <- packed set (t-1)&1
+// The three parts of a slot are independent, so the scheduler can issue B's arithmetic between the
+// MFMAs.  Three LDS stages hold the tiles of units t-1 .. t+1; tile j+2 is written during slot 2j+1 into
+// the stage that tile j-1 left at the end of slot 2j.  Slots run from t = -1 to t = U with the same body:
+// LDS and the registers start as zeros, so the parts that fall outside 0 .. U-1 add exact zeros (C) or
+// compute values nobody reads (A, B).  Units a wave has no visible query for are simply fully masked.
+__device__ __forceinline__ void wg_barrier_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+constexpr int kPipePad = 40;
+template <int HD>
+__global__ __launch_bounds__(256) void flash_bwd_dkdv_pipe_kernel(AttnArgs a) {
+    // row pitch HD + 40 elements: consecutive rows are 20 banks apart, which keeps the 16-byte row reads
+    // conflict-free (odd multiple of 4 banks) and lets the four rows of a transposing read overlap in only
+    // 12 of 64 banks (with HD + 8 they pile up on the same 28 banks)
+    constexpr int LDK = HD + kPipePad, KS = HD / 16, HB = HD / 32;
+    constexpr int STAGE_BF = 2 * 64 * LDK, STAGE = STAGE_BF + 256;  // Q, dO (bf16) | lse*log2e[64], delta[64] (fp32)
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+
+    const int T = a.T, G = a.Hq / a.Hkv;
+    int set, kvb;
+    if (!decode_block((T + 127) / 128, a.B * a.Hkv, &set, &kvb)) return;
+    const int b = set / a.Hkv, hk = set % a.Hkv;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int tr_off = tr_lane_offset(lane, LDK);
+    const int kv0w = kvb * 128 + wave * 32, kv = kv0w + l32;
+    const bool kvok = kv < T;
+
+    // zero the three stages: the pipeline's first and last slots read tiles that were never written
+    {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int i = threadIdx.x; i < 3 * STAGE / 8; i += 256) reinterpret_cast<u32x4 *>(smem)[i] = z;
+    }
+
+    bf16x8 kf[KS], vf[KS];
+    {
+        const int kvc = kvok ? kv : T - 1;
+        const bf16_t *kp = a.k + ((int64_t)b * T + kvc) * a.ldk + (int64_t)hk * HD + hl * 8;
+        const bf16_t *vp = a.v + ((int64_t)b * T + kvc) * a.ldv + (int64_t)hk * HD + hl * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = load_frag_global(kp + ks * 16);
+            vf[ks] = load_frag_global(vp + ks * 16);
+        }
+    }
+    f32x16 dvacc[HB], dkacc[HB];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        dvacc[hb] = zero16();
+        dkacc[hb] = zero16();
+    }
+    f32x16 sS[2] = {zero16(), zero16()}, sP[2] = {zero16(), zero16()};  // S and dP of the unit in flight / in use
+    bf16x8 fP[2][2], fS[2][2];                                          // packed P and dS, [set][16-query half]
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            fP[i][j] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+            fS[i][j] = fP[i][j];
+        }
+    const float c = a.scale * kLog2e;
+    const int qt_first = (kvb * 128) / 64, n_qt = (T + 63) / 64 - qt_first;
+    const int total = G * n_qt;
+
+    TileStage<64, HD, LDK, 256> stQ, stDO;
+    float stat = 0.f;
+    // tiles are fetched in order; (f_head, f_tile) is the next one: query head of the group, query tile
+    int f_head = 0, f_tile = 0;
+    auto fetch_next = [&]() {
+        const int h = hk * G + f_head, q0t = (qt_first + f_tile) * 64;
+        if (++f_tile == n_qt) {
+            f_tile = 0;
+            ++f_head;
+        }
+        stQ.fetch_clamped(a.q + ((int64_t)b * T + q0t) * a.ldq + (int64_t)h * HD, a.ldq, T - q0t);
+        stDO.fetch_clamped(a.dout + ((int64_t)b * T + q0t) * a.lddo + (int64_t)h * HD, a.lddo, T - q0t);
+        if (threadIdx.x < 128) {
+            const int qq = q0t + (threadIdx.x & 63);
+            const int64_t si = ((int64_t)b * a.Hq + h) * T + (qq < T ? qq : T - 1);
+            // queries past T: lse = +inf makes their P (and with it dS) exactly zero
+            stat = threadIdx.x < 64 ? (qq < T ? a.lse[si] * kLog2e : INFINITY) : a.delta[si];
+        }
+    };
+    auto commit = [&](int stage) {
+        bf16_t *st = smem + stage * STAGE;
+        stQ.commit_plain(st);
+        stDO.commit_plain(st + 64 * LDK);
+        if (threadIdx.x < 128) reinterpret_cast<float *>(st + STAGE_BF)[threadIdx.x] = stat;
+    };
+    __syncthreads();  // zeros in place before the first tiles land
+    if (total > 0) {
+        fetch_next();
+        commit(0);
+    }
+    if (total > 1) {
+        fetch_next();
+        commit(1);
+    }
+    if (total > 2) fetch_next();
+    __syncthreads();
+
+    // one slot; PAR = t & 1 (compile time); SA / SB / SC = LDS stages of the tiles of units t+1, t, t-1;
+    // QSB = first query of the tile of unit t
+#define DKDV_SLOT(PAR, SA, SB, SC, QSB)                                                                 \
+    {                                                                                                   \
+        constexpr int rbA = 1 - (PAR), rbB = (PAR), rbC = 1 - (PAR);                                    \
+        const bf16_t *QA = smem + (SA) * STAGE, *dOA = QA + 64 * LDK;                                   \
+        const bf16_t *QB = smem + (SB) * STAGE;                                                         \
+        const bf16_t *QC = smem + (SC) * STAGE, *dOC = QC + 64 * LDK;                                   \
+        const float *lses = reinterpret_cast<const float *>(QB + STAGE_BF), *dlts = lses + 64;          \
+        /* ---- B(t): needs S, dP of set PAR */                                                         \
+        {                                                                                               \
+            /* causal mask: key kv sees query q0u + qi + e only if kv <= it, i.e. the element with in-unit  \
+               offset o = r4*8 + e is masked when o < lim (lim <= 0 for units past the diagonal) */            \
+            const int lim = kv - ((QSB) + rbB * 32 + hl * 4);                                           \
+            f32x16 pacc, dsacc;                                                                         \
+            _Pragma("unroll") for (int r4 = 0; r4 < 4; ++r4) {                                          \
+                const int qi = rbB * 32 + r4 * 8 + hl * 4;                                              \
+                const float4 l4 = *reinterpret_cast<const float4 *>(lses + qi);                         \
+                const float4 d4 = *reinterpret_cast<const float4 *>(dlts + qi);                         \
+                const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};        \
+                _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                         \
+                    const int r = r4 * 4 + e;                                                           \
+                    float p = __builtin_amdgcn_exp2f(sS[PAR][r] * c - lv[e]);                           \
+                    p = (r4 * 8 + e < lim) ? 0.f : p;                                                   \
+                    pacc[r] = p;                                                                        \
+                    dsacc[r] = p * (sP[PAR][r] - dv4[e]);                                               \
+                }                                                                                       \
+            }                                                                                           \
+            fP[PAR][0] = pack_frag(pacc, 0);                                                            \
+            fP[PAR][1] = pack_frag(pacc, 1);                                                            \
+            fS[PAR][0] = pack_frag(dsacc, 0);                                                           \
+            fS[PAR][1] = pack_frag(dsacc, 1);                                                           \
+        }                                                                                               \
+        /* ---- A(t+1): S, dP of the next unit into set 1 - PAR */                                      \
+        {                                                                                               \
+            const bf16_t *qr = QA + (rbA * 32 + l32) * LDK + hl * 8;                                    \
+            const bf16_t *dor = dOA + (rbA * 32 + l32) * LDK + hl * 8;                                  \
+            f32x16 s_ = zero16(), p_ = zero16();                                                        \
+            _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                         \
+                const bf16x8 qq8 = *reinterpret_cast<const bf16x8 *>(qr + ks * 16);                     \
+                const bf16x8 dd8 = *reinterpret_cast<const bf16x8 *>(dor + ks * 16);                    \
+                s_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq8, kf[ks], s_, 0, 0, 0);                 \
+                p_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dd8, vf[ks], p_, 0, 0, 0);                 \
+            }                                                                                           \
+            sS[1 - (PAR)] = s_;                                                                         \
+            sP[1 - (PAR)] = p_;                                                                         \
+        }                                                                                               \
+        /* ---- C(t-1): dV, dK from the packed set 1 - PAR */                                           \
+        _Pragma("unroll") for (int cch = 0; cch < 2; ++cch) {                                           \
+            mfma_tr_accumulate<HD, LDK>(dvacc, dOC, tr_off, rbC, cch, fP[1 - (PAR)][cch]);              \
+            mfma_tr_accumulate<HD, LDK>(dkacc, QC, tr_off, rbC, cch, fS[1 - (PAR)][cch]);               \
+        }                                                                                               \
+    }
+    // B's dependence on the set written by the previous slot's A, and C's on the previous slot's B, are the
+    // only links between slots; within a slot the scheduler is free to interleave the three parts.
+    int st_j = 2, st_j1 = 0;   // LDS stages of tiles j and j+1 (tile -1 reads the still-zero stage 2)
+    int tq_j = 0, tq_j1 = 0;   // their query-tile numbers inside the head
+    for (int j = -1; j < total; ++j) {
+        const int st_j2 = st_j1 == 2 ? 0 : st_j1 + 1;
+        // odd slot t = 2j+1: A(2j+2) tile j+1 half 0, B(2j+1) tile j half 1, C(2j) tile j half 0
+        DKDV_SLOT(1, st_j1, st_j, st_j, (qt_first + tq_j) * 64)
+        // tile j+2 goes to the stage tile j-1 left at the end of the previous slot; then tile j+3 is requested
+        if (j >= 0 && j + 2 < total) commit(st_j2);
+        if (j >= 0 && j + 3 < total) fetch_next();
+        wg_barrier_lds();
+        // even slot t = 2j+2: A(2j+3) tile j+1 half 1, B(2j+2) tile j+1 half 0, C(2j+1) tile j half 1
+        DKDV_SLOT(0, st_j1, st_j1, st_j, (qt_first + tq_j1) * 64)
+        wg_barrier_lds();
+        st_j = st_j1;
+        st_j1 = st_j2;
+        tq_j = tq_j1;
+        tq_j1 = tq_j1 + 1 == n_qt ? 0 : tq_j1 + 1;
+    }
+#undef DKDV_SLOT
+    if (kvok) {
+        store_owned_rows<HD>(a.dk + ((int64_t)b * T + kv) * a.lddk + (int64_t)hk * HD, dkacc, a.scale, hl);
+        store_owned_rows<HD>(a.dv + ((int64_t)b * T + kv) * a.lddv + (int64_t)hk * HD, dvacc, 1.0f, hl);
+    }
+}
+
 bool attn_shape_ok(const AttnArgs &a) {
     if (a.B <= 0 || a.T <= 0 || a.Hq <= 0 || a.Hkv <= 0 || a.Hq % a.Hkv) return false;
     if (a.hd != 64 && a.hd != 128) return false;
@@ -566,13 +765,13 @@ hipError_t flash_fwd(const AttnArgs &a, hipStream_t s) {
     constexpr int NW = 8;
     const dim3 grid(grid_blocks((a.Hq / a.Hkv) * ((a.T + 32 * NW - 1) / (32 * NW)), a.B * a.Hkv));
     if (a.hd == 128) {
-        constexpr size_t lds = 2 * (2 * 64 * (128 + 8)) * sizeof(bf16_t);
+        constexpr size_t lds = 2 * (2 * 64 * (128 + kFwdPad)) * sizeof(bf16_t);
         static bool done = false;
         hipError_t e = ensure_lds(&flash_fwd_kernel<128, NW>, lds, &done);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL((flash_fwd_kernel<128, NW>), grid, dim3(64 * NW), lds, s, a);
     } else {
-        constexpr size_t lds = 2 * (2 * 64 * (64 + 8)) * sizeof(bf16_t);
+        constexpr size_t lds = 2 * (2 * 64 * (64 + kFwdPad)) * sizeof(bf16_t);
         static bool done = false;
         hipError_t e = ensure_lds(&flash_fwd_kernel<64, NW>, lds, &done);
         if (e != hipSuccess) return e;
@@ -586,19 +785,20 @@ hipError_t flash_bwd_dq(const AttnArgs &a, hipStream_t s) {
         return hipErrorInvalidValue;
     if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.dout) || ((uintptr_t)a.dq & 7))
         return hipErrorInvalidValue;
-    const dim3 grid(grid_blocks((a.Hq / a.Hkv) * ((a.T + 127) / 128), a.B * a.Hkv));
+    constexpr int NW = MT_DQ_WAVES;
+    const dim3 grid(grid_blocks((a.Hq / a.Hkv) * ((a.T + 32 * NW - 1) / (32 * NW)), a.B * a.Hkv));
     if (a.hd == 128) {
-        constexpr size_t lds = 2 * (2 * 64 * (128 + 8)) * sizeof(bf16_t);
+        constexpr size_t lds = 2 * (2 * 64 * (128 + kDqPad)) * sizeof(bf16_t);
         static bool done = false;
-        hipError_t e = ensure_lds(&flash_bwd_dq_kernel<128>, lds, &done);
+        hipError_t e = ensure_lds(&flash_bwd_dq_kernel<128, NW>, lds, &done);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, dim3(256), lds, s, a);
+        hipLaunchKernelGGL((flash_bwd_dq_kernel<128, NW>), grid, dim3(64 * NW), lds, s, a);
     } else {
-        constexpr size_t lds = 2 * (2 * 64 * (64 + 8)) * sizeof(bf16_t);
+        constexpr size_t lds = 2 * (2 * 64 * (64 + kDqPad)) * sizeof(bf16_t);
         static bool done = false;
-        hipError_t e = ensure_lds(&flash_bwd_dq_kernel<64>, lds, &done);
+        hipError_t e = ensure_lds(&flash_bwd_dq_kernel<64, NW>, lds, &done);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, dim3(256), lds, s, a);
+        hipLaunchKernelGGL((flash_bwd_dq_kernel<64, NW>), grid, dim3(64 * NW), lds, s, a);
     }
     return hipGetLastError();
 }
@@ -611,6 +811,26 @@ hipError_t flash_bwd_dkdv(const AttnArgs &a, hipStream_t s) {
         ((uintptr_t)a.dv & 7))
         return hipErrorInvalidValue;
     const dim3 grid(grid_blocks((a.T + 127) / 128, a.B * a.Hkv));
+    static const bool pipelined = [] {
+        const char *e = getenv("MT_DKDV_PIPE");  // diagnostic: 0 selects the unpipelined kernel
+        return !e || atoi(e) != 0;
+    }();
+    if (pipelined) {
+        if (a.hd == 128) {
+            constexpr size_t lds = 3 * ((2 * 64 * (128 + kPipePad)) * sizeof(bf16_t) + 512);
+            static bool done = false;
+            hipError_t e = ensure_lds(&flash_bwd_dkdv_pipe_kernel<128>, lds, &done);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(flash_bwd_dkdv_pipe_kernel<128>, grid, dim3(256), lds, s, a);
+        } else {
+            constexpr size_t lds = 3 * ((2 * 64 * (64 + kPipePad)) * sizeof(bf16_t) + 512);
+            static bool done = false;
+            hipError_t e = ensure_lds(&flash_bwd_dkdv_pipe_kernel<64>, lds, &done);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(flash_bwd_dkdv_pipe_kernel<64>, grid, dim3(256), lds, s, a);
+        }
+        return hipGetLastError();
+    }
     if (a.hd == 128) {
         constexpr size_t lds = 2 * ((2 * 64 * (128 + 8)) * sizeof(bf16_t) + 512);
         static bool done = false;
