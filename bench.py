@@ -92,6 +92,8 @@ def main() -> int:
     ap.add_argument("--config", default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flags", type=int, default=0, help="extra MT_FLAG_* bits (diagnostics)")
+    ap.add_argument("--ckpt-interval", type=int, default=1,
+                    help="checkpoint interval K of Algorithm 1 (the headline number is quoted at K = 1)")
     ap.add_argument("--separate-adam", action="store_true",
                     help="call mt_train_step then mt_adam_step instead of the overlapped mt_train_step_adam")
     args = ap.parse_args()
@@ -117,7 +119,7 @@ def main() -> int:
     tok, lab = mt_inputs.make_batch(shape.vocab, B, T, seed=1)
     cfg = mt.ModelCfg.make(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
                            shape.vocab, B, T, rope_base=shape.rope_base, rms_eps=shape.rms_eps,
-                           flags=mt.FLAG_KERNEL_TIMING | args.flags)
+                           flags=mt.FLAG_KERNEL_TIMING | args.flags, ckpt_interval=args.ckpt_interval)
     link = mt.link_probe(256 << 20, 4)     # copy-bandwidth probe of this session: the host-link roofline
     h = mt.TrainHandle(cfg, params)
     t_setup = time.time() - t_setup
@@ -200,7 +202,8 @@ def main() -> int:
         "config": {"workload": f"{name}: {shape.n_layers} layers, hidden {shape.hidden}, {shape.n_q_heads}/"
                                f"{shape.n_kv_heads} heads x {shape.head_dim}, ffn {shape.ffn}, vocab {shape.vocab}, "
                                f"batch {B} x seq {T}", "n_params": n_params, "tokens_per_step": B * T,
-                   "host_state": "fp32 master/grad/Adam on host, bf16 streamed weights"},
+                   "host_state": "fp32 master/grad/Adam on host, bf16 streamed weights",
+                   "ckpt_interval": args.ckpt_interval},
         "roofline": roofline,
         "train_step_ms": mean("step_ms"), "adam_step_ms": mean("adam_ms"),
         "train_only_tflops": (flops / (mean("step_ms") * 1e-3) / 1e12) if args.separate_adam else None,

@@ -88,7 +88,9 @@ typedef struct {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
     int32_t max_batch, max_seq; /* the device arena is sized once for max_batch*max_seq tokens */
     float rope_base, rms_eps;
-    int32_t ckpt_interval; /* checkpoint interval K of Algorithm 1; only 1 is implemented */
+    int32_t ckpt_interval; /* checkpoint interval K >= 1 of Algorithm 1 (values above n_layers act as n_layers):
+                            * only h_0, h_K, h_2K, ... stay in device memory; the backward recomputes one block
+                            * of K layers at a time (K activation sets) and streams its weights a third time */
     int32_t device_id;
     uint32_t flags;
     uint32_t reserved;

@@ -505,27 +505,29 @@ void orc_block_backward(real *dx, const real *dy, const real *x, const real *con
 /* ------------------------------------------------------------------ the training step
  * params / grads: 9L+3 arrays in canonical order
  *   0 embed[V,d]; per layer the nine tensors above; final_norm[d]; lm_head[V,d].
- * mode 0 = monolithic (all block caches kept), 1 = streamed (Algorithm 1 with one
- * layer per block: only h_0..h_L kept, each layer recomputed before its backward).
+ * mode 0 = monolithic (all block caches kept); mode K >= 1 = streamed, Algorithm 1 with
+ * checkpoint interval K: after the forward only h_0, h_K, h_2K, ... survive (every other boundary
+ * is overwritten with NaN to prove it is never read again); the backward walks the blocks of K
+ * layers last to first, recomputes a block's forward from its checkpoint (keeping that block's
+ * activations only) and then runs LocalBackward through the block in reverse.
  * Returns 0, or -1 for a token/label outside the vocabulary. */
 int orc_train_step(const orc_cfg *cf, const real *const *params, const int32_t *tokens, const int32_t *labels,
                    int64_t B, int64_t T, real *const *grads, real *loss, int mode) {
     const int64_t L = cf->n_layers, d = cf->hidden, V = cf->vocab, n = B * T;
+    const int64_t K = mode < 1 ? 1 : (mode > L ? (L > 0 ? L : 1) : mode);
     for (int64_t t = 0; t < n; ++t)
         if (tokens[t] < 0 || tokens[t] >= V || labels[t] >= V) return -1;
 
-    /* Phase 1: streaming forward, every block boundary h_i kept (checkpoint interval 1) */
+    /* Phase 1: streaming forward */
     real **h = (real **)malloc(sizeof(real *) * (size_t)(L + 1));
     for (int64_t i = 0; i <= L; ++i) h[i] = ralloc(n * d);
-    block_cache *caches = (block_cache *)calloc((size_t)(L > 0 ? L : 1), sizeof(block_cache));
-    block_cache scratch;
-    if (mode == 0)
-        for (int64_t i = 0; i < L; ++i) cache_alloc(&caches[i], cf, n);
-    cache_alloc(&scratch, cf, n);
+    const int64_t ncache = mode == 0 ? L : K;
+    block_cache *caches = (block_cache *)calloc((size_t)(ncache > 0 ? ncache : 1), sizeof(block_cache));
+    for (int64_t i = 0; i < ncache; ++i) cache_alloc(&caches[i], cf, n);
 
     orc_embed_fwd(h[0], params[0], tokens, n, d);
     for (int64_t i = 0; i < L; ++i)
-        block_forward(h[i + 1], h[i], params + 1 + 9 * i, mode == 0 ? &caches[i] : &scratch, cf, B, T);
+        block_forward(h[i + 1], h[i], params + 1 + 9 * i, mode == 0 ? &caches[i] : &caches[0], cf, B, T);
 
     /* Phase 2: loss anchoring */
     const real *gf = params[1 + 9 * L], *wlm = params[2 + 9 * L];
@@ -540,23 +542,30 @@ int orc_train_step(const orc_cfg *cf, const real *const *params, const int32_t *
 
     /* Phase 3: block-wise backward, last block first */
     real *ydummy = ralloc(n * d);
-    for (int64_t i = L - 1; i >= 0; --i) {
-        const block_cache *c;
-        if (mode == 0) {
-            c = &caches[i];
-        } else {
-            block_forward(ydummy, h[i], params + 1 + 9 * i, &scratch, cf, B, T); /* RecomputeBlock */
-            c = &scratch;
+    if (mode == 0) {
+        for (int64_t i = L - 1; i >= 0; --i) {
+            block_backward(gprev, g, h[i], params + 1 + 9 * i, grads + 1 + 9 * i, &caches[i], cf, B, T);
+            real *sw = g; g = gprev; gprev = sw;
         }
-        block_backward(gprev, g, h[i], params + 1 + 9 * i, grads + 1 + 9 * i, c, cf, B, T);
-        real *sw = g; g = gprev; gprev = sw;
+    } else {
+        /* only the checkpoints are kept on the device */
+        for (int64_t i = 1; i <= L; ++i)
+            if (i % K != 0)
+                for (int64_t e = 0; e < n * d; ++e) h[i][e] = (real)NAN;
+        for (int64_t b = (L - 1) / K; b >= 0 && L > 0; --b) {
+            const int64_t lo = b * K, hi = (lo + K < L ? lo + K : L) - 1; /* layers lo..hi (0-based) */
+            for (int64_t i = lo; i <= hi; ++i) /* RecomputeBlock from the checkpoint h[lo] */
+                block_forward(i < hi ? h[i + 1] : ydummy, h[i], params + 1 + 9 * i, &caches[i - lo], cf, B, T);
+            for (int64_t i = hi; i >= lo; --i) { /* LocalBackward, reverse order */
+                block_backward(gprev, g, h[i], params + 1 + 9 * i, grads + 1 + 9 * i, &caches[i - lo], cf, B, T);
+                real *sw = g; g = gprev; gprev = sw;
+            }
+        }
     }
     orc_embed_bwd(grads[0], g, tokens, n, V, d);
 
     free(ydummy); free(zn); free(logits); free(dlogits); free(dzn); free(g); free(gprev);
-    cache_free(&scratch);
-    if (mode == 0)
-        for (int64_t i = 0; i < L; ++i) cache_free(&caches[i]);
+    for (int64_t i = 0; i < ncache; ++i) cache_free(&caches[i]);
     free(caches);
     for (int64_t i = 0; i <= L; ++i) free(h[i]);
     free(h);

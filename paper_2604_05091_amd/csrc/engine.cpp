@@ -102,7 +102,7 @@ mt_status check_cfg(const mt_model_cfg *c) {
     if ((c->hidden & 7) || (c->ffn & 7) || (c->vocab & 7))
         return fail(MT_ERR_UNSUPPORTED, "hidden, ffn and vocab must be multiples of 8");
     if (c->hidden > 8192) return fail(MT_ERR_UNSUPPORTED, "hidden > 8192 is not supported");
-    if (c->ckpt_interval != 1) return fail(MT_ERR_UNSUPPORTED, "only checkpoint interval 1 is implemented");
+    if (c->ckpt_interval < 1) return fail(MT_ERR_INVALID_ARG, "ckpt_interval must be >= 1");
     if (!(c->rope_base > 0.f) || !(c->rms_eps > 0.f)) return fail(MT_ERR_INVALID_ARG, "rope_base and rms_eps must be > 0");
     return MT_OK;
 }
@@ -169,7 +169,20 @@ struct mt_handle {
     size_t arena_bytes = 0;
     uint16_t *Wbuf[2] = {nullptr, nullptr};
     float *Gbuf[2] = {nullptr, nullptr};
-    std::vector<uint16_t *> anchors;  // h_0..h_L
+    // Block boundaries (Algorithm 1, checkpoint interval K): h_i with i % K == 0 are checkpoints that
+    // live through the step; the other boundaries of the block in flight share K-1 buffers.
+    int K = 1;
+    std::vector<uint16_t *> anchors;  // h_0, h_K, h_2K, ...
+    std::vector<uint16_t *> blk_h;    // h_i, i % K = 1 .. K-1 of the current block
+    uint16_t *boundary(int i) const { return i % K == 0 ? anchors[i / K] : blk_h[i % K - 1]; }
+    // One layer's saved activations; K sets, one per layer of a recomputation block.  xn .. lse below are
+    // the set the kernels currently work on (select_acts).
+    struct ActSet { uint16_t *xn, *yn, *qkv, *att, *h1, *gu, *sact; float *lse; };
+    std::vector<ActSet> acts;
+    void select_acts(int slot) {
+        const ActSet &a = acts[slot];
+        xn = a.xn; yn = a.yn; qkv = a.qkv; att = a.att; h1 = a.h1; gu = a.gu; sact = a.sact; lse = a.lse;
+    }
     uint16_t *xn, *yn, *qkv, *att, *h1, *gu, *sact;
     uint16_t *dsact, *dgu, *dyn, *dh1, *datt, *dqkv, *dxn, *gA, *gB, *tA, *tB, *wT;
     uint16_t *dlogits, *dlT;
@@ -685,17 +698,26 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     const size_t tB_rows = (size_t)std::max<int64_t>(std::max<int64_t>(D.F, D.Nq), D.d);
     const size_t wT_elems = std::max<size_t>(std::max<size_t>((size_t)2 * D.F * D.d, (size_t)D.Nqkv * D.d),
                                             std::max<size_t>((size_t)D.V * D.d, (size_t)D.d * D.Nq));
+    struct ActPlan { size_t xn, yn, qkv, att, h1, gu, sact, lse; };
     struct Plan {
-        size_t W[2], G[2], anchors, xn, yn, qkv, att, h1, gu, sact, dsact, dgu, dyn, dh1, datt, dqkv,
-            dxn, gA, gB, tA, tB, wT, dlogits, dlT, lse, delta, logits, loss_rows, loss_dev, norm_ws, rope_cos, rope_sin,
+        size_t W[2], G[2], anchors, blk_h, dsact, dgu, dyn, dh1, datt, dqkv,
+            dxn, gA, gB, tA, tB, wT, dlogits, dlT, delta, logits, loss_rows, loss_dev, norm_ws, rope_cos, rope_sin,
             tok, lab, rowstart, order;
     } P;
+    const int K = std::min<int>(cfg->ckpt_interval, D.L);
+    h->K = K;
+    const int n_ck = D.L / K + 1;
+    std::vector<ActPlan> AP(K);
     for (int i = 0; i < 2; ++i) P.W[i] = plan(h->pmax * e2);
     for (int i = 0; i < 2; ++i) P.G[i] = plan(h->pmax * e4);
-    P.anchors = plan((size_t)(D.L + 1) * n * D.d * e2);
-    P.xn = plan(n * D.d * e2); P.yn = plan(n * D.d * e2);
-    P.qkv = plan(n * D.Nqkv * e2); P.att = plan(n * D.Nq * e2); P.h1 = plan(n * D.d * e2);
-    P.gu = plan(n * 2 * D.F * e2); P.sact = plan(n * D.F * e2);
+    P.anchors = plan((size_t)n_ck * n * D.d * e2);
+    P.blk_h = plan((size_t)(K - 1) * n * D.d * e2);
+    for (auto &ap : AP) {
+        ap.xn = plan(n * D.d * e2); ap.yn = plan(n * D.d * e2);
+        ap.qkv = plan(n * D.Nqkv * e2); ap.att = plan(n * D.Nq * e2); ap.h1 = plan(n * D.d * e2);
+        ap.gu = plan(n * 2 * D.F * e2); ap.sact = plan(n * D.F * e2);
+        ap.lse = plan((size_t)n * D.Hq * e4);
+    }
     P.dsact = plan(n * D.F * e2); P.dgu = plan(n * 2 * D.F * e2);
     P.dyn = plan(n * D.d * e2); P.dh1 = plan(n * D.d * e2); P.datt = plan(n * D.Nq * e2);
     P.dqkv = plan(n * D.Nqkv * e2); P.dxn = plan(n * D.d * e2);
@@ -703,7 +725,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     P.tA = plan(tA_rows * n * e2); P.tB = plan(tB_rows * n * e2);
     P.wT = plan(wT_elems * e2);
     P.dlogits = plan((size_t)chunk * D.V * e2); P.dlT = plan((size_t)chunk * D.V * e2);
-    P.lse = plan((size_t)n * D.Hq * e4); P.delta = plan((size_t)n * D.Hq * e4);
+    P.delta = plan((size_t)n * D.Hq * e4);
     P.logits = plan((size_t)chunk * D.V * e4);
     P.loss_rows = plan(n * e4); P.loss_dev = plan(256);
     P.norm_ws = plan(rmsnorm_bwd_ws_floats(D.d) * e4);
@@ -747,16 +769,23 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
         h->Wbuf[i] = (uint16_t *)(A + P.W[i]);
         h->Gbuf[i] = (float *)(A + P.G[i]);
     }
-    h->anchors.resize(D.L + 1);
-    for (int i = 0; i <= D.L; ++i) h->anchors[i] = (uint16_t *)(A + P.anchors) + (size_t)i * n * D.d;
-    h->xn = (uint16_t *)(A + P.xn); h->yn = (uint16_t *)(A + P.yn); h->qkv = (uint16_t *)(A + P.qkv);
-    h->att = (uint16_t *)(A + P.att); h->h1 = (uint16_t *)(A + P.h1); h->gu = (uint16_t *)(A + P.gu);
-    h->sact = (uint16_t *)(A + P.sact); h->dsact = (uint16_t *)(A + P.dsact);
+    h->anchors.resize(n_ck);
+    for (int i = 0; i < n_ck; ++i) h->anchors[i] = (uint16_t *)(A + P.anchors) + (size_t)i * n * D.d;
+    h->blk_h.resize(K - 1);
+    for (int i = 0; i < K - 1; ++i) h->blk_h[i] = (uint16_t *)(A + P.blk_h) + (size_t)i * n * D.d;
+    h->acts.resize(K);
+    for (int i = 0; i < K; ++i) {
+        const ActPlan &ap = AP[i];
+        h->acts[i] = {(uint16_t *)(A + ap.xn), (uint16_t *)(A + ap.yn), (uint16_t *)(A + ap.qkv), (uint16_t *)(A + ap.att),
+                      (uint16_t *)(A + ap.h1), (uint16_t *)(A + ap.gu), (uint16_t *)(A + ap.sact), (float *)(A + ap.lse)};
+    }
+    h->select_acts(0);
+    h->dsact = (uint16_t *)(A + P.dsact);
     h->dgu = (uint16_t *)(A + P.dgu); h->dyn = (uint16_t *)(A + P.dyn); h->dh1 = (uint16_t *)(A + P.dh1);
     h->datt = (uint16_t *)(A + P.datt); h->dqkv = (uint16_t *)(A + P.dqkv); h->dxn = (uint16_t *)(A + P.dxn);
     h->gA = (uint16_t *)(A + P.gA); h->gB = (uint16_t *)(A + P.gB); h->tA = (uint16_t *)(A + P.tA);
     h->tB = (uint16_t *)(A + P.tB); h->wT = (uint16_t *)(A + P.wT); h->dlogits = (uint16_t *)(A + P.dlogits);
-    h->dlT = (uint16_t *)(A + P.dlT); h->lse = (float *)(A + P.lse); h->delta = (float *)(A + P.delta);
+    h->dlT = (uint16_t *)(A + P.dlT); h->delta = (float *)(A + P.delta);
     h->logits = (float *)(A + P.logits); h->loss_rows = (float *)(A + P.loss_rows);
     h->loss_dev = (float *)(A + P.loss_dev); h->norm_ws = (float *)(A + P.norm_ws);
     h->rope_cos = (float *)(A + P.rope_cos); h->rope_sin = (float *)(A + P.rope_sin);
@@ -766,7 +795,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     CREATE_HIP(hipStreamCreateWithFlags(&h->s_comp, hipStreamNonBlocking));
     CREATE_HIP(hipStreamCreateWithFlags(&h->s_h2d, hipStreamNonBlocking));
     CREATE_HIP(hipStreamCreateWithFlags(&h->s_d2h, hipStreamNonBlocking));
-    const int nloads = 2 * D.L + 2, ngrads = D.L + 2;
+    const int nloads = 3 * D.L + 2, ngrads = D.L + 2;  // at most three passes over the blocks (K > 1)
     auto make_events = [&](std::vector<hipEvent_t> &v, int cnt) -> hipError_t {
         v.assign(cnt, nullptr);
         for (int i = 0; i < cnt; ++i) {
@@ -967,13 +996,25 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     HIPCHK(hipEventRecord(h->ev_inputs, sh));
     HIPCHK(hipStreamWaitEvent(sc, h->ev_inputs, 0));
 
-    // ---- load schedule: E, 1..L, H, L..1
-    const int nloads = 2 * D.L + 2;
+    // ---- load schedule: E, 1..L, H, then per block of K layers (last block first) the layers in forward
+    // order up to the block's last one (RecomputeBlock) and back down in reverse order (LocalBackward).
+    // The block's last layer is recomputed and differentiated in one slot, so a block of m layers costs
+    // 2m-1 loads; with K = 1 this is the sequence E, 1..L, H, L..1.
+    struct BwdSlot { int layer; bool recompute, backward; };
+    std::vector<BwdSlot> bslots;
+    const int K = h->K;
+    for (int b = (D.L - 1) / K; b >= 0; --b) {
+        const int lo = b * K + 1, hi = std::min((b + 1) * K, D.L);
+        for (int l = lo; l < hi; ++l) bslots.push_back({l, true, false});
+        bslots.push_back({hi, true, true});
+        for (int l = hi - 1; l >= lo; --l) bslots.push_back({l, false, true});
+    }
+    const int nloads = D.L + 2 + (int)bslots.size();
     std::vector<int> load_unit(nloads);
     load_unit[0] = 0;
     for (int l = 1; l <= D.L; ++l) load_unit[l] = l;
     load_unit[D.L + 1] = D.L + 1;
-    for (int i = 0; i < D.L; ++i) load_unit[D.L + 2 + i] = D.L - i;
+    for (size_t i = 0; i < bslots.size(); ++i) load_unit[D.L + 2 + i] = bslots[i].layer;
     std::vector<char> load_issued(nloads, 0);
     h->resident[0] = h->resident[1] = -1;
     uint64_t h2d_bytes = 0, d2h_bytes = 0;
@@ -1058,9 +1099,9 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
         const uint16_t *W = h->Wbuf[s & 1];
         if (!no_kern) {
             if (s == 0) {
-                KCHK(embed_gather(h->anchors[0], W, h->tok_dev, n, D.d, sc));
+                KCHK(embed_gather(h->boundary(0), W, h->tok_dev, n, D.d, sc));
             } else {
-                STEP(layer_forward(h, bind_layer(W, h->lo), h->anchors[s - 1], h->anchors[s], batch, seq));
+                STEP(layer_forward(h, bind_layer(W, h->lo), h->boundary(s - 1), h->boundary(s), batch, seq));
             }
         }
         STEP(end_unit(s));
@@ -1072,25 +1113,31 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
         STEP(issue_load(s + 1));
         STEP(begin_unit(s));
         if (!no_kern)
-            STEP(head_forward_backward(h, h->Wbuf[s & 1], h->Gbuf[0], h->anchors[D.L], gcur, n, inv_n));
+            STEP(head_forward_backward(h, h->Wbuf[s & 1], h->Gbuf[0], h->boundary(D.L), gcur, n, inv_n));
         STEP(end_unit(s));
         STEP(issue_offload(0, D.L + 1));
     }
-    // ---- Phase 3: block-wise backward, one block per recomputation block
-    for (int i = 0; i < D.L; ++i) {
-        const int s = D.L + 2 + i, l = D.L - i, r = 1 + i;
+    // ---- Phase 3: block-wise backward.  Activation set (l - lo) holds layer l of the block in flight.
+    for (size_t i = 0; i < bslots.size(); ++i) {
+        const int s = D.L + 2 + (int)i, l = bslots[i].layer, r = 1 + (D.L - l);
+        const int lo = ((l - 1) / K) * K + 1;
         if (s + 1 < nloads) STEP(issue_load(s + 1));
         STEP(begin_unit(s));
-        STEP(wait_gbuf(r));
+        if (bslots[i].backward) STEP(wait_gbuf(r));
         if (!no_kern) {
             const LayerW w = bind_layer(h->Wbuf[s & 1], h->lo);
-            STEP(layer_forward(h, w, h->anchors[l - 1], nullptr, batch, seq));  // RecomputeBlock
-            STEP(layer_backward(h, w, h->Gbuf[r & 1], h->anchors[l - 1], gcur, gnext, batch, seq));
-            std::swap(gcur, gnext);
+            h->select_acts(l - lo);
+            if (bslots[i].recompute)  // RecomputeBlock: the last layer of a block needs no output
+                STEP(layer_forward(h, w, h->boundary(l - 1), bslots[i].backward ? nullptr : h->boundary(l), batch, seq));
+            if (bslots[i].backward) {
+                STEP(layer_backward(h, w, h->Gbuf[r & 1], h->boundary(l - 1), gcur, gnext, batch, seq));
+                std::swap(gcur, gnext);
+            }
         }
         STEP(end_unit(s));
-        STEP(issue_offload(r, l));
+        if (bslots[i].backward) STEP(issue_offload(r, l));
     }
+    h->select_acts(0);
     // ---- embedding backward (no weights needed), gradient block L+1
     {
         const int r = D.L + 1;

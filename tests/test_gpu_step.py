@@ -188,6 +188,37 @@ def test_micro_batch_accumulation_adds_gradients(orc64, flags):
             assert np.max(np.abs(p - want)) < 1e-6, i
 
 
+def test_checkpoint_interval_k_blocks(orc64):
+    """Algorithm 1 with K layers per recomputation block: same kernels on the same inputs, so the loss and
+    every gradient are bit-identical to K = 1; fewer checkpoints are held, more weight bytes are streamed;
+    the result matches the oracle run with the same interval."""
+    shape = ModelShape(5, 128, 2, 2, 64, 264, 520)
+    params = mt_inputs.make_params(shape, seed=41, std=0.05)
+    tok, lab = mt_inputs.make_batch(shape.vocab, 2, 72, seed=42)
+
+    def run(K, flags=0):
+        ps = [p.copy() for p in params]
+        cfg = make_cfg(shape, 2, 72, flags=flags, ckpt_interval=K)
+        with mt.TrainHandle(cfg, ps) as h:
+            loss = h.train_step(tok, lab)
+            return loss, [g.copy() for g in h.grads()], h.stats()
+
+    l1, g1, s1 = run(1)
+    for K in (2, 3, 5, 9):
+        lk, gk, sk = run(K)
+        assert lk == l1, K
+        for i, (a, b) in enumerate(zip(g1, gk)):
+            assert np.array_equal(a, b), (K, i)
+        assert sk["d2h_bytes"] == s1["d2h_bytes"]
+        assert sk["h2d_bytes"] >= s1["h2d_bytes"]
+    l3, g3, _ = run(3, flags=mt.FLAG_SERIAL)
+    assert l3 == l1 and all(np.array_equal(a, b) for a, b in zip(g1, g3))
+    ref_loss, ref_grads = orc64.train_step(shape, params, tok, lab, mode=3)
+    assert abs(l1 - ref_loss) <= LOSS_RTOL * abs(ref_loss)
+    for g, r in zip(g3, ref_grads):
+        assert cosine(g, r) >= GRAD_COS and rel_l2(g, r) <= GRAD_L2
+
+
 def test_smaller_batch_than_capacity_and_error_paths(orc64):
     shape = ModelShape(2, 128, 2, 2, 64, 264, 520)
     params = mt_inputs.make_params(shape, seed=7, std=0.05)
