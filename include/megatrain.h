@@ -79,6 +79,10 @@ typedef int32_t mt_status;
                                    copies through 4 recycled pinned slabs folded in by a host thread.  Chosen automatically
                                    when pinning every gradient block would exceed the pinned-memory budget (56 GiB, or
                                    MT_PINNED_BUDGET_GB in the environment). */
+#define MT_FLAG_STAGED_WEIGHTS 32u /* no persistent pinned bf16 copy of the weights (Section 3.3, pinned slab recycling): a host
+                                  * thread converts the fp32 master tensors of the unit to be streamed next into one of three
+                                  * pinned slabs of the largest unit's size, just in time; pinned host memory no longer grows
+                                  * with the model.  Results are bit-identical to the default mode. */
 #define MT_FLAG_KERNEL_TIMING 8u /* bracket every GEMM and attention launch with HIP events on the compute
                                    stream and report per-class time, FLOPs and launch counts in mt_stats */
 

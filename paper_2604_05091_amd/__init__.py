@@ -6,5 +6,5 @@ missing or no GPU is present, the calls that need one fail loudly.
 """
 from .binding import (  # noqa: F401
     MtError, ModelCfg, Stats, TrainHandle, lib, lib_path, link_probe, device_count, device_synchronize, model_flops, STATUS_NAMES,
-    FLAG_SERIAL, FLAG_COMPUTE_ONLY, FLAG_COPY_ONLY, FLAG_KERNEL_TIMING, FLAG_GRAD_SLABS,
+    FLAG_SERIAL, FLAG_COMPUTE_ONLY, FLAG_COPY_ONLY, FLAG_KERNEL_TIMING, FLAG_GRAD_SLABS, FLAG_STAGED_WEIGHTS,
 )

@@ -19,6 +19,7 @@ STATUS_NAMES = {0: "MT_OK", -1: "MT_ERR_INVALID_ARG", -2: "MT_ERR_UNSUPPORTED", 
                 -4: "MT_ERR_DEVICE_OOM", -5: "MT_ERR_HIP", -6: "MT_ERR_SHAPE", -7: "MT_ERR_TOKEN_RANGE",
                 -8: "MT_ERR_STATE"}
 FLAG_SERIAL, FLAG_COMPUTE_ONLY, FLAG_COPY_ONLY, FLAG_KERNEL_TIMING, FLAG_GRAD_SLABS = 1, 2, 4, 8, 16
+FLAG_STAGED_WEIGHTS = 32
 KIND_GRAD, KIND_ADAM_M, KIND_ADAM_V = 0, 1, 2
 ABI_VERSION = 1
 

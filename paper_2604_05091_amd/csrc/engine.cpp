@@ -34,6 +34,7 @@
 #include <vector>
 #include <condition_variable>
 #include <deque>
+#include <set>
 #include <mutex>
 #include <thread>
 
@@ -195,6 +196,11 @@ struct mt_handle {
     bool grad_slabs = false;
     int n_slabs = 0;
     std::vector<float *> slabs;
+    // staged weights (Section 3.3, layer-contiguous tiling with pinned slab recycling): no persistent bf16
+    // copy; a host thread converts the fp32 master tensors of the unit to be streamed next into one of a
+    // few pinned slabs of P_max bf16 elements just in time, and the H2D copy reads the slab.
+    bool staged = false;
+    std::vector<uint16_t *> wslabs;
 
     // pinned staging
     int32_t *tok_host = nullptr;  // tokens | labels | row_start | order
@@ -401,6 +407,8 @@ mt_status head_forward_backward(mt_handle *h, const uint16_t *W, float *G, const
 }
 
 void build_shadow(mt_handle *h) {
+    h->resident[0] = h->resident[1] = -1;
+    if (h->staged) return;  // nothing persistent to rebuild: every step converts from the master copy
     for (int i = 0; i < h->n_tensors; ++i) {
         const TensorRef &t = h->tref[i];
         host_f32_to_bf16(h->units[t.unit].h_shadow + t.off, h->params[i], t.numel);
@@ -438,6 +446,8 @@ void free_handle(mt_handle *h) {
     }
     for (auto p : h->slabs)
         if (p) (void)hipHostFree(p);
+    for (auto p : h->wslabs)
+        if (p) (void)hipHostFree(p);
     for (auto p : h->adam_m) free(p);
     for (auto p : h->adam_v) free(p);
     if (h->tok_host) (void)hipHostFree(h->tok_host);
@@ -474,8 +484,8 @@ void adam_unit(mt_handle *h, int unit, const AdamHyper &hp) {
         const TensorRef &t = h->tref[i];
         if (t.unit != unit) continue;
         Unit &u = h->units[unit];
-        host_adam(h->params[i], u.h_grad + t.off, h->adam_m[unit] + t.off, h->adam_v[unit] + t.off, u.h_shadow + t.off,
-                  t.numel, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.wd, hp.step);
+        host_adam(h->params[i], u.h_grad + t.off, h->adam_m[unit] + t.off, h->adam_v[unit] + t.off,
+                  u.h_shadow ? u.h_shadow + t.off : nullptr, t.numel, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.wd, hp.step);
     }
 }
 
@@ -583,6 +593,103 @@ class HostWorker {
     std::deque<Item> q_;
     std::vector<char> slab_busy_;
     bool done_ = false, abort_ = false, failed_ = false;
+    double busy_ms_ = 0;
+    std::thread th_;
+};
+
+// Just-in-time packing of streamed weights (Section 3.3; Appendix A.2): a host thread converts the fp32
+// master tensors of a unit into a pinned bf16 slab while the GPU works on earlier units.  The main thread
+// requests load s (slab = running count of requests modulo the number of slabs), later waits for it,
+// enqueues the host-to-device copy and reports that; before a slab is reused the worker waits for the
+// w_ready event of the load that last read it.
+class PackWorker {
+  public:
+    explicit PackWorker(mt_handle *h) : h_(h), slab_user_(h->wslabs.size(), -1) { th_ = std::thread([this] { run(); }); }
+    ~PackWorker() { finish(); }
+    int request(int s, int unit) {
+        const int slab = (int)(n_req_++ % h_->wslabs.size());
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            q_.push_back({s, unit, slab});
+        }
+        cv_.notify_all();
+        return slab;
+    }
+    bool wait_packed(int s) {
+        std::unique_lock<std::mutex> lk(mu_);
+        cv_.wait(lk, [&] { return packed_.count(s) || failed_; });
+        return !failed_;
+    }
+    void copy_enqueued(int s) {
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            enqueued_.insert(s);
+        }
+        cv_.notify_all();
+    }
+    void finish() {
+        if (!th_.joinable()) return;
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            done_ = true;
+        }
+        cv_.notify_all();
+        th_.join();
+    }
+    double busy_ms() const { return busy_ms_; }
+
+  private:
+    struct Item { int s, unit, slab; };
+    void run() {
+        if (hipSetDevice(h_->cfg.device_id) != hipSuccess) return set_failed();
+        for (;;) {
+            Item it;
+            int prev;
+            {
+                std::unique_lock<std::mutex> lk(mu_);
+                cv_.wait(lk, [this] { return done_ || !q_.empty(); });
+                if (q_.empty()) return;
+                it = q_.front();
+                q_.pop_front();
+                prev = slab_user_[it.slab];
+                // the copy that last read this slab must have been enqueued before its event means anything
+                if (prev >= 0) cv_.wait(lk, [&] { return done_ || enqueued_.count(prev); });
+                if (prev >= 0 && !enqueued_.count(prev)) return;
+                slab_user_[it.slab] = it.s;
+            }
+            if (prev >= 0 && hipEventSynchronize(h_->w_ready[prev]) != hipSuccess) {
+                (void)hipGetLastError();
+                return set_failed();
+            }
+            const double t0 = now_ms();
+            uint16_t *dst = h_->wslabs[it.slab];
+            for (int i = 0; i < h_->n_tensors; ++i) {
+                const TensorRef &t = h_->tref[i];
+                if (t.unit == it.unit) host_f32_to_bf16(dst + t.off, h_->params[i], t.numel);
+            }
+            busy_ms_ += now_ms() - t0;
+            {
+                std::lock_guard<std::mutex> lk(mu_);
+                packed_.insert(it.s);
+            }
+            cv_.notify_all();
+        }
+    }
+    void set_failed() {
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            failed_ = true;
+        }
+        cv_.notify_all();
+    }
+    mt_handle *h_;
+    std::mutex mu_;
+    std::condition_variable cv_;
+    std::deque<Item> q_;
+    std::set<int> packed_, enqueued_;
+    std::vector<int> slab_user_;
+    size_t n_req_ = 0;
+    bool done_ = false, failed_ = false;
     double busy_ms_ = 0;
     std::thread th_;
 };
@@ -819,15 +926,19 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     {
         // Pin every gradient block when that fits the pinned-memory budget; otherwise use the slab pool.
         size_t want = 0;
-        for (auto &u : h->units) want += align_up(u.numel * e2, 4096) + align_up(u.numel * e4, 4096);
+        h->staged = (cfg->flags & MT_FLAG_STAGED_WEIGHTS) != 0;
+        for (auto &u : h->units) want += (h->staged ? 0 : align_up(u.numel * e2, 4096)) + align_up(u.numel * e4, 4096);
         size_t budget = (size_t)56 << 30;
         if (const char *e = getenv("MT_PINNED_BUDGET_GB")) budget = (size_t)atoll(e) << 30;
         h->grad_slabs = (cfg->flags & MT_FLAG_GRAD_SLABS) || want > budget;
         h->n_slabs = h->grad_slabs ? 4 : 0;
     }
     for (auto &u : h->units) {
-        bool ok = hipHostMalloc((void **)&u.h_shadow, align_up(u.numel * e2, 4096), hipHostMallocDefault) == hipSuccess;
-        pinned += align_up(u.numel * e2, 4096);
+        bool ok = true;
+        if (!h->staged) {
+            ok = hipHostMalloc((void **)&u.h_shadow, align_up(u.numel * e2, 4096), hipHostMallocDefault) == hipSuccess;
+            pinned += align_up(u.numel * e2, 4096);
+        }
         if (ok) {
             if (h->grad_slabs) {
                 void *pg = nullptr;
@@ -844,6 +955,19 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
             free_handle(h);
             return fail(MT_ERR_HOST_OOM, "host allocation of a unit's bf16 / gradient block failed (pinned so far: %zu bytes)",
                         pinned);
+        }
+    }
+    if (h->staged) {
+        h->wslabs.assign(3, nullptr);
+        for (auto &p : h->wslabs) {
+            if (hipHostMalloc((void **)&p, align_up(h->pmax * e2, 4096), hipHostMallocDefault) != hipSuccess) {
+                (void)hipGetLastError();
+                p = nullptr;
+                free_handle(h);
+                return fail(MT_ERR_HOST_OOM, "pinned weight staging slab allocation failed");
+            }
+            host_zero(p, align_up(h->pmax * e2, 4096));
+            pinned += align_up(h->pmax * e2, 4096);
         }
     }
     h->slabs.assign(h->n_slabs, nullptr);
@@ -1018,19 +1142,45 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     std::vector<char> load_issued(nloads, 0);
     h->resident[0] = h->resident[1] = -1;
     uint64_t h2d_bytes = 0, d2h_bytes = 0;
+    std::unique_ptr<PackWorker> packer;
+    if (h->staged) packer.reset(new PackWorker(h));
+    std::vector<int> load_slab(nloads, -1);  // staged mode: slab of a requested load
+    // staged mode: ask the packer for load s unless its unit will still be resident in the target buffer
+    auto request_pack = [&](int s) {
+        if (!packer || s >= nloads || load_slab[s] >= 0) return;
+        const int resident_then = s >= 2 ? load_unit[s - 2] : -1;  // loads alternate between the two buffers
+        if (resident_then == load_unit[s]) return;
+        load_slab[s] = packer->request(s, load_unit[s]);
+    };
     if (no_copy) {
         // weights of block 1 in both buffers once, so the kernels see finite numbers
+        const uint16_t *src = h->units[1].h_shadow;
+        if (h->staged) {
+            for (int i = 0; i < h->n_tensors; ++i)
+                if (h->tref[i].unit == 1) host_f32_to_bf16(h->wslabs[0] + h->tref[i].off, h->params[i], h->tref[i].numel);
+            src = h->wslabs[0];
+        }
         for (int b = 0; b < 2; ++b)
-            HIPCHK(hipMemcpyAsync(h->Wbuf[b], h->units[1].h_shadow, h->units[1].numel * 2, hipMemcpyHostToDevice, sc));
+            HIPCHK(hipMemcpyAsync(h->Wbuf[b], src, h->units[1].numel * 2, hipMemcpyHostToDevice, sc));
+        HIPCHK(hipStreamSynchronize(sc));
     }
 
     auto issue_load = [&](int s) -> mt_status {
         const int u = load_unit[s], b = s & 1;
         if (no_copy || h->resident[b] == u) return MT_OK;
+        const uint16_t *src = h->units[u].h_shadow;
+        if (packer) {
+            request_pack(s);
+            request_pack(s + 1);  // one load of lookahead keeps the packer busy while this copy runs
+            if (load_slab[s] < 0 || !packer->wait_packed(s))
+                return fail(MT_ERR_HIP, "the weight packing thread failed before load %d", s);
+            src = h->wslabs[load_slab[s]];
+        }
         if (s >= 2) HIPCHK(hipStreamWaitEvent(sh, h->w_free[s - 2], 0));
         HIPCHK(hipEventRecord(h->h2d_start[s], sh));
-        HIPCHK(hipMemcpyAsync(h->Wbuf[b], h->units[u].h_shadow, h->units[u].numel * 2, hipMemcpyHostToDevice, sh));
+        HIPCHK(hipMemcpyAsync(h->Wbuf[b], src, h->units[u].numel * 2, hipMemcpyHostToDevice, sh));
         HIPCHK(hipEventRecord(h->w_ready[s], sh));
+        if (packer) packer->copy_enqueued(s);
         h->resident[b] = u;
         load_issued[s] = 1;
         h2d_bytes += h->units[u].numel * 2;
@@ -1240,7 +1390,7 @@ mt_status mt_adam_step(mt_handle *h, float lr, float beta1, float beta2, float e
         const TensorRef &t = h->tref[i];
         Unit &u = h->units[t.unit];
         host_adam(h->params[i], u.h_grad + t.off, h->adam_m[t.unit] + t.off, h->adam_v[t.unit] + t.off,
-                  u.h_shadow + t.off, t.numel, lr, beta1, beta2, eps, wd, step);
+                  u.h_shadow ? u.h_shadow + t.off : nullptr, t.numel, lr, beta1, beta2, eps, wd, step);
     }
     h->resident[0] = h->resident[1] = -1;
     h->stats.adam_ms = now_ms() - t0;
