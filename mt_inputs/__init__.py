@@ -52,7 +52,8 @@ def _load():
 
 @dataclass(frozen=True)
 class ModelShape:
-    """Architecture of a decoder-only LM (pre-norm, RMSNorm, RoPE, SwiGLU, no biases, untied head)."""
+    """Architecture of a decoder-only LM (pre-norm, RMSNorm, RoPE, SwiGLU, untied head).  qkv_bias adds a bias
+    vector to the q, k and v projections (three more tensors per layer, after w_down)."""
     n_layers: int
     hidden: int
     n_q_heads: int
@@ -62,6 +63,7 @@ class ModelShape:
     vocab: int
     rope_base: float = 10000.0
     rms_eps: float = 1e-5
+    qkv_bias: bool = False
 
     def dict(self):
         return asdict(self)
@@ -78,7 +80,7 @@ CONFIGS = {
 
 
 def tensor_table(s: ModelShape):
-    """Canonical tensor order: (name, rows, cols) for the 9L+3 parameter tensors.
+    """Canonical tensor order: (name, rows, cols) for the 9L+3 (12L+3 with qkv_bias) parameter tensors.
 
     Matrices are row-major [out_features, in_features]; vectors have cols == 1... no:
     vectors are reported as (rows=n, cols=1).
@@ -90,6 +92,8 @@ def tensor_table(s: ModelShape):
               (f"l{l}.wv", nkv, s.hidden), (f"l{l}.wo", s.hidden, nq), (f"l{l}.mlp_norm", s.hidden, 1),
               (f"l{l}.w_gate", s.ffn, s.hidden), (f"l{l}.w_up", s.ffn, s.hidden),
               (f"l{l}.w_down", s.hidden, s.ffn)]
+        if s.qkv_bias:
+            t += [(f"l{l}.bq", nq, 1), (f"l{l}.bk", nkv, 1), (f"l{l}.bv", nkv, 1)]
     t += [("final_norm", s.hidden, 1), ("lm_head", s.vocab, s.hidden)]
     return t
 

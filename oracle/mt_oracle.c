@@ -47,8 +47,13 @@ typedef REAL real;
 
 typedef struct {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+    int32_t qkv_bias; /* 1: the q, k, v projections carry a bias vector each (Qwen2.5-style layers, the models of
+                         Section 4.1); a layer then has 12 tensors instead of 9: ..., w_down, bq, bk, bv */
     double rope_base, rms_eps;
 } orc_cfg;
+
+/* tensors per layer in the canonical order */
+static int64_t per_layer(const orc_cfg *cf) { return cf->qkv_bias ? 12 : 9; }
 
 int orc_real_bytes(void) { return (int)sizeof(real); }
 
@@ -391,6 +396,21 @@ void orc_adam(real *p, const real *g, real *m, real *v, int64_t n, double lr, do
 
 /* ------------------------------------------------------------------ one transformer block
  * Everything a block's backward needs besides its input x. */
+/* y[t, :] += b  and its gradient  db = sum over rows of dy */
+void orc_bias_add(real *y, const real *b, int64_t n, int64_t out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t)
+        for (int64_t o = 0; o < out; ++o) y[t * out + o] += b[o];
+}
+void orc_bias_bwd(real *db, const real *dy, int64_t n, int64_t out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < out; ++o) {
+        real acc = 0;
+        for (int64_t t = 0; t < n; ++t) acc += dy[t * out + o];
+        db[o] = acc;
+    }
+}
+
 typedef struct {
     real *xn;  /* RMSNorm(x; g1)              [n, d]        */
     real *q;   /* rotated queries             [n, Hq*hd]    */
@@ -430,6 +450,11 @@ static void block_forward(real *y, const real *x, const real *const *w, block_ca
     orc_linear_fwd(c->q, c->xn, w[1], n, d, nq);
     orc_linear_fwd(c->k, c->xn, w[2], n, d, nkv);
     orc_linear_fwd(c->v, c->xn, w[3], n, d, nkv);
+    if (cf->qkv_bias) {
+        orc_bias_add(c->q, w[9], n, nq);
+        orc_bias_add(c->k, w[10], n, nkv);
+        orc_bias_add(c->v, w[11], n, nkv);
+    }
     orc_rope(c->q, B, T, Hq, hd, cf->rope_base, +1);
     orc_rope(c->k, B, T, Hkv, hd, cf->rope_base, +1);
     orc_attention_fwd(c->a, c->q, c->k, c->v, B, T, Hq, Hkv, hd);
@@ -471,6 +496,11 @@ static void block_backward(real *dx, const real *dy, const real *x, const real *
     orc_attention_bwd(dq, dk, dv, da, c->q, c->k, c->v, B, T, Hq, Hkv, hd);
     orc_rope(dq, B, T, Hq, hd, cf->rope_base, -1);
     orc_rope(dk, B, T, Hkv, hd, cf->rope_base, -1);
+    if (cf->qkv_bias) {
+        orc_bias_bwd(gw[9], dq, n, nq);
+        orc_bias_bwd(gw[10], dk, n, nkv);
+        orc_bias_bwd(gw[11], dv, n, nkv);
+    }
     orc_linear_bwd_w(gw[1], dq, c->xn, n, d, nq);
     orc_linear_bwd_w(gw[2], dk, c->xn, n, d, nkv);
     orc_linear_bwd_w(gw[3], dv, c->xn, n, d, nkv);
@@ -514,7 +544,7 @@ void orc_block_backward(real *dx, const real *dy, const real *x, const real *con
 int orc_train_step(const orc_cfg *cf, const real *const *params, const int32_t *tokens, const int32_t *labels,
                    int64_t B, int64_t T, real *const *grads, real *loss, int mode) {
     const int64_t L = cf->n_layers, d = cf->hidden, V = cf->vocab, n = B * T;
-    const int64_t K = mode < 1 ? 1 : (mode > L ? (L > 0 ? L : 1) : mode);
+    const int64_t K = mode < 1 ? 1 : (mode > L ? (L > 0 ? L : 1) : mode), PL = per_layer(cf);
     for (int64_t t = 0; t < n; ++t)
         if (tokens[t] < 0 || tokens[t] >= V || labels[t] >= V) return -1;
 
@@ -527,24 +557,24 @@ int orc_train_step(const orc_cfg *cf, const real *const *params, const int32_t *
 
     orc_embed_fwd(h[0], params[0], tokens, n, d);
     for (int64_t i = 0; i < L; ++i)
-        block_forward(h[i + 1], h[i], params + 1 + 9 * i, mode == 0 ? &caches[i] : &caches[0], cf, B, T);
+        block_forward(h[i + 1], h[i], params + 1 + PL * i, mode == 0 ? &caches[i] : &caches[0], cf, B, T);
 
     /* Phase 2: loss anchoring */
-    const real *gf = params[1 + 9 * L], *wlm = params[2 + 9 * L];
+    const real *gf = params[1 + PL * L], *wlm = params[2 + PL * L];
     real *zn = ralloc(n * d), *logits = ralloc(n * V), *dlogits = ralloc(n * V), *dzn = ralloc(n * d);
     real *g = ralloc(n * d), *gprev = ralloc(n * d);
     orc_rmsnorm_fwd(zn, h[L], gf, n, d, cf->rms_eps);
     orc_linear_fwd(logits, zn, wlm, n, d, V);
     orc_cross_entropy(loss, dlogits, logits, labels, n, V);
-    orc_linear_bwd_w(grads[2 + 9 * L], dlogits, zn, n, d, V);
+    orc_linear_bwd_w(grads[2 + PL * L], dlogits, zn, n, d, V);
     orc_linear_bwd_x(dzn, dlogits, wlm, n, d, V);
-    orc_rmsnorm_bwd(g, grads[1 + 9 * L], dzn, h[L], gf, n, d, cf->rms_eps);
+    orc_rmsnorm_bwd(g, grads[1 + PL * L], dzn, h[L], gf, n, d, cf->rms_eps);
 
     /* Phase 3: block-wise backward, last block first */
     real *ydummy = ralloc(n * d);
     if (mode == 0) {
         for (int64_t i = L - 1; i >= 0; --i) {
-            block_backward(gprev, g, h[i], params + 1 + 9 * i, grads + 1 + 9 * i, &caches[i], cf, B, T);
+            block_backward(gprev, g, h[i], params + 1 + PL * i, grads + 1 + PL * i, &caches[i], cf, B, T);
             real *sw = g; g = gprev; gprev = sw;
         }
     } else {
@@ -555,9 +585,9 @@ int orc_train_step(const orc_cfg *cf, const real *const *params, const int32_t *
         for (int64_t b = (L - 1) / K; b >= 0 && L > 0; --b) {
             const int64_t lo = b * K, hi = (lo + K < L ? lo + K : L) - 1; /* layers lo..hi (0-based) */
             for (int64_t i = lo; i <= hi; ++i) /* RecomputeBlock from the checkpoint h[lo] */
-                block_forward(i < hi ? h[i + 1] : ydummy, h[i], params + 1 + 9 * i, &caches[i - lo], cf, B, T);
+                block_forward(i < hi ? h[i + 1] : ydummy, h[i], params + 1 + PL * i, &caches[i - lo], cf, B, T);
             for (int64_t i = hi; i >= lo; --i) { /* LocalBackward, reverse order */
-                block_backward(gprev, g, h[i], params + 1 + 9 * i, grads + 1 + 9 * i, &caches[i - lo], cf, B, T);
+                block_backward(gprev, g, h[i], params + 1 + PL * i, grads + 1 + PL * i, &caches[i - lo], cf, B, T);
                 real *sw = g; g = gprev; gprev = sw;
             }
         }
@@ -575,7 +605,7 @@ int orc_train_step(const orc_cfg *cf, const real *const *params, const int32_t *
 /* Forward only: loss (and, if logits_out is not NULL, the [n,V] logits). */
 int orc_forward_loss(const orc_cfg *cf, const real *const *params, const int32_t *tokens, const int32_t *labels,
                      int64_t B, int64_t T, real *loss, real *logits_out, real *hL_out) {
-    const int64_t L = cf->n_layers, d = cf->hidden, V = cf->vocab, n = B * T;
+    const int64_t L = cf->n_layers, d = cf->hidden, V = cf->vocab, n = B * T, PL = per_layer(cf);
     for (int64_t t = 0; t < n; ++t)
         if (tokens[t] < 0 || tokens[t] >= V || labels[t] >= V) return -1;
     real *x = ralloc(n * d), *y = ralloc(n * d);
@@ -583,13 +613,13 @@ int orc_forward_loss(const orc_cfg *cf, const real *const *params, const int32_t
     cache_alloc(&scratch, cf, n);
     orc_embed_fwd(x, params[0], tokens, n, d);
     for (int64_t i = 0; i < L; ++i) {
-        block_forward(y, x, params + 1 + 9 * i, &scratch, cf, B, T);
+        block_forward(y, x, params + 1 + PL * i, &scratch, cf, B, T);
         real *sw = x; x = y; y = sw;
     }
     if (hL_out) memcpy(hL_out, x, sizeof(real) * (size_t)(n * d));
     real *zn = ralloc(n * d), *logits = logits_out ? logits_out : ralloc(n * V);
-    orc_rmsnorm_fwd(zn, x, params[1 + 9 * L], n, d, cf->rms_eps);
-    orc_linear_fwd(logits, zn, params[2 + 9 * L], n, d, V);
+    orc_rmsnorm_fwd(zn, x, params[1 + PL * L], n, d, cf->rms_eps);
+    orc_linear_fwd(logits, zn, params[2 + PL * L], n, d, V);
     orc_cross_entropy(loss, NULL, logits, labels, n, V);
     if (!logits_out) free(logits);
     free(zn); free(x); free(y);

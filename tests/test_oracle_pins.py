@@ -13,6 +13,8 @@ import torch
 import torch.nn.functional as F
 
 import mt_inputs
+from dataclasses import replace
+
 from mt_inputs import ModelShape
 
 SMALL_MHA = ModelShape(n_layers=2, hidden=16, n_q_heads=4, n_kv_heads=4, head_dim=8, ffn=24, vocab=32)
@@ -26,6 +28,8 @@ def small_problem(shape, B=2, T=8, seed=3, std=0.3):
     for name, r, c in mt_inputs.tensor_table(shape):
         if name.endswith("norm"):
             params.append(1.0 + 0.2 * rng.standard_normal(r))
+        elif c == 1:
+            params.append(std * rng.standard_normal(r))      # bias vectors
         else:
             params.append(std * rng.standard_normal((r, c)))
     tokens = rng.integers(0, shape.vocab, (B, T)).astype(np.int32)
@@ -34,7 +38,10 @@ def small_problem(shape, B=2, T=8, seed=3, std=0.3):
 
 
 # ----------------------------------------------------------------------------- finite differences
-@pytest.mark.parametrize("shape", [SMALL_MHA, SMALL_GQA], ids=["mha", "gqa"])
+SMALL_GQA_BIAS = replace(SMALL_GQA, qkv_bias=True)
+
+
+@pytest.mark.parametrize("shape", [SMALL_MHA, SMALL_GQA, SMALL_GQA_BIAS], ids=["mha", "gqa", "gqa-bias"])
 def test_backward_matches_central_differences(orc64, shape):
     params, tokens, labels = small_problem(shape)
     loss, grads = orc64.train_step(shape, params, tokens, labels, mode=1)
@@ -76,12 +83,14 @@ def torch_model_loss(shape, tparams, tokens, labels):
         return torch.cat([x1 * cos - x2 * sin, x2 * cos + x1 * sin], dim=-1)
 
     h = F.embedding(tok, tparams[0])
+    pl = 12 if shape.qkv_bias else 9
     for l in range(L):
-        g1, wq, wk, wv, wo, g2, wg, wu, wd = tparams[1 + 9 * l: 10 + 9 * l]
+        g1, wq, wk, wv, wo, g2, wg, wu, wd = tparams[1 + pl * l: 10 + pl * l]
+        bq, bk, bv = tparams[10 + pl * l: 13 + pl * l] if shape.qkv_bias else (None, None, None)
         xn = F.rms_norm(h, (d,), g1, shape.rms_eps)
-        q = rope(F.linear(xn, wq).view(B, T, Hq, hd)).transpose(1, 2)
-        k = rope(F.linear(xn, wk).view(B, T, Hkv, hd)).transpose(1, 2)
-        v = F.linear(xn, wv).view(B, T, Hkv, hd).transpose(1, 2)
+        q = rope(F.linear(xn, wq, bq).view(B, T, Hq, hd)).transpose(1, 2)
+        k = rope(F.linear(xn, wk, bk).view(B, T, Hkv, hd)).transpose(1, 2)
+        v = F.linear(xn, wv, bv).view(B, T, Hkv, hd).transpose(1, 2)
         k = k.repeat_interleave(Hq // Hkv, dim=1)
         v = v.repeat_interleave(Hq // Hkv, dim=1)
         a = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(B, T, Hq * hd)
@@ -92,7 +101,7 @@ def torch_model_loss(shape, tparams, tokens, labels):
     return F.cross_entropy(z.view(B * T, -1), lab.view(-1), ignore_index=-100)
 
 
-@pytest.mark.parametrize("shape", [SMALL_MHA, SMALL_GQA], ids=["mha", "gqa"])
+@pytest.mark.parametrize("shape", [SMALL_MHA, SMALL_GQA, SMALL_GQA_BIAS], ids=["mha", "gqa", "gqa-bias"])
 def test_step_matches_torch_autograd(orc64, shape):
     params, tokens, labels = small_problem(shape, B=3, T=11, seed=5)
     loss, grads = orc64.train_step(shape, params, tokens, labels, mode=1)
