@@ -38,10 +38,15 @@
  *     1 + 9 l + 8       w_down     [hidden, ffn]
  *     1 + 9 L           final_norm [hidden]
  *     2 + 9 L           lm_head    [vocab, hidden]
+ * With cfg.qkv_bias = 1 a layer has 12 tensors (replace 9 by 12 above) and
+ *     1 + 12 l + 9      bq         [n_q_heads*head_dim]
+ *     1 + 12 l + 10     bk         [n_kv_heads*head_dim]
+ *     1 + 12 l + 11     bv         [n_kv_heads*head_dim]
  * The block is pre-norm: RMSNorm -> q,k,v projections -> rotary embedding (pairs
  * (j, j + head_dim/2), angle t * rope_base^(-2j/head_dim)) -> causal softmax attention with
  * scale 1/sqrt(head_dim), query head h reading KV head h / (n_q_heads/n_kv_heads) ->
- * output projection + residual -> RMSNorm -> SwiGLU MLP + residual.  No biases.
+ * output projection + residual -> RMSNorm -> SwiGLU MLP + residual.  No biases, except the optional
+ * q, k, v biases (added before the rotary embedding).
  */
 #ifndef MEGATRAIN_H_
 #define MEGATRAIN_H_
@@ -97,7 +102,8 @@ typedef struct {
                             * of K layers at a time (K activation sets) and streams its weights a third time */
     int32_t device_id;
     uint32_t flags;
-    uint32_t reserved;
+    uint32_t qkv_bias; /* 1: every layer has bias vectors for the q, k and v projections (12 tensors per layer: the 9
+                        * below, then bq, bk, bv); 0: none */
     uint64_t max_device_bytes; /* 0 = no cap; otherwise mt_create fails with MT_ERR_DEVICE_OOM above it */
 } mt_model_cfg;
 
@@ -133,7 +139,7 @@ mt_status mt_tensor_count(const mt_model_cfg *cfg, int32_t *n);
  * thread-local storage valid until the next call on the same thread. */
 mt_status mt_tensor_info(const mt_model_cfg *cfg, int32_t idx, int64_t *rows, int64_t *cols, const char **name);
 
-/* Create a handle.  host_param_ptrs[9L+3] are the caller's fp32 master parameters in
+/* Create a handle.  host_param_ptrs[9L+3] (12L+3 with qkv_bias) are the caller's fp32 master parameters in
  * canonical order (Section 3.1: the host copy is authoritative).  They stay owned by the
  * caller, must outlive the handle, may be pageable memory and are modified only by
  * mt_adam_step.  The library allocates: a pinned bf16 copy of every unit's weights laid out

@@ -35,6 +35,15 @@ int32_t mt_k_gemm_nt(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t 
                      const uint16_t *R, int64_t ldr, int32_t M, int32_t N, int32_t K, int32_t out_fp32,
                      int32_t accumulate, void *stream);
 
+/* C[M,N] bf16 = A . B^T + bias (bias bf16 [N], 8-byte aligned, added to every row before rounding): the q, k, v
+ * projections of layers with biases. */
+int32_t mt_k_gemm_nt_bias(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, uint16_t *C, int64_t ldc,
+                          const uint16_t *bias, int32_t M, int32_t N, int32_t K, void *stream);
+/* db[cols] fp32 (written) = sum over the n rows of x [n, ld] bf16 (the gradient of such a bias); cols % 8 == 0;
+ * ws: device scratch of at least mt_k_bias_grad_ws_bytes(cols) bytes.  Fixed summation order. */
+size_t mt_k_bias_grad_ws_bytes(int32_t cols);
+int32_t mt_k_bias_grad(float *db, const uint16_t *x, int64_t ld, int64_t n, int32_t cols, void *ws, void *stream);
+
 /* out[b0][b1][c][r] = in[b0][b1][r][c], bf16; rows, cols multiples of 8; batch strides in elements. */
 int32_t mt_k_transpose(const uint16_t *in, uint16_t *out, int32_t rows, int32_t cols, int64_t ld_in, int64_t ld_out,
                        int32_t nb0, int32_t nb1, int64_t in_s0, int64_t in_s1, int64_t out_s0, int64_t out_s1,

@@ -36,14 +36,15 @@ class ModelCfg(ctypes.Structure):
                 ("head_dim", c_int32), ("ffn", c_int32), ("vocab", c_int32),
                 ("max_batch", c_int32), ("max_seq", c_int32),
                 ("rope_base", c_float), ("rms_eps", c_float),
-                ("ckpt_interval", c_int32), ("device_id", c_int32), ("flags", c_uint32), ("reserved", c_uint32),
+                ("ckpt_interval", c_int32), ("device_id", c_int32), ("flags", c_uint32), ("qkv_bias", c_uint32),
                 ("max_device_bytes", c_uint64)]
 
     @classmethod
     def make(cls, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, max_batch, max_seq,
-             rope_base=10000.0, rms_eps=1e-5, ckpt_interval=1, device_id=0, flags=0, max_device_bytes=0):
+             rope_base=10000.0, rms_eps=1e-5, ckpt_interval=1, device_id=0, flags=0, max_device_bytes=0, qkv_bias=False):
         return cls(ctypes.sizeof(cls), ABI_VERSION, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab,
-                   max_batch, max_seq, rope_base, rms_eps, ckpt_interval, device_id, flags, 0, max_device_bytes)
+                   max_batch, max_seq, rope_base, rms_eps, ckpt_interval, device_id, flags, int(bool(qkv_bias)),
+                   max_device_bytes)
 
 
 class Stats(ctypes.Structure):
@@ -112,6 +113,9 @@ def lib():
         "mt_k_embed_scatter": ([pf, p16, pi, pi, c_int32, c_int32, c_void_p], c_int32),
         "mt_k_cross_entropy": ([pf, p16, pf, pi, c_int64, c_int32, c_float, c_void_p], c_int32),
         "mt_k_reduce_sum": ([pf, pf, c_int64, c_float, c_int32, c_void_p], c_int32),
+        "mt_k_gemm_nt_bias": ([p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int32, c_int32, c_int32, c_void_p], c_int32),
+        "mt_k_bias_grad_ws_bytes": ([c_int32], c_size_t),
+        "mt_k_bias_grad": ([pf, p16, c_int64, c_int64, c_int32, c_void_p, c_void_p], c_int32),
         "mt_k_flash_fwd": ([p16, c_int64, pf, p16, c_int64, p16, c_int64, p16, c_int64, c_int32, c_int32, c_int32,
                             c_int32, c_int32, c_float, c_void_p], c_int32),
         "mt_k_flash_bwd": ([p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, p16,

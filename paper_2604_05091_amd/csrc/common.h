@@ -44,6 +44,7 @@ __device__ __forceinline__ float wave_max(float v) {
 // C[M,N] = A[M,K] . B[N,K]^T (+ R) ; A, B bf16 with the reduction index contiguous.
 //   out_fp32 = 0: C bf16, optional residual R bf16 [M,N] added before rounding
 //   out_fp32 = 1: C fp32; accumulate = 1 adds to the existing C
+//   bias: optional per-column bf16 vector added before the residual and the rounding (bf16 output only)
 struct GemmArgs {
     const bf16_t *A; int64_t lda;
     const bf16_t *B; int64_t ldb;
@@ -51,6 +52,7 @@ struct GemmArgs {
     const bf16_t *R; int64_t ldr;
     int32_t M, N, K;
     int32_t out_fp32, accumulate;
+    const bf16_t *bias = nullptr;  // optional bf16 [N], added to every row (bf16 output only)
 };
 hipError_t gemm_nt(const GemmArgs &g, hipStream_t s);
 
@@ -91,6 +93,9 @@ hipError_t cross_entropy(float *loss_rows, bf16_t *dlogits, const float *logits,
                          int32_t V, float inv_n, hipStream_t s);
 // out[0] = (accumulate ? out[0] : 0) + scale * sum(in[0..n)) , one block, fixed order
 hipError_t reduce_sum(float *out, const float *in, int64_t n, float scale, int accumulate, hipStream_t s);
+// db[cols] fp32 (written) = sum over the n rows of x [n, ld] bf16; ws: >= bias_grad_ws_floats(cols) floats
+size_t bias_grad_ws_floats(int32_t cols);
+hipError_t bias_grad(float *db, const bf16_t *x, int64_t ld, int64_t n, int32_t cols, float *ws, hipStream_t s);
 
 // Flash attention (causal, grouped KV heads).  q/k/v/o rows are tokens (b*T + t); head h occupies
 // columns [h*hd, (h+1)*hd) from the given base pointer with the given leading dimension.

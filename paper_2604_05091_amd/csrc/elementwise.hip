@@ -191,6 +191,25 @@ __global__ __launch_bounds__(256) void colsum_kernel(float *out, const float *pa
     out[j] = s;
 }
 
+// ------------------------------------------------------------------ bias gradient (column sums of a bf16 matrix)
+// block (bx, by): 16-byte column chunk bx*256 + thread of the rows [by*rpb, (by+1)*rpb) -> partial[by][cols]
+constexpr int kBiasGradRowBlocks = 128;
+__global__ __launch_bounds__(256) void bias_grad_partial_kernel(float *partial, const bf16_t *x, int64_t ld, int64_t n,
+                                                                int cols, int64_t rpb) {
+    const int c = (blockIdx.x * 256 + threadIdx.x) * 8;
+    if (c >= cols) return;
+    const int64_t r0 = (int64_t)blockIdx.y * rpb, r1 = min(n, r0 + rpb);
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int64_t r = r0; r < r1; ++r) {
+        const uint4 u = *reinterpret_cast<const uint4 *>(x + r * ld + c);
+        a[0] += bflo(u.x); a[1] += bfhi(u.x); a[2] += bflo(u.y); a[3] += bfhi(u.y);
+        a[4] += bflo(u.z); a[5] += bfhi(u.z); a[6] += bflo(u.w); a[7] += bfhi(u.w);
+    }
+    float *p = partial + (int64_t)blockIdx.y * cols + c;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p[e] = a[e];
+}
+
 // ------------------------------------------------------------------ rotary embedding
 // thread = (row, head, group of 8 pair indices j); pairs (j, j + hd/2)
 __global__ __launch_bounds__(256) void rope_kernel(bf16_t *x, int64_t ld, int64_t n, int T, int n_heads, int hd,
@@ -441,6 +460,19 @@ hipError_t rmsnorm_bwd(bf16_t *dx_out, float *dgain, const bf16_t *dy, const bf1
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(d, 256)), dim3(256), 0, s, dgain, partial, (int)grid, d);
+    return hipGetLastError();
+}
+
+size_t bias_grad_ws_floats(int32_t cols) { return (size_t)kBiasGradRowBlocks * (size_t)cols; }
+
+hipError_t bias_grad(float *db, const bf16_t *x, int64_t ld, int64_t n, int32_t cols, float *ws, hipStream_t s) {
+    if (n <= 0 || cols <= 0 || (cols & 7) || (ld & 7)) return hipErrorInvalidValue;
+    const int64_t rpb = (n + kBiasGradRowBlocks - 1) / kBiasGradRowBlocks;
+    hipLaunchKernelGGL(bias_grad_partial_kernel, dim3(blocks_for(cols / 8, 256), kBiasGradRowBlocks), dim3(256), 0, s, ws, x,
+                       ld, n, cols, rpb);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(cols, 256)), dim3(256), 0, s, db, ws, kBiasGradRowBlocks, cols);
     return hipGetLastError();
 }
 

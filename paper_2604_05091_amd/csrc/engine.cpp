@@ -70,6 +70,8 @@ double now_ms() {
 struct Dims {
     int L, d, Hq, Hkv, hd, F, V;
     int64_t Nq, Nkv, Nqkv;
+    int bias = 0;  // q, k, v projections carry biases
+    int PL = 9;    // tensors per layer in the canonical order
 };
 
 struct TensorRef {
@@ -86,7 +88,7 @@ struct Unit {
 
 // element offsets inside a block unit
 struct LayerOff {
-    size_t wqkv, wo, wgu, wd, g1, g2, total;
+    size_t wqkv, wo, wgu, wd, g1, g2, bqkv, total;  // bqkv: bq | bk | bv (only with biases)
 };
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -113,6 +115,8 @@ Dims dims_of(const mt_model_cfg *c) {
     D.L = c->n_layers; D.d = c->hidden; D.Hq = c->n_q_heads; D.Hkv = c->n_kv_heads; D.hd = c->head_dim;
     D.F = c->ffn; D.V = c->vocab;
     D.Nq = (int64_t)D.Hq * D.hd; D.Nkv = (int64_t)D.Hkv * D.hd; D.Nqkv = D.Nq + 2 * D.Nkv;
+    D.bias = c->qkv_bias ? 1 : 0;
+    D.PL = D.bias ? 12 : 9;
     return D;
 }
 
@@ -124,12 +128,13 @@ LayerOff layer_off(const Dims &D) {
     o.wd = o.wgu + (size_t)2 * D.F * D.d;
     o.g1 = o.wd + (size_t)D.d * D.F;
     o.g2 = o.g1 + D.d;
-    o.total = o.g2 + D.d;
+    o.bqkv = o.g2 + D.d;
+    o.total = o.bqkv + (D.bias ? (size_t)D.Nqkv : 0);
     return o;
 }
 
 void tensor_shape(const Dims &D, int idx, int64_t *rows, int64_t *cols, std::string *name) {
-    const int n = 9 * D.L + 3;
+    const int n = D.PL * D.L + 3;
     auto set = [&](int64_t r, int64_t c, const std::string &s) {
         *rows = r; *cols = c;
         if (name) *name = s;
@@ -137,7 +142,7 @@ void tensor_shape(const Dims &D, int idx, int64_t *rows, int64_t *cols, std::str
     if (idx == 0) return set(D.V, D.d, "embed");
     if (idx == n - 2) return set(D.d, 1, "final_norm");
     if (idx == n - 1) return set(D.V, D.d, "lm_head");
-    const int l = (idx - 1) / 9, k = (idx - 1) % 9;
+    const int l = (idx - 1) / D.PL, k = (idx - 1) % D.PL;
     const std::string p = "l" + std::to_string(l) + ".";
     switch (k) {
         case 0: return set(D.d, 1, p + "attn_norm");
@@ -148,7 +153,10 @@ void tensor_shape(const Dims &D, int idx, int64_t *rows, int64_t *cols, std::str
         case 5: return set(D.d, 1, p + "mlp_norm");
         case 6: return set(D.F, D.d, p + "w_gate");
         case 7: return set(D.F, D.d, p + "w_up");
-        default: return set(D.d, D.F, p + "w_down");
+        case 8: return set(D.d, D.F, p + "w_down");
+        case 9: return set(D.Nq, 1, p + "bq");
+        case 10: return set(D.Nkv, 1, p + "bk");
+        default: return set(D.Nkv, 1, p + "bv");
     }
 }
 
@@ -187,7 +195,7 @@ struct mt_handle {
     uint16_t *xn, *yn, *qkv, *att, *h1, *gu, *sact;
     uint16_t *dsact, *dgu, *dyn, *dh1, *datt, *dqkv, *dxn, *gA, *gB, *tA, *tB, *wT;
     uint16_t *dlogits, *dlT;
-    float *lse, *delta, *logits, *loss_rows, *loss_dev, *norm_ws, *rope_cos, *rope_sin;
+    float *lse, *delta, *logits, *loss_rows, *loss_dev, *norm_ws, *bias_ws, *rope_cos, *rope_sin;
     int32_t *tok_dev, *lab_dev, *rowstart_dev, *order_dev;
     int64_t ce_chunk = 0;
     // gradient slab pool (Section 3.3 / Appendix A.3): when the fp32 gradient blocks cannot all be pinned,
@@ -258,22 +266,23 @@ struct Timed {
 
 hipError_t gemm_raw(hipStream_t s, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, void *C, int64_t ldc,
                 int64_t M, int64_t N, int64_t K, bool out_fp32 = false, bool accumulate = false,
-                const uint16_t *R = nullptr, int64_t ldr = 0) {
+                const uint16_t *R = nullptr, int64_t ldr = 0, const uint16_t *bias = nullptr) {
     GemmArgs g;
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.R = R; g.ldr = ldr;
     g.M = (int32_t)M; g.N = (int32_t)N; g.K = (int32_t)K;
     g.out_fp32 = out_fp32; g.accumulate = accumulate;
+    g.bias = bias;
     return gemm_nt(g, s);
 }
 
 hipError_t gemm(mt_handle *h, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, void *C, int64_t ldc,
                 int64_t M, int64_t N, int64_t K, bool out_fp32 = false, bool accumulate = false,
-                const uint16_t *R = nullptr, int64_t ldr = 0) {
+                const uint16_t *R = nullptr, int64_t ldr = 0, const uint16_t *bias = nullptr) {
     // algorithmic bytes: both operands once, the result once (plus the residual / the accumulated-into result read)
     const double out_b = out_fp32 ? 4.0 : 2.0;
     const double bytes = 2.0 * ((double)M * K + (double)N * K) + (double)M * N * (out_b + (R ? 2.0 : 0.0) + (accumulate ? 4.0 : 0.0));
     Timed t(h, CLS_GEMM, 2.0 * (double)M * (double)N * (double)K, bytes);
-    return gemm_raw(h->s_comp, A, lda, B, ldb, C, ldc, M, N, K, out_fp32, accumulate, R, ldr);
+    return gemm_raw(h->s_comp, A, lda, B, ldb, C, ldc, M, N, K, out_fp32, accumulate, R, ldr, bias);
 }
 
 // out[cols, rows] = in[rows, cols]^T
@@ -286,10 +295,11 @@ hipError_t transpose2d(hipStream_t s, const uint16_t *in, uint16_t *out, int64_t
 }
 
 struct LayerW {
-    const uint16_t *wqkv, *wo, *wgu, *wd, *g1, *g2;
+    const uint16_t *wqkv, *wo, *wgu, *wd, *g1, *g2, *bqkv;  // bqkv = NULL without biases
 };
 LayerW bind_layer(const uint16_t *base, const LayerOff &o) {
-    return {base + o.wqkv, base + o.wo, base + o.wgu, base + o.wd, base + o.g1, base + o.g2};
+    return {base + o.wqkv, base + o.wo, base + o.wgu, base + o.wd, base + o.g1, base + o.g2,
+            o.total > o.bqkv ? base + o.bqkv : nullptr};
 }
 
 AttnArgs attn_args(const mt_handle *h, int B, int T) {
@@ -317,7 +327,7 @@ mt_status layer_forward(mt_handle *h, const LayerW &w, const uint16_t *x, uint16
     const int64_t n = (int64_t)B * T;
     hipStream_t s = h->s_comp;
     KCHK(rmsnorm_fwd(h->xn, x, w.g1, n, D.d, h->cfg.rms_eps, s));
-    KCHK(gemm(h, h->xn, D.d, w.wqkv, D.d, h->qkv, D.Nqkv, n, D.Nqkv, D.d));
+    KCHK(gemm(h, h->xn, D.d, w.wqkv, D.d, h->qkv, D.Nqkv, n, D.Nqkv, D.d, false, false, nullptr, 0, w.bqkv));
     KCHK(rope_inplace(h->qkv, D.Nqkv, n, T, D.Hq + D.Hkv, D.hd, h->rope_cos, h->rope_sin, +1, s));
     const AttnArgs a = attn_args(h, B, T);
     {
@@ -372,7 +382,8 @@ mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t
         KCHK(flash_bwd_dq(a, s));
     }
     KCHK(rope_inplace(h->dqkv, D.Nqkv, n, T, D.Hq + D.Hkv, D.hd, h->rope_cos, h->rope_sin, -1, s));
-    // qkv = xn Wqkv^T
+    if (D.bias) KCHK(bias_grad(G + o.bqkv, h->dqkv, D.Nqkv, n, (int32_t)D.Nqkv, h->bias_ws, s));
+    // qkv = xn Wqkv^T + b
     KCHK(transpose2d(s, h->dqkv, h->tA, n, D.Nqkv, D.Nqkv, n));
     KCHK(transpose2d(s, h->xn, h->tB, n, D.d, D.d, n));
     KCHK(gemm(h, h->tA, n, h->tB, n, G + o.wqkv, D.d, D.Nqkv, D.d, n, true));
@@ -708,13 +719,14 @@ const char *mt_last_error(void) { return g_err; }
 mt_status mt_tensor_count(const mt_model_cfg *cfg, int32_t *n) {
     if (!cfg || !n) return fail(MT_ERR_INVALID_ARG, "NULL argument");
     if (cfg->n_layers <= 0) return fail(MT_ERR_INVALID_ARG, "n_layers must be positive");
-    *n = 9 * cfg->n_layers + 3;
+    *n = (cfg->qkv_bias ? 12 : 9) * cfg->n_layers + 3;
     return MT_OK;
 }
 
 mt_status mt_tensor_info(const mt_model_cfg *cfg, int32_t idx, int64_t *rows, int64_t *cols, const char **name) {
     if (!cfg || !rows || !cols) return fail(MT_ERR_INVALID_ARG, "NULL argument");
-    if (cfg->n_layers <= 0 || idx < 0 || idx >= 9 * cfg->n_layers + 3) return fail(MT_ERR_INVALID_ARG, "tensor index out of range");
+    if (cfg->n_layers <= 0 || idx < 0 || idx >= (cfg->qkv_bias ? 12 : 9) * cfg->n_layers + 3)
+        return fail(MT_ERR_INVALID_ARG, "tensor index out of range");
     static thread_local std::string nm;
     const Dims D = dims_of(cfg);
     tensor_shape(D, idx, rows, cols, &nm);
@@ -745,7 +757,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     if (cfg->max_batch <= 0 || cfg->max_seq <= 0) return fail(MT_ERR_INVALID_ARG, "max_batch and max_seq must be positive");
     if (cfg->max_seq & 7) return fail(MT_ERR_UNSUPPORTED, "max_seq must be a multiple of 8");
     const Dims D = dims_of(cfg);
-    const int nt = 9 * D.L + 3;
+    const int nt = D.PL * D.L + 3;
     for (int i = 0; i < nt; ++i)
         if (!host_param_ptrs[i]) return fail(MT_ERR_INVALID_ARG, "host_param_ptrs[%d] is NULL", i);
     const int64_t n = (int64_t)cfg->max_batch * cfg->max_seq;
@@ -769,7 +781,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     h->tref.resize(nt);
     h->tref[0] = {0, 0, (size_t)D.V * D.d};
     for (int l = 0; l < D.L; ++l) {
-        const int u = l + 1, b = 1 + 9 * l;
+        const int u = l + 1, b = 1 + D.PL * l;
         const LayerOff &o = h->lo;
         h->tref[b + 0] = {u, o.g1, (size_t)D.d};
         h->tref[b + 1] = {u, o.wqkv, (size_t)D.Nq * D.d};
@@ -780,6 +792,11 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
         h->tref[b + 6] = {u, o.wgu, (size_t)D.F * D.d};
         h->tref[b + 7] = {u, o.wgu + (size_t)D.F * D.d, (size_t)D.F * D.d};
         h->tref[b + 8] = {u, o.wd, (size_t)D.d * D.F};
+        if (D.bias) {
+            h->tref[b + 9] = {u, o.bqkv, (size_t)D.Nq};
+            h->tref[b + 10] = {u, o.bqkv + (size_t)D.Nq, (size_t)D.Nkv};
+            h->tref[b + 11] = {u, o.bqkv + (size_t)(D.Nq + D.Nkv), (size_t)D.Nkv};
+        }
     }
     h->tref[nt - 2] = {D.L + 1, (size_t)D.V * D.d, (size_t)D.d};
     h->tref[nt - 1] = {D.L + 1, 0, (size_t)D.V * D.d};
@@ -808,7 +825,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     struct ActPlan { size_t xn, yn, qkv, att, h1, gu, sact, lse; };
     struct Plan {
         size_t W[2], G[2], anchors, blk_h, dsact, dgu, dyn, dh1, datt, dqkv,
-            dxn, gA, gB, tA, tB, wT, dlogits, dlT, delta, logits, loss_rows, loss_dev, norm_ws, rope_cos, rope_sin,
+            dxn, gA, gB, tA, tB, wT, dlogits, dlT, delta, logits, loss_rows, loss_dev, norm_ws, bias_ws, rope_cos, rope_sin,
             tok, lab, rowstart, order;
     } P;
     const int K = std::min<int>(cfg->ckpt_interval, D.L);
@@ -836,6 +853,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     P.logits = plan((size_t)chunk * D.V * e4);
     P.loss_rows = plan(n * e4); P.loss_dev = plan(256);
     P.norm_ws = plan(rmsnorm_bwd_ws_floats(D.d) * e4);
+    P.bias_ws = plan(D.bias ? bias_grad_ws_floats((int32_t)D.Nqkv) * e4 : 0);
     P.rope_cos = plan((size_t)cfg->max_seq * (D.hd / 2) * e4);
     P.rope_sin = plan((size_t)cfg->max_seq * (D.hd / 2) * e4);
     P.tok = plan(n * 4); P.lab = plan(n * 4); P.rowstart = plan(((size_t)D.V + 1) * 4); P.order = plan(n * 4);
@@ -895,6 +913,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     h->dlT = (uint16_t *)(A + P.dlT); h->delta = (float *)(A + P.delta);
     h->logits = (float *)(A + P.logits); h->loss_rows = (float *)(A + P.loss_rows);
     h->loss_dev = (float *)(A + P.loss_dev); h->norm_ws = (float *)(A + P.norm_ws);
+    h->bias_ws = (float *)(A + P.bias_ws);
     h->rope_cos = (float *)(A + P.rope_cos); h->rope_sin = (float *)(A + P.rope_sin);
     h->tok_dev = (int32_t *)(A + P.tok); h->lab_dev = (int32_t *)(A + P.lab);
     h->rowstart_dev = (int32_t *)(A + P.rowstart); h->order_dev = (int32_t *)(A + P.order);

@@ -220,6 +220,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(GemmArgs g, int
                 for (int j = 0; j < TN; ++j) {
                     if (!full && col_w + j * 32 >= g.N) continue;
                     float v = acc[i][j][r];
+                    if (g.bias) v += bf2f(g.bias[col_w + j * 32]);
                     if (rr) v += bf2f(rr[j * 32]);
                     cr[j * 32] = f2bf(v);
                 }
@@ -405,7 +406,8 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
     // four consecutive columns 8 q + 4 hl + (0..3): one 8-byte (bf16) or 16-byte (fp32) store each.
     const int row_l = m0 + wm * 128 + l32, col_l = n0 + wn * 128 + hl * 4;
     const bool full = (m0 + BM <= g.M) && (n0 + BN <= g.N);
-    const bool vec = full && !(g.ldc & 3) && !((uintptr_t)g.C & 15) && (!g.R || (!(g.ldr & 3) && !((uintptr_t)g.R & 7)));
+    const bool vec = full && !(g.ldc & 3) && !((uintptr_t)g.C & 15) && (!g.R || (!(g.ldr & 3) && !((uintptr_t)g.R & 7))) &&
+                     !((uintptr_t)g.bias & 7);
     if (g.out_fp32) {
         float *cw = reinterpret_cast<float *>(g.C);
 #pragma unroll
@@ -443,6 +445,10 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
                     if (vec) {
                         float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2],
                               v3 = acc[i][j][4 * q + 3];
+                        if (g.bias) {
+                            const uint2 bv = *reinterpret_cast<const uint2 *>(g.bias + col);
+                            v0 += bflo(bv.x); v1 += bfhi(bv.x); v2 += bflo(bv.y); v3 += bfhi(bv.y);
+                        }
                         if (rp) {
                             const uint2 rv = *reinterpret_cast<const uint2 *>(rp);
                             v0 += bflo(rv.x); v1 += bfhi(rv.x); v2 += bflo(rv.y); v3 += bfhi(rv.y);
@@ -454,7 +460,9 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
                     } else if (row < g.M) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (col + e < g.N) cp[e] = f2bf(acc[i][j][4 * q + e] + (rp ? bf2f(rp[e]) : 0.f));
+                            if (col + e < g.N)
+                                cp[e] = f2bf(acc[i][j][4 * q + e] + (g.bias ? bf2f(g.bias[col + e]) : 0.f) +
+                                             (rp ? bf2f(rp[e]) : 0.f));
                     }
                 }
         }
@@ -491,6 +499,7 @@ hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
     if (((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
     if (g.lda < g.K || g.ldb < g.K || g.ldc < g.N) return hipErrorInvalidValue;
     if (g.R && (g.out_fp32 || g.ldr < g.N)) return hipErrorInvalidValue;
+    if (g.bias && g.out_fp32) return hipErrorInvalidValue;
     // offsets inside one tile are 32-bit: 256 rows of either operand must stay below 2^31 elements
     if (g.lda >= (1 << 22) || g.ldb >= (1 << 22)) return hipErrorInvalidValue;
     const int64_t big_tiles = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256);

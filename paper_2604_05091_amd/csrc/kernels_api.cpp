@@ -32,6 +32,21 @@ int32_t mt_k_gemm_nt(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t 
     return to_status(gemm_nt(g, S(stream)));
 }
 
+int32_t mt_k_gemm_nt_bias(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, uint16_t *C, int64_t ldc,
+                          const uint16_t *bias, int32_t M, int32_t N, int32_t K, void *stream) {
+    if (!A || !B || !C || !bias) return MT_ERR_INVALID_ARG;
+    GemmArgs g;
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.R = nullptr; g.ldr = 0;
+    g.M = M; g.N = N; g.K = K; g.out_fp32 = 0; g.accumulate = 0; g.bias = bias;
+    return to_status(gemm_nt(g, S(stream)));
+}
+
+size_t mt_k_bias_grad_ws_bytes(int32_t cols) { return bias_grad_ws_floats(cols) * sizeof(float); }
+int32_t mt_k_bias_grad(float *db, const uint16_t *x, int64_t ld, int64_t n, int32_t cols, void *ws, void *stream) {
+    if (!db || !x || !ws || !al16(x)) return MT_ERR_INVALID_ARG;
+    return to_status(bias_grad(db, x, ld, n, cols, reinterpret_cast<float *>(ws), S(stream)));
+}
+
 int32_t mt_k_transpose(const uint16_t *in, uint16_t *out, int32_t rows, int32_t cols, int64_t ld_in, int64_t ld_out,
                        int32_t nb0, int32_t nb1, int64_t in_s0, int64_t in_s1, int64_t out_s0, int64_t out_s1,
                        void *stream) {

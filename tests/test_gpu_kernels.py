@@ -84,6 +84,24 @@ def test_gemm_large_grid_kernel_all_epilogues(orc64, M, N, K):
     assert rel_l2(host(C32), 2 * ref) < 2e-6
 
 
+@pytest.mark.parametrize("M,N,K", [(300, 200, 136), (4100, 3080, 128)])
+def test_gemm_bias_epilogue_and_bias_gradient(orc64, M, N, K):
+    """C = A B^T + bias in both GEMM kernels (small grid / large grid), and db = column sums."""
+    rng = np.random.default_rng(M + N)
+    a, b = bf16_round(rng.standard_normal((M, K))), bf16_round(rng.standard_normal((N, K)))
+    bias = bf16_round(rng.standard_normal(N))
+    ref = orc64.linear_fwd(a, b) + bias[None, :]
+    A, B, BI = dev_bf16(a), dev_bf16(b), dev_bf16(bias)
+    C = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_gemm_nt_bias(A.data_ptr(), K, B.data_ptr(), K, C.data_ptr(), N, BI.data_ptr(), M, N, K, None))
+    assert rel_l2(host(C), ref) < BF16_TOL
+    ws = torch.empty(L.mt_k_bias_grad_ws_bytes(N) // 4, dtype=torch.float32, device="cuda")
+    DB = torch.full((N,), 5.0, dtype=torch.float32, device="cuda")
+    ok(L.mt_k_bias_grad(DB.data_ptr(), C.data_ptr(), N, M, N, ws.data_ptr(), None))
+    want = host(C).astype(np.float64).sum(axis=0)
+    assert np.max(np.abs(host(DB) - want)) <= 1e-5 * np.sqrt(M) * np.max(np.abs(host(C)))
+
+
 def test_gemm_weight_gradient_form_long_reduction(orc64):
     """dW[out,in] = sum_t dy[t,out] x[t,in]: both operands transposed first, fp32 result."""
     rng = np.random.default_rng(2)

@@ -24,7 +24,8 @@ LOSS_RTOL, GRAD_COS, GRAD_L2, PARAM_L2 = 1e-2, 0.999, 3e-2, 1e-3
 
 def make_cfg(shape, B, T, flags=0, **kw):
     return ModelCfg.make(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
-                         shape.vocab, B, T, rope_base=shape.rope_base, rms_eps=shape.rms_eps, flags=flags, **kw)
+                         shape.vocab, B, T, rope_base=shape.rope_base, rms_eps=shape.rms_eps, flags=flags,
+                         qkv_bias=shape.qkv_bias, **kw)
 
 
 def gpu_step(shape, B, T, params, tok, lab, flags=0):
@@ -186,6 +187,30 @@ def test_micro_batch_accumulation_adds_gradients(orc64, flags):
             v = 0.001 * g.astype(np.float64) ** 2
             want = p0 - 1e-3 * (m / 0.1) / (np.sqrt(v / 0.001) + 1e-8)
             assert np.max(np.abs(p - want)) < 1e-6, i
+
+
+@pytest.mark.parametrize("K,flags", [(1, 0), (2, mt.FLAG_STAGED_WEIGHTS)])
+def test_qkv_bias_layers_match_oracle(orc64, K, flags):
+    """Layers with q, k, v biases (12 tensors per layer): loss, every gradient including the bias gradients,
+    and one Adam step against the oracle."""
+    shape = ModelShape(3, 128, 4, 2, 64, 264, 520, qkv_bias=True)
+    names = [t[0] for t in mt_inputs.tensor_table(shape)]
+    assert len(names) == 12 * 3 + 3 and names[10:13] == ["l0.bq", "l0.bk", "l0.bv"]
+    params = mt_inputs.make_params(shape, seed=61, std=0.05)
+    tok, lab = mt_inputs.make_batch(shape.vocab, 2, 72, seed=62)
+    ps = [p.copy() for p in params]
+    with mt.TrainHandle(make_cfg(shape, 2, 72, flags=flags, ckpt_interval=K), ps) as h:
+        loss = h.train_step(tok, lab)
+        grads = [g.copy() for g in h.grads()]
+        check_against_oracle(orc64, shape, 2, 72, params, tok, lab, loss, grads)
+        assert all(np.linalg.norm(grads[i]) > 0 for i in (10, 11, 12))
+        h.adam_step(1e-3, step=1)
+        for i in (10, 11, 12):      # first Adam step: p - lr * sign-like update of the bias
+            want = params[i] - 1e-3 * grads[i] / (np.abs(grads[i]) + 1e-8)
+            assert np.max(np.abs(ps[i] - want)) < 1e-6
+        loss2 = h.train_step(tok, lab)          # the updated biases are streamed in the next step
+        ref2, _ = orc64.train_step(shape, ps, tok, lab, mode=1)
+        assert abs(loss2 - ref2) <= LOSS_RTOL * abs(ref2)
 
 
 def test_staged_weights_equal_pinned_bf16_copy():
