@@ -60,3 +60,80 @@ def test_attention_rows_at_128k_context(orc64):
                 assert np.max(np.abs(dq)) < 1e-5 and np.all(dq_ref == 0)
             else:
                 assert rel_l2(dq, dq_ref) < 3e-2 and cosine(dq, dq_ref) > 0.999, (h, t, rel_l2(dq, dq_ref))
+
+
+# ----------------------------------------------------------------------------- full-size launches, sampled outputs
+@pytest.mark.parametrize("name,M,N,K,fp32", [("7B qkv", 65536, 12288, 4096, False), ("7B down", 65536, 4096, 11008, False),
+                                             ("7B wgrad gate/up", 22016, 4096, 65536, True),
+                                             ("14B qkv", 65536, 7168, 5120, False)])
+def test_gemm_at_benchmark_shapes_sampled_outputs(orc64, name, M, N, K, fp32):
+    """The GEMM launches of the benchmark step at their real sizes (same grid, tile order and kernel as in
+    bench.py); 48 output elements, sampled over first/last tiles and at random, against the oracle's dot
+    products of the same bf16 inputs."""
+    L = mt.lib()
+    g = torch.Generator(device="cuda").manual_seed(M % 1000 + N)
+    A = (torch.randn((M, K), device="cuda", generator=g) * 0.5).to(torch.bfloat16)
+    B = (torch.randn((N, K), device="cuda", generator=g) * 0.5).to(torch.bfloat16)
+    C = torch.zeros((M, N), dtype=torch.float32 if fp32 else torch.bfloat16, device="cuda")
+    print(f"[scale] gemm {name}: {M} x {N} x {K}", flush=True)
+    ok(L.mt_k_gemm_nt(A.data_ptr(), K, B.data_ptr(), K, C.data_ptr(), N, None, 0, M, N, K, int(fp32), 0, None))
+    rng = np.random.default_rng(7)
+    rows = np.concatenate([[0, 255, 256, M - 1, M - 256], rng.integers(0, M, 11)])
+    cols = np.concatenate([[0, 255, N - 1], rng.integers(0, N, 0)])
+    picks = [(int(r), int(c)) for r in rows[:8] for c in cols] + [(int(r), int(rng.integers(0, N))) for r in rows for _ in range(2)]
+    for r, c in picks[:48]:
+        a = A[r].float().cpu().numpy().astype(np.float64)[None, :]
+        b = B[c].float().cpu().numpy().astype(np.float64)[None, :]
+        ref = float(orc64.linear_fwd(a, b)[0, 0])
+        got = float(C[r, c].float().cpu())
+        tol = (1e-5 if fp32 else 2.0 ** -8) * max(abs(ref), 1.0) + 1e-6 * np.sqrt(K)
+        assert abs(got - ref) <= tol, (name, r, c, got, ref)
+
+
+def test_attention_at_benchmark_shape_sampled_rows(orc64):
+    """Forward output and dq at the 7B benchmark shape (16 sequences x 4096 tokens, 32 heads of 128): rows of
+    several sequences and heads against the single-row oracle."""
+    L = mt.lib()
+    Bn, T, Hq, Hkv, hd = 16, 4096, 32, 32, 128
+    nq = Hq * hd
+    ld = 3 * nq
+    g = torch.Generator(device="cuda").manual_seed(9)
+    qkv = (torch.randn((Bn * T, ld), device="cuda", generator=g) * 0.5).to(torch.bfloat16)
+    dout = torch.randn((Bn * T, nq), device="cuda", generator=g).to(torch.bfloat16)
+    pq, pk, pv = qkv.data_ptr(), qkv.data_ptr() + 2 * nq, qkv.data_ptr() + 4 * nq
+    O = torch.zeros((Bn * T, nq), dtype=torch.bfloat16, device="cuda")
+    LSE = torch.zeros((Bn, Hq, T), dtype=torch.float32, device="cuda")
+    DELTA = torch.empty((Bn, Hq, T), dtype=torch.float32, device="cuda")
+    DQKV = torch.zeros((Bn * T, ld), dtype=torch.bfloat16, device="cuda")
+    scale = 1.0 / np.sqrt(hd)
+    ok(L.mt_k_flash_fwd(O.data_ptr(), nq, LSE.data_ptr(), pq, ld, pk, ld, pv, ld, Bn, T, Hq, Hkv, hd, scale, None))
+    ok(L.mt_k_flash_bwd(DQKV.data_ptr(), ld, DQKV.data_ptr() + 2 * nq, ld, DQKV.data_ptr() + 4 * nq, ld,
+                        dout.data_ptr(), nq, pq, ld, pk, ld, pv, ld, O.data_ptr(), nq, LSE.data_ptr(),
+                        DELTA.data_ptr(), Bn, T, Hq, Hkv, hd, scale, None))
+    for b, h, t in ((0, 0, 1), (0, 31, 4095), (7, 13, 2047), (15, 5, 255), (15, 31, 256), (3, 17, 3000)):
+        r0 = b * T
+        kh = qkv[r0:r0 + t + 1, nq + h * hd: nq + (h + 1) * hd].float().cpu().numpy().astype(np.float64)
+        vh = qkv[r0:r0 + t + 1, 2 * nq + h * hd: 2 * nq + (h + 1) * hd].float().cpu().numpy().astype(np.float64)
+        qt = qkv[r0 + t, h * hd:(h + 1) * hd].float().cpu().numpy().astype(np.float64)
+        dat = dout[r0 + t, h * hd:(h + 1) * hd].float().cpu().numpy().astype(np.float64)
+        a_ref, dq_ref = orc64.attention_row(qt, dat, kh, vh)
+        a = O[r0 + t, h * hd:(h + 1) * hd].float().cpu().numpy()
+        dq = DQKV[r0 + t, h * hd:(h + 1) * hd].float().cpu().numpy()
+        assert rel_l2(a, a_ref) < 1e-2, (b, h, t)
+        assert cosine(dq, dq_ref) > 0.999 and rel_l2(dq, dq_ref) < 3e-2, (b, h, t, rel_l2(dq, dq_ref))
+    # dK, dV of the last key of a sequence depend on the last query alone: a closed form from the row oracle's pieces
+    b, h, t = 9, 20, T - 1
+    r0 = b * T
+    kh = qkv[r0:r0 + T, nq + h * hd: nq + (h + 1) * hd].float().cpu().numpy().astype(np.float64)
+    vh = qkv[r0:r0 + T, 2 * nq + h * hd: 2 * nq + (h + 1) * hd].float().cpu().numpy().astype(np.float64)
+    qt = qkv[r0 + t, h * hd:(h + 1) * hd].float().cpu().numpy().astype(np.float64)
+    dat = dout[r0 + t, h * hd:(h + 1) * hd].float().cpu().numpy().astype(np.float64)
+    s = kh @ qt * scale
+    p = np.exp(s - s.max())
+    p /= p.sum()
+    a_row = p @ vh
+    dv_ref = p[-1] * dat
+    dk_ref = p[-1] * (vh[-1] @ dat - a_row @ dat) * scale * qt
+    dv = DQKV[r0 + t, 2 * nq + h * hd: 2 * nq + (h + 1) * hd].float().cpu().numpy()
+    dk = DQKV[r0 + t, nq + h * hd: nq + (h + 1) * hd].float().cpu().numpy()
+    assert rel_l2(dv, dv_ref) < 3e-2 and rel_l2(dk, dk_ref) < 3e-2, (rel_l2(dv, dv_ref), rel_l2(dk, dk_ref))
