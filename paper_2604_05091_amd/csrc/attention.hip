@@ -22,6 +22,10 @@
 // (ds_read_b64_tr_b16), which hands each lane four consecutive rows of one column; two such
 // reads give exactly the eight reduction indices of the accumulator permutation.
 // dQ and dK/dV are separate kernels: no atomics, results are bit-reproducible.
+//
+// LDS rows have a pitch of head_dim + 40 elements: consecutive rows then start 20 banks apart, which keeps
+// the 16-byte row reads conflict-free and lets the four rows touched by one transposing read overlap in 12
+// of the 64 banks only (a pitch of head_dim + 8 piles them onto the same 28 banks and halves the LDS rate).
 #include <stdlib.h>
 
 #include "common.h"
@@ -414,148 +418,10 @@ __global__ __launch_bounds__(64 * NW) void flash_bwd_dq_kernel(AttnArgs a) {
     if (qok) store_owned_rows<HD>(a.dq + ((int64_t)b * T + q) * a.lddq + (int64_t)h * HD, dqacc, a.scale, hl);
 }
 
-// ------------------------------------------------------------------ backward: dK, dV
-// grid (key blocks of 128, heaviest first = block 0; Hkv; B); a lane owns one key and keeps
-// its K and V fragments in registers; loops over the query heads of the group and the query
-// tiles >= the key block.
-template <int HD>
-__global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
-#ifndef MT_DKDV_KB
-#define MT_DKDV_KB 2
-#endif
-    constexpr int LDK = HD + 8, KB = MT_DKDV_KB;  // KB: k-steps whose fragments are read ahead of their MFMAs
-    // one stage: Q [64][LDK], dO [64][LDK] (bf16), then lse*log2e [64], delta [64] (fp32)
-    constexpr int STAGE_BF = 2 * 64 * LDK, STAGE = STAGE_BF + 256;  // in bf16 elements
-    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-
-    const int T = a.T, G = a.Hq / a.Hkv;
-    int set, kvb;  // key block 0 is the heaviest and comes first
-    if (!decode_block((T + 127) / 128, a.B * a.Hkv, &set, &kvb)) return;
-    const int b = set / a.Hkv, hk = set % a.Hkv;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
-    const int tr_off = tr_lane_offset(lane, LDK);
-    const int kv0w = kvb * 128 + wave * 32, kv = kv0w + l32;
-    const bool kvok = kv < T;
-
-    bf16x8 kf[HD / 16], vf[HD / 16];
-    {
-        const int kvc = kvok ? kv : T - 1;  // padded keys read the last row; their dK/dV are never stored
-        const bf16_t *kp = a.k + ((int64_t)b * T + kvc) * a.ldk + (int64_t)hk * HD + hl * 8;
-        const bf16_t *vp = a.v + ((int64_t)b * T + kvc) * a.ldv + (int64_t)hk * HD + hl * 8;
-#pragma unroll
-        for (int ks = 0; ks < HD / 16; ++ks) {
-            kf[ks] = load_frag_global(kp + ks * 16);
-            vf[ks] = load_frag_global(vp + ks * 16);
-        }
-    }
-    f32x16 dvacc[HD / 32], dkacc[HD / 32];
-#pragma unroll
-    for (int hb = 0; hb < HD / 32; ++hb) {
-        dvacc[hb] = zero16();
-        dkacc[hb] = zero16();
-    }
-    const float c = a.scale * kLog2e;
-    const int qt_first = (kvb * 128) / 64, n_qt = (T + 63) / 64 - qt_first;
-    const int total = G * n_qt;  // (query head of the group, query tile) pairs, walked as one pipeline
-
-    TileStage<64, HD, LDK, 256> stQ, stDO;
-    float stat = 0.f;  // thread < 64: lse * log2e of query (tile row = thread); 64..127: delta
-    auto fetch = [&](int it) {
-        const int h = hk * G + it / n_qt, q0t = (qt_first + it % n_qt) * 64;
-        // query rows past T repeat row T-1; the mask below zeroes their P and dS
-        stQ.fetch_clamped(a.q + ((int64_t)b * T + q0t) * a.ldq + (int64_t)h * HD, a.ldq, T - q0t);
-        stDO.fetch_clamped(a.dout + ((int64_t)b * T + q0t) * a.lddo + (int64_t)h * HD, a.lddo, T - q0t);
-        if (threadIdx.x < 128) {
-            const int qq = q0t + (threadIdx.x & 63);
-            const int64_t si = ((int64_t)b * a.Hq + h) * T + (qq < T ? qq : T - 1);
-            stat = threadIdx.x < 64 ? a.lse[si] * kLog2e : a.delta[si];
-        }
-    };
-    auto commit = [&](int buf) {
-        bf16_t *st = smem + buf * STAGE;
-        stQ.commit_plain(st);
-        stDO.commit_plain(st + 64 * LDK);
-        if (threadIdx.x < 128) reinterpret_cast<float *>(st + STAGE_BF)[threadIdx.x] = stat;
-    };
-    if (total > 0) {
-        fetch(0);
-        commit(0);
-    }
-    __syncthreads();
-
-    for (int it = 0; it < total; ++it) {
-        const int q0t = (qt_first + it % n_qt) * 64;
-        const bool more = it + 1 < total;
-        const bf16_t *Qs = smem + (it & 1) * STAGE, *dOs = Qs + 64 * LDK;
-        const float *lses = reinterpret_cast<const float *>(Qs + STAGE_BF), *dlts = lses + 64;
-        if (more) fetch(it + 1);
-        if (q0t + 63 >= kv0w) {  // otherwise every query of the tile precedes every key of this wave
-            const bool diag = q0t < kv0w + 31 || q0t + 63 >= T;  // some (query, key) pair masked, or padded queries
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-                f32x16 sacc = zero16(), dpacc = zero16();
-                const bf16_t *qr = Qs + (rb * 32 + l32) * LDK + hl * 8;
-                const bf16_t *dor = dOs + (rb * 32 + l32) * LDK + hl * 8;
-#pragma unroll
-                for (int part = 0; part < HD / (16 * KB); ++part) {
-                    bf16x8 qq4[KB], dd4[KB];
-#pragma unroll
-                    for (int j = 0; j < KB; ++j) {
-                        qq4[j] = *reinterpret_cast<const bf16x8 *>(qr + (part * KB + j) * 16);
-                        dd4[j] = *reinterpret_cast<const bf16x8 *>(dor + (part * KB + j) * 16);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int j = 0; j < KB; ++j) {
-                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq4[j], kf[part * KB + j], sacc, 0, 0, 0);
-                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dd4[j], vf[part * KB + j], dpacc, 0, 0, 0);
-                    }
-                }
-                f32x16 pacc;
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int qi = rb * 32 + r4 * 8 + hl * 4;  // 4 consecutive query rows of the tile
-                    const float4 l4 = *reinterpret_cast<const float4 *>(lses + qi);
-                    const float4 d4 = *reinterpret_cast<const float4 *>(dlts + qi);
-                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
-                    if (diag) {  // wave-uniform: only tiles on the diagonal or with padded queries pay for the mask
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int r = r4 * 4 + e, qq = q0t + qi + e;
-                            const float p = (kv > qq || qq >= T) ? 0.f : __builtin_amdgcn_exp2f(sacc[r] * c - lv[e]);
-                            pacc[r] = p;
-                            sacc[r] = p * (dpacc[r] - dv4[e]);  // dS
-                        }
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int r = r4 * 4 + e;
-                            const float p = __builtin_amdgcn_exp2f(sacc[r] * c - lv[e]);
-                            pacc[r] = p;
-                            sacc[r] = p * (dpacc[r] - dv4[e]);  // dS
-                        }
-                    }
-                }
-                // dV^T += dO^T P,  dK^T += Q^T dS
-#pragma unroll
-                for (int cch = 0; cch < 2; ++cch) {
-                    mfma_tr_accumulate<HD, LDK>(dvacc, dOs, tr_off, rb, cch, pack_frag(pacc, cch));
-                    mfma_tr_accumulate<HD, LDK>(dkacc, Qs, tr_off, rb, cch, pack_frag(sacc, cch));
-                }
-            }
-        }
-        if (more) commit((it + 1) & 1);
-        __syncthreads();
-    }
-    if (kvok) {
-        store_owned_rows<HD>(a.dk + ((int64_t)b * T + kv) * a.lddk + (int64_t)hk * HD, dkacc, a.scale, hl);
-        store_owned_rows<HD>(a.dv + ((int64_t)b * T + kv) * a.lddv + (int64_t)hk * HD, dvacc, 1.0f, hl);
-    }
-}
-
 // ------------------------------------------------------------------ backward: dK, dV, software-pipelined
-// Same ownership and arithmetic as flash_bwd_dkdv_kernel; the work is cut into units u = (query tile,
-// 32-query half) and every wave runs a three-stage pipeline over them so that the matrix cores and the
+// grid: key blocks of 128 (heaviest first = block 0) x (batch, KV head); a lane owns one key and keeps its K
+// and V fragments in registers; the query heads of the group and their query tiles >= the key block are
+// walked as one sequence.  The work is cut into units u = (query tile, 32-query half) and every wave runs a three-stage pipeline over them so that the matrix cores and the
 // vector ALU work at the same time although only one wave fits on a SIMD:
 //     slot t :   A(t+1)  S = Q K^T, dP = dO V^T          16 MFMAs  -> accumulator set (t+1)&1
 //                B(t)    P = exp2(S c - lse), dS = P (dP - delta), packed to bf16     VALU
@@ -569,7 +435,7 @@ __device__ __forceinline__ void wg_barrier_lds() { asm volatile("s_waitcnt lgkmc
 
 constexpr int kPipePad = 40;
 template <int HD>
-__global__ __launch_bounds__(256) void flash_bwd_dkdv_pipe_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
     // row pitch HD + 40 elements: consecutive rows are 20 banks apart, which keeps the 16-byte row reads
     // conflict-free (odd multiple of 4 banks) and lets the four rows of a transposing read overlap in only
     // 12 of 64 banks (with HD + 8 they pile up on the same 28 banks)
@@ -811,34 +677,14 @@ hipError_t flash_bwd_dkdv(const AttnArgs &a, hipStream_t s) {
         ((uintptr_t)a.dv & 7))
         return hipErrorInvalidValue;
     const dim3 grid(grid_blocks((a.T + 127) / 128, a.B * a.Hkv));
-    static const bool pipelined = [] {
-        const char *e = getenv("MT_DKDV_PIPE");  // diagnostic: 0 selects the unpipelined kernel
-        return !e || atoi(e) != 0;
-    }();
-    if (pipelined) {
-        if (a.hd == 128) {
-            constexpr size_t lds = 3 * ((2 * 64 * (128 + kPipePad)) * sizeof(bf16_t) + 512);
-            static bool done = false;
-            hipError_t e = ensure_lds(&flash_bwd_dkdv_pipe_kernel<128>, lds, &done);
-            if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(flash_bwd_dkdv_pipe_kernel<128>, grid, dim3(256), lds, s, a);
-        } else {
-            constexpr size_t lds = 3 * ((2 * 64 * (64 + kPipePad)) * sizeof(bf16_t) + 512);
-            static bool done = false;
-            hipError_t e = ensure_lds(&flash_bwd_dkdv_pipe_kernel<64>, lds, &done);
-            if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(flash_bwd_dkdv_pipe_kernel<64>, grid, dim3(256), lds, s, a);
-        }
-        return hipGetLastError();
-    }
     if (a.hd == 128) {
-        constexpr size_t lds = 2 * ((2 * 64 * (128 + 8)) * sizeof(bf16_t) + 512);
+        constexpr size_t lds = 3 * ((2 * 64 * (128 + kPipePad)) * sizeof(bf16_t) + 512);
         static bool done = false;
         hipError_t e = ensure_lds(&flash_bwd_dkdv_kernel<128>, lds, &done);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(flash_bwd_dkdv_kernel<128>, grid, dim3(256), lds, s, a);
     } else {
-        constexpr size_t lds = 2 * ((2 * 64 * (64 + 8)) * sizeof(bf16_t) + 512);
+        constexpr size_t lds = 3 * ((2 * 64 * (64 + kPipePad)) * sizeof(bf16_t) + 512);
         static bool done = false;
         hipError_t e = ensure_lds(&flash_bwd_dkdv_kernel<64>, lds, &done);
         if (e != hipSuccess) return e;

@@ -1,26 +1,25 @@
 // bf16 x bf16 -> fp32-accumulate GEMM on the gfx950 matrix cores.
 //
-//   C[M,N] = A[M,K] . B[N,K]^T        both operands have the reduction index contiguous
+//   C[M,N] = A[M,K] . B[N,K]^T (+ bias) (+ R)      both operands have the reduction index contiguous
 //
-// This one kernel serves every projection of a transformer block (Algorithm 1,
+// This one entry point serves every projection of a transformer block (Algorithm 1,
 // "h_i <- f_i(h_{i-1}; theta_i)" and "LocalBackward"): forward uses the weight as
 // stored ([out,in]); the input-gradient and weight-gradient products are brought to
 // the same form by transposing one or both operands with transpose_bf16 first.
 //
-// Tiling: a workgroup of 4 waves (2 x 2) owns a BM x BN tile of C; each wave owns a
-// (BM/2) x (BN/2) sub-tile made of 32x32 MFMA blocks (v_mfma_f32_32x32x16_bf16,
-// 16 fp32 accumulators per lane per block).  K is walked in steps of 64 through a
-// double-buffered LDS stage fed from two register stages: while the matrix cores
-// consume step s from LDS, the loads of step s+1 are landing in registers and those of
-// step s+2 are being issued; step s+1 is written to the other LDS buffer after the
-// MFMAs of step s were issued, so one barrier per step suffices.
-// LDS rows are padded to 72 elements (144 B) which makes the 16-byte fragment reads
-// of 8 consecutive lanes hit 32 distinct banks.
+// Two kernels share the tile geometry: a workgroup owns a 256 x 256 (or 128 x 128) tile of C made of
+// 32x32 MFMA blocks (v_mfma_f32_32x32x16_bf16, 16 fp32 accumulators per lane per block); K is walked in
+// steps of 64 through a double-buffered LDS stage; LDS rows are padded to 72 elements (144 B), which
+// makes the 16-byte fragment reads of consecutive lanes conflict-free.
+//   gemm_nt_w4_kernel  large grids with K % 64 == 0 (every projection of the billion-parameter
+//                      workloads): 4 waves x 128x128 quadrants, software-pipelined inside the wave.
+//   gemm_nt_kernel     everything else (ragged K, small problems): 8 waves x 128x64 (or 4 x 64x64),
+//                      load - compute - commit - barrier per step.
 //
 // Workgroup -> tile mapping: consecutive workgroup ids are dealt round-robin to the
 // 8 XCDs, each with a private L2.  The id is first re-numbered so that every XCD gets
 // a contiguous range of tiles, then walked in column-major groups of 8 tile rows so
-// the tiles resident on one XCD share A and B panels.
+// the 32 tiles resident on one XCD form an 8 x 4 patch that shares A and B panels.
 #include <stdlib.h>
 
 #include "common.h"
@@ -33,12 +32,6 @@ constexpr int BK = 64;
 constexpr int LDT = BK + 8;
 constexpr int kXcd = 8;
 constexpr int kGroupM = 8;
-#ifndef MT_GX_SETPRIO
-#define MT_GX_SETPRIO 0
-#endif
-#ifndef MT_GX_STAGES
-#define MT_GX_STAGES 1
-#endif
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 template <int BM, int BN, int WGM, int WGN>
@@ -80,11 +73,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(GemmArgs g, int
     for (int j = 0; j < NA; ++j) aoff[j] = (uint32_t)(min(lrow + RS * j, g.M - 1 - m0) * (int)g.lda + lkc);
 #pragma unroll
     for (int j = 0; j < NB; ++j) boff[j] = (uint32_t)(min(lrow + RS * j, g.N - 1 - n0) * (int)g.ldb + lkc);
-    // Two register stages (native vectors, so the selects below stay value selects): while the matrix
-    // cores work on k-step t out of LDS, the loads of step t+1 are landing in one stage and the loads of
-    // step t+2 are being issued into the other, i.e. every global load has two compute phases to arrive.
-    u32x4 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
-    bool kok0 = true, kok1 = true;
+    // One register stage (native vectors, so the selects below stay value selects): while the matrix cores
+    // work on k-step t out of LDS, the loads of step t+1 are landing in these registers.
+    u32x4 ra0[NA], rb0[NB];
+    bool kok0 = true;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
     f32x16 acc[TM][TN];
@@ -131,39 +123,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(GemmArgs g, int
         _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                        \
             if (ks + 1 < BK / 16) MT_GEMM_READ_FRAGS((ks + 1) & 1, ks + 1);                             \
             __builtin_amdgcn_sched_barrier(0);                                                          \
-            if (MT_GX_SETPRIO) __builtin_amdgcn_s_setprio(1);                                           \
             _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
                 _Pragma("unroll") for (int j = 0; j < TN; ++j)                                          \
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j],  \
                                                                         acc[i][j], 0, 0, 0);            \
-            if (MT_GX_SETPRIO) __builtin_amdgcn_s_setprio(0);                                           \
             __builtin_amdgcn_sched_barrier(0);                                                          \
         }                                                                                               \
     }
 
     const int nk = (g.K + BK - 1) / BK;
-#if MT_GX_STAGES == 2
-    MT_GEMM_LOAD(ra0, rb0, kok0, 0);
-    MT_GEMM_COMMIT(ra0, rb0, kok0, 0);
-    if (nk > 1) MT_GEMM_LOAD(ra1, rb1, kok1, BK);
-    __syncthreads();
-
-    int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
-        // even step: LDS[0] holds step kt, stage 1 holds step kt+1 (in flight)
-        if (kt + 2 < nk) MT_GEMM_LOAD(ra0, rb0, kok0, (kt + 2) * BK);
-        MT_GEMM_COMPUTE(0);
-        MT_GEMM_COMMIT(ra1, rb1, kok1, 1);
-        __syncthreads();
-        // odd step: LDS[1] holds step kt+1, stage 0 holds step kt+2 (in flight)
-        if (kt + 3 < nk) MT_GEMM_LOAD(ra1, rb1, kok1, (kt + 3) * BK);
-        MT_GEMM_COMPUTE(1);
-        if (kt + 2 < nk) MT_GEMM_COMMIT(ra0, rb0, kok0, 0);
-        __syncthreads();
-    }
-    if (kt < nk) MT_GEMM_COMPUTE(0);  // odd number of steps: the last one is already in LDS[0]
-#else
-    (void)ra1; (void)rb1; (void)kok1;
     MT_GEMM_LOAD(ra0, rb0, kok0, 0);
     MT_GEMM_COMMIT(ra0, rb0, kok0, 0);
     __syncthreads();
@@ -179,7 +147,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(GemmArgs g, int
         __syncthreads();
     }
     if (kt < nk) MT_GEMM_COMPUTE(0);
-#endif
 #undef MT_GEMM_LOAD
 #undef MT_GEMM_COMMIT
 #undef MT_GEMM_COMPUTE
@@ -504,11 +471,8 @@ hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
     if (g.lda >= (1 << 22) || g.ldb >= (1 << 22)) return hipErrorInvalidValue;
     const int64_t big_tiles = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256);
     switch (variant_override()) {   // diagnostic override (MT_GEMM_VARIANT), 0 = heuristic
-        case 1: return launch<256, 256, 2, 2>(g, s);
         case 2: return launch<256, 256, 2, 4>(g, s);
         case 3: return launch<128, 128, 2, 2>(g, s);
-        case 4: return launch<256, 128, 2, 2>(g, s);
-        case 5: return launch<256, 128, 4, 2>(g, s);
         case 6: if (g.K % BK == 0) return launch_w4(g, s); break;
         default: break;
     }
