@@ -36,6 +36,7 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kLazyMax = 8.0f;  // forward: the running maximum may lag the true one by this much (log2 units)
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
@@ -208,8 +209,8 @@ __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
     f32x16 oacc[HD / 32];
 #pragma unroll
     for (int hb = 0; hb < HD / 32; ++hb) oacc[hb] = zero16();
-    float m = -INFINITY, lsum = 0.f;
-    const float c = a.scale * kLog2e;
+    float m = -INFINITY, lsum = 0.f;  // m: running maximum of the raw (unscaled) scores
+    const float c = a.scale * kLog2e, tau = kLazyMax / c;
 
     const bf16_t *kbase = a.k + (int64_t)b * T * a.ldk + (int64_t)hk * HD;
     const bf16_t *vbase = a.v + (int64_t)b * T * a.ldv + (int64_t)hk * HD;
@@ -253,49 +254,66 @@ __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
                     }
                 }
             }
-            float mx = -INFINITY;
+            // V^T fragments of the first two 16-key chunks are requested now, so that their LDS latency is
+            // covered by the softmax arithmetic below; the other two chunks follow behind the first MFMAs
+            bf16x8 va[2][HD / 32];
+#pragma unroll
+            for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+                for (int hb = 0; hb < HD / 32; ++hb) va[ch][hb] = read_tr_frag(Vs, tr_off, LDK, ch * 16, hb * 32);
+            __builtin_amdgcn_sched_barrier(0);
+            // Softmax on the raw scores: the scale is folded into the exponent's multiply-add, the running
+            // maximum m is only moved when some query of the wave saw a score more than kLazyMax above it
+            // (P then stays below 2^kLazyMax * ... which bf16 and the fp32 sums hold without loss; the final
+            // O / lsum and lse do not depend on which maximum was used), so the accumulator rescale is rare.
             if (kv0 + 63 > q0) {  // tile touches the diagonal: mask keys after the query
 #pragma unroll
                 for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int kv = kv0 + rb * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
-                        const float sv = kv > qm ? -INFINITY : sacc[rb][r] * c;
-                        sacc[rb][r] = sv;
-                        mx = fmaxf(mx, sv);
-                    }
-            } else {
-#pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float sv = sacc[rb][r] * c;
-                        sacc[rb][r] = sv;
-                        mx = fmaxf(mx, sv);
+                        sacc[rb][r] = kv > qm ? -INFINITY : sacc[rb][r];
                     }
             }
+            float mx = fmaxf(sacc[0][0], sacc[1][0]);
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, sacc[0][r]), sacc[1][r]);  // v_max3_f32
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m, mx);  // finite: kv0 <= q0 <= qm, so key kv0 is visible to every query
-            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            // m = -inf before the first tile: the comparison is then true (every query sees key kv0)
+            if (__builtin_amdgcn_ballot_w64(mx > m + tau) != 0) {
+                const float m_new = fmaxf(m, mx);
+                const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+                lsum *= alpha;
+#pragma unroll
+                for (int hb = 0; hb < HD / 32; ++hb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[hb][r] *= alpha;
+                m = m_new;
+            }
+            const float negmc = -m * c;
             float ps = 0.f;
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float pv = __builtin_amdgcn_exp2f(sacc[rb][r] - m_new);
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[rb][r], c, negmc));
                     sacc[rb][r] = pv;
                     ps += pv;
                 }
-            lsum = lsum * alpha + ps;
-            m = m_new;
-#pragma unroll
-            for (int hb = 0; hb < HD / 32; ++hb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[hb][r] *= alpha;
+            lsum += ps;
             // O^T += V^T P^T
 #pragma unroll
-            for (int ch = 0; ch < 4; ++ch)
-                mfma_tr_accumulate<HD, LDK>(oacc, Vs, tr_off, ch >> 1, ch & 1, pack_frag(sacc[ch >> 1], ch & 1));
+            for (int ch = 0; ch < 4; ++ch) {
+                const bf16x8 pf = pack_frag(sacc[ch >> 1], ch & 1);
+#pragma unroll
+                for (int hb = 0; hb < HD / 32; ++hb)
+                    oacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ch & 1][hb], pf, oacc[hb], 0, 0, 0);
+                if (ch < 2) {
+#pragma unroll
+                    for (int hb = 0; hb < HD / 32; ++hb)
+                        va[ch & 1][hb] = read_tr_frag(Vs, tr_off, LDK, (ch + 2) * 16, hb * 32);
+                }
+            }
         }
         if (more) {
             bf16_t *nx = smem + ((kt + 1) & 1) * STAGE;
@@ -307,7 +325,7 @@ __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
     lsum += __shfl_xor(lsum, 32, 64);
     if (qok) {
         store_owned_rows<HD>(a.o + ((int64_t)b * T + q) * a.ldo + (int64_t)h * HD, oacc, 1.0f / lsum, hl);
-        if (hl == 0) a.lse[((int64_t)b * a.Hq + h) * T + q] = (m + __builtin_amdgcn_logf(lsum)) * kLn2;
+        if (hl == 0) a.lse[((int64_t)b * a.Hq + h) * T + q] = (m * c + __builtin_amdgcn_logf(lsum)) * kLn2;
     }
 }
 
