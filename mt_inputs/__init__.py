@@ -52,8 +52,9 @@ def _load():
 
 @dataclass(frozen=True)
 class ModelShape:
-    """Architecture of a decoder-only LM (pre-norm, RMSNorm, RoPE, SwiGLU, untied head).  qkv_bias adds a bias
-    vector to the q, k and v projections (three more tensors per layer, after w_down)."""
+    """Architecture of a decoder-only LM (pre-norm, RMSNorm, RoPE, SwiGLU).  qkv_bias adds a bias vector to the
+    q, k and v projections (three more tensors per layer, after w_down); tie_embeddings makes the output
+    projection reuse the embedding table (the lm_head tensor disappears from the table)."""
     n_layers: int
     hidden: int
     n_q_heads: int
@@ -64,6 +65,7 @@ class ModelShape:
     rope_base: float = 10000.0
     rms_eps: float = 1e-5
     qkv_bias: bool = False
+    tie_embeddings: bool = False
 
     def dict(self):
         return asdict(self)
@@ -80,7 +82,8 @@ CONFIGS = {
 
 
 def tensor_table(s: ModelShape):
-    """Canonical tensor order: (name, rows, cols) for the 9L+3 (12L+3 with qkv_bias) parameter tensors.
+    """Canonical tensor order: (name, rows, cols) for the 9L+3 (12L+3 with qkv_bias; one fewer with tie_embeddings)
+    parameter tensors.
 
     Matrices are row-major [out_features, in_features]; vectors have cols == 1... no:
     vectors are reported as (rows=n, cols=1).
@@ -94,7 +97,9 @@ def tensor_table(s: ModelShape):
               (f"l{l}.w_down", s.hidden, s.ffn)]
         if s.qkv_bias:
             t += [(f"l{l}.bq", nq, 1), (f"l{l}.bk", nkv, 1), (f"l{l}.bv", nkv, 1)]
-    t += [("final_norm", s.hidden, 1), ("lm_head", s.vocab, s.hidden)]
+    t += [("final_norm", s.hidden, 1)]
+    if not s.tie_embeddings:
+        t += [("lm_head", s.vocab, s.hidden)]
     return t
 
 

@@ -23,7 +23,8 @@ _SRC = os.path.join(_HERE, "mt_oracle.c")
 class OrcCfg(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("hidden", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
                 ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("ffn", ctypes.c_int32),
-                ("vocab", ctypes.c_int32), ("qkv_bias", ctypes.c_int32), ("rope_base", ctypes.c_double),
+                ("vocab", ctypes.c_int32), ("qkv_bias", ctypes.c_int32), ("tie_embeddings", ctypes.c_int32),
+                ("rope_base", ctypes.c_double),
                 ("rms_eps", ctypes.c_double)]
 
 
@@ -43,7 +44,8 @@ def build(force: bool = False) -> None:
 def _cfg(shape) -> OrcCfg:
     g = shape if isinstance(shape, dict) else shape.__dict__
     return OrcCfg(g["n_layers"], g["hidden"], g["n_q_heads"], g["n_kv_heads"], g["head_dim"], g["ffn"],
-                  g["vocab"], int(bool(g.get("qkv_bias", False))), float(g.get("rope_base", 10000.0)),
+                  g["vocab"], int(bool(g.get("qkv_bias", False))), int(bool(g.get("tie_embeddings", False))),
+                  float(g.get("rope_base", 10000.0)),
                   float(g.get("rms_eps", 1e-5)))
 
 
@@ -199,7 +201,7 @@ class Oracle:
         """Returns (loss, grads) with grads in canonical tensor order; mode 0 monolithic, 1 streamed."""
         cfg = _cfg(shape)
         ps = [self.arr(p) for p in params]
-        assert len(ps) == (12 if cfg.qkv_bias else 9) * cfg.n_layers + 3
+        assert len(ps) == (12 if cfg.qkv_bias else 9) * cfg.n_layers + (2 if cfg.tie_embeddings else 3)
         tokens = np.ascontiguousarray(tokens, dtype=np.int32)
         labels = np.ascontiguousarray(labels, dtype=np.int32)
         B, T = tokens.shape

@@ -49,6 +49,9 @@ typedef struct {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
     int32_t qkv_bias; /* 1: the q, k, v projections carry a bias vector each (Qwen2.5-style layers, the models of
                          Section 4.1); a layer then has 12 tensors instead of 9: ..., w_down, bq, bk, bv */
+    int32_t tie_embeddings; /* 1: the output projection uses the embedding table (Appendix A.1, tied weights); the
+                               parameter list then ends with final_norm and the table's gradient is the sum of
+                               the head's weight gradient and the embedding's scatter-add */
     double rope_base, rms_eps;
 } orc_cfg;
 
@@ -560,13 +563,14 @@ int orc_train_step(const orc_cfg *cf, const real *const *params, const int32_t *
         block_forward(h[i + 1], h[i], params + 1 + PL * i, mode == 0 ? &caches[i] : &caches[0], cf, B, T);
 
     /* Phase 2: loss anchoring */
-    const real *gf = params[1 + PL * L], *wlm = params[2 + PL * L];
+    const real *gf = params[1 + PL * L], *wlm = cf->tie_embeddings ? params[0] : params[2 + PL * L];
     real *zn = ralloc(n * d), *logits = ralloc(n * V), *dlogits = ralloc(n * V), *dzn = ralloc(n * d);
     real *g = ralloc(n * d), *gprev = ralloc(n * d);
+    real *dhead = cf->tie_embeddings ? ralloc(V * d) : grads[2 + PL * L]; /* tied: added to the table's gradient below */
     orc_rmsnorm_fwd(zn, h[L], gf, n, d, cf->rms_eps);
     orc_linear_fwd(logits, zn, wlm, n, d, V);
     orc_cross_entropy(loss, dlogits, logits, labels, n, V);
-    orc_linear_bwd_w(grads[2 + PL * L], dlogits, zn, n, d, V);
+    orc_linear_bwd_w(dhead, dlogits, zn, n, d, V);
     orc_linear_bwd_x(dzn, dlogits, wlm, n, d, V);
     orc_rmsnorm_bwd(g, grads[1 + PL * L], dzn, h[L], gf, n, d, cf->rms_eps);
 
@@ -593,6 +597,10 @@ int orc_train_step(const orc_cfg *cf, const real *const *params, const int32_t *
         }
     }
     orc_embed_bwd(grads[0], g, tokens, n, V, d);
+    if (cf->tie_embeddings) {
+        for (int64_t i = 0; i < V * d; ++i) grads[0][i] += dhead[i];
+        free(dhead);
+    }
 
     free(ydummy); free(zn); free(logits); free(dlogits); free(dzn); free(g); free(gprev);
     for (int64_t i = 0; i < ncache; ++i) cache_free(&caches[i]);
@@ -619,7 +627,7 @@ int orc_forward_loss(const orc_cfg *cf, const real *const *params, const int32_t
     if (hL_out) memcpy(hL_out, x, sizeof(real) * (size_t)(n * d));
     real *zn = ralloc(n * d), *logits = logits_out ? logits_out : ralloc(n * V);
     orc_rmsnorm_fwd(zn, x, params[1 + PL * L], n, d, cf->rms_eps);
-    orc_linear_fwd(logits, zn, params[2 + PL * L], n, d, V);
+    orc_linear_fwd(logits, zn, cf->tie_embeddings ? params[0] : params[2 + PL * L], n, d, V);
     orc_cross_entropy(loss, NULL, logits, labels, n, V);
     if (!logits_out) free(logits);
     free(zn); free(x); free(y);

@@ -39,9 +39,11 @@ def small_problem(shape, B=2, T=8, seed=3, std=0.3):
 
 # ----------------------------------------------------------------------------- finite differences
 SMALL_GQA_BIAS = replace(SMALL_GQA, qkv_bias=True)
+SMALL_TIED = replace(SMALL_GQA, qkv_bias=True, tie_embeddings=True)
 
 
-@pytest.mark.parametrize("shape", [SMALL_MHA, SMALL_GQA, SMALL_GQA_BIAS], ids=["mha", "gqa", "gqa-bias"])
+@pytest.mark.parametrize("shape", [SMALL_MHA, SMALL_GQA, SMALL_GQA_BIAS, SMALL_TIED],
+                         ids=["mha", "gqa", "gqa-bias", "tied"])
 def test_backward_matches_central_differences(orc64, shape):
     params, tokens, labels = small_problem(shape)
     loss, grads = orc64.train_step(shape, params, tokens, labels, mode=1)
@@ -97,11 +99,13 @@ def torch_model_loss(shape, tparams, tokens, labels):
         h = h + F.linear(a, wo)
         yn = F.rms_norm(h, (d,), g2, shape.rms_eps)
         h = h + F.linear(F.silu(F.linear(yn, wg)) * F.linear(yn, wu), wd)
-    z = F.linear(F.rms_norm(h, (d,), tparams[-2], shape.rms_eps), tparams[-1])
+    gf, wlm = (tparams[-1], tparams[0]) if shape.tie_embeddings else (tparams[-2], tparams[-1])
+    z = F.linear(F.rms_norm(h, (d,), gf, shape.rms_eps), wlm)
     return F.cross_entropy(z.view(B * T, -1), lab.view(-1), ignore_index=-100)
 
 
-@pytest.mark.parametrize("shape", [SMALL_MHA, SMALL_GQA, SMALL_GQA_BIAS], ids=["mha", "gqa", "gqa-bias"])
+@pytest.mark.parametrize("shape", [SMALL_MHA, SMALL_GQA, SMALL_GQA_BIAS, SMALL_TIED],
+                         ids=["mha", "gqa", "gqa-bias", "tied"])
 def test_step_matches_torch_autograd(orc64, shape):
     params, tokens, labels = small_problem(shape, B=3, T=11, seed=5)
     loss, grads = orc64.train_step(shape, params, tokens, labels, mode=1)
