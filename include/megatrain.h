@@ -38,6 +38,7 @@
  *     1 + 9 l + 8       w_down     [hidden, ffn]
  *     1 + 9 L           final_norm [hidden]
  *     2 + 9 L           lm_head    [vocab, hidden]
+ * With cfg.tie_embeddings = 1 the list ends with final_norm (index 1 + 9 L) and tensor 0 is also the head.
  * With cfg.qkv_bias = 1 a layer has 12 tensors (replace 9 by 12 above) and
  *     1 + 12 l + 9      bq         [n_q_heads*head_dim]
  *     1 + 12 l + 10     bk         [n_kv_heads*head_dim]
@@ -71,7 +72,7 @@ typedef int32_t mt_status;
 #define MT_ERR_TOKEN_RANGE (-7) /* token < 0 or >= vocab, or label >= vocab                      */
 #define MT_ERR_STATE (-8)       /* call out of order (e.g. Adam before any training step)        */
 
-#define MT_ABI_VERSION 1
+#define MT_ABI_VERSION 2
 
 /* diagnostic flags (mt_model_cfg.flags) */
 #define MT_FLAG_SERIAL 1u       /* no overlap: every copy and every unit is followed by a device sync.
@@ -105,6 +106,11 @@ typedef struct {
     uint32_t qkv_bias; /* 1: every layer has bias vectors for the q, k and v projections (12 tensors per layer: the 9
                         * below, then bq, bk, bv); 0: none */
     uint64_t max_device_bytes; /* 0 = no cap; otherwise mt_create fails with MT_ERR_DEVICE_OOM above it */
+    uint32_t tie_embeddings;   /* 1: the output projection reuses the embedding table (Appendix A.1, tied weights):
+                                * the tensor list ends with final_norm (no lm_head); the table is streamed again for
+                                * the loss, and its gradient is the head's weight gradient plus the embedding's
+                                * scatter-add, summed on the host */
+    uint32_t reserved;         /* 0 */
 } mt_model_cfg;
 
 typedef struct {
@@ -139,7 +145,7 @@ mt_status mt_tensor_count(const mt_model_cfg *cfg, int32_t *n);
  * thread-local storage valid until the next call on the same thread. */
 mt_status mt_tensor_info(const mt_model_cfg *cfg, int32_t idx, int64_t *rows, int64_t *cols, const char **name);
 
-/* Create a handle.  host_param_ptrs[9L+3] (12L+3 with qkv_bias) are the caller's fp32 master parameters in
+/* Create a handle.  host_param_ptrs[9L+3] (12L+3 with qkv_bias; one fewer with tie_embeddings) are the caller's fp32 master parameters in
  * canonical order (Section 3.1: the host copy is authoritative).  They stay owned by the
  * caller, must outlive the handle, may be pageable memory and are modified only by
  * mt_adam_step.  The library allocates: a pinned bf16 copy of every unit's weights laid out

@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "MT_OK", -1: "MT_ERR_INVALID_ARG", -2: "MT_ERR_UNSUPPORTED", 
 FLAG_SERIAL, FLAG_COMPUTE_ONLY, FLAG_COPY_ONLY, FLAG_KERNEL_TIMING, FLAG_GRAD_SLABS = 1, 2, 4, 8, 16
 FLAG_STAGED_WEIGHTS = 32
 KIND_GRAD, KIND_ADAM_M, KIND_ADAM_V = 0, 1, 2
-ABI_VERSION = 1
+ABI_VERSION = 2
 
 
 class MtError(RuntimeError):
@@ -37,14 +37,15 @@ class ModelCfg(ctypes.Structure):
                 ("max_batch", c_int32), ("max_seq", c_int32),
                 ("rope_base", c_float), ("rms_eps", c_float),
                 ("ckpt_interval", c_int32), ("device_id", c_int32), ("flags", c_uint32), ("qkv_bias", c_uint32),
-                ("max_device_bytes", c_uint64)]
+                ("max_device_bytes", c_uint64), ("tie_embeddings", c_uint32), ("reserved", c_uint32)]
 
     @classmethod
     def make(cls, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, max_batch, max_seq,
-             rope_base=10000.0, rms_eps=1e-5, ckpt_interval=1, device_id=0, flags=0, max_device_bytes=0, qkv_bias=False):
+             rope_base=10000.0, rms_eps=1e-5, ckpt_interval=1, device_id=0, flags=0, max_device_bytes=0, qkv_bias=False,
+             tie_embeddings=False):
         return cls(ctypes.sizeof(cls), ABI_VERSION, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab,
                    max_batch, max_seq, rope_base, rms_eps, ckpt_interval, device_id, flags, int(bool(qkv_bias)),
-                   max_device_bytes)
+                   max_device_bytes, int(bool(tie_embeddings)), 0)
 
 
 class Stats(ctypes.Structure):

@@ -72,6 +72,8 @@ struct Dims {
     int64_t Nq, Nkv, Nqkv;
     int bias = 0;  // q, k, v projections carry biases
     int PL = 9;    // tensors per layer in the canonical order
+    int tied = 0;  // the output projection reuses the embedding table (no lm_head tensor)
+    int n_tensors() const { return PL * L + (tied ? 2 : 3); }
 };
 
 struct TensorRef {
@@ -117,6 +119,7 @@ Dims dims_of(const mt_model_cfg *c) {
     D.Nq = (int64_t)D.Hq * D.hd; D.Nkv = (int64_t)D.Hkv * D.hd; D.Nqkv = D.Nq + 2 * D.Nkv;
     D.bias = c->qkv_bias ? 1 : 0;
     D.PL = D.bias ? 12 : 9;
+    D.tied = c->tie_embeddings ? 1 : 0;
     return D;
 }
 
@@ -134,14 +137,13 @@ LayerOff layer_off(const Dims &D) {
 }
 
 void tensor_shape(const Dims &D, int idx, int64_t *rows, int64_t *cols, std::string *name) {
-    const int n = D.PL * D.L + 3;
     auto set = [&](int64_t r, int64_t c, const std::string &s) {
         *rows = r; *cols = c;
         if (name) *name = s;
     };
     if (idx == 0) return set(D.V, D.d, "embed");
-    if (idx == n - 2) return set(D.d, 1, "final_norm");
-    if (idx == n - 1) return set(D.V, D.d, "lm_head");
+    if (idx == 1 + D.PL * D.L) return set(D.d, 1, "final_norm");
+    if (idx == 2 + D.PL * D.L) return set(D.V, D.d, "lm_head");
     const int l = (idx - 1) / D.PL, k = (idx - 1) % D.PL;
     const std::string p = "l" + std::to_string(l) + ".";
     switch (k) {
@@ -522,10 +524,11 @@ class HostWorker {
         return true;
     }
     // add = true: the slab is added to the gradient block instead of replacing it (micro-batch accumulation)
-    void push(int r, int unit, int slab, bool add) {
+    // run_adam = false: only land the gradient (a tied table's head part; its update follows the embedding part)
+    void push(int r, int unit, int slab, bool add, size_t count, bool run_adam) {
         {
             std::lock_guard<std::mutex> lk(mu_);
-            q_.push_back({r, unit, slab, add});
+            q_.push_back({r, unit, slab, add, count, run_adam});
         }
         cv_.notify_one();
     }
@@ -546,7 +549,7 @@ class HostWorker {
     bool failed() const { return failed_; }
 
   private:
-    struct Item { int r, unit, slab; bool add; };
+    struct Item { int r, unit, slab; bool add; size_t count; bool run_adam; };
     void run() {
         if (hipSetDevice(h_->cfg.device_id) != hipSuccess) set_failed();
         for (;;) {
@@ -573,11 +576,11 @@ class HostWorker {
                 if (item.add) {
                     const float *sf = h_->slabs[item.slab];
                     float *df = u.h_grad;
-                    parallel_for(u.numel, 1 << 20, [&](size_t b, size_t e) {
+                    parallel_for(item.count, 1 << 20, [&](size_t b, size_t e) {
                         for (size_t i = b; i < e; ++i) df[i] += sf[i];
                     });
                 } else {
-                    parallel_for(u.numel * sizeof(float), 1 << 22, [&](size_t b, size_t e) { memcpy(dst + b, src + b, e - b); });
+                    parallel_for(item.count * sizeof(float), 1 << 22, [&](size_t b, size_t e) { memcpy(dst + b, src + b, e - b); });
                 }
                 {
                     std::lock_guard<std::mutex> lk(mu_);
@@ -585,7 +588,7 @@ class HostWorker {
                 }
                 cv_main_.notify_all();
             }
-            if (has_opt_) adam_unit(h_, item.unit, hp_);
+            if (has_opt_ && item.run_adam) adam_unit(h_, item.unit, hp_);
             busy_ms_ += now_ms() - t0;
         }
     }
@@ -617,11 +620,12 @@ class PackWorker {
   public:
     explicit PackWorker(mt_handle *h) : h_(h), slab_user_(h->wslabs.size(), -1) { th_ = std::thread([this] { run(); }); }
     ~PackWorker() { finish(); }
-    int request(int s, int unit) {
+    // pieces: (unit, element offset of that unit's image inside the slab)
+    int request(int s, const std::vector<std::pair<int, size_t>> &pieces) {
         const int slab = (int)(n_req_++ % h_->wslabs.size());
         {
             std::lock_guard<std::mutex> lk(mu_);
-            q_.push_back({s, unit, slab});
+            q_.push_back({s, slab, pieces});
         }
         cv_.notify_all();
         return slab;
@@ -650,7 +654,7 @@ class PackWorker {
     double busy_ms() const { return busy_ms_; }
 
   private:
-    struct Item { int s, unit, slab; };
+    struct Item { int s, slab; std::vector<std::pair<int, size_t>> pieces; };
     void run() {
         if (hipSetDevice(h_->cfg.device_id) != hipSuccess) return set_failed();
         for (;;) {
@@ -674,10 +678,11 @@ class PackWorker {
             }
             const double t0 = now_ms();
             uint16_t *dst = h_->wslabs[it.slab];
-            for (int i = 0; i < h_->n_tensors; ++i) {
-                const TensorRef &t = h_->tref[i];
-                if (t.unit == it.unit) host_f32_to_bf16(dst + t.off, h_->params[i], t.numel);
-            }
+            for (const auto &pc : it.pieces)
+                for (int i = 0; i < h_->n_tensors; ++i) {
+                    const TensorRef &t = h_->tref[i];
+                    if (t.unit == pc.first) host_f32_to_bf16(dst + pc.second + t.off, h_->params[i], t.numel);
+                }
             busy_ms_ += now_ms() - t0;
             {
                 std::lock_guard<std::mutex> lk(mu_);
@@ -719,13 +724,13 @@ const char *mt_last_error(void) { return g_err; }
 mt_status mt_tensor_count(const mt_model_cfg *cfg, int32_t *n) {
     if (!cfg || !n) return fail(MT_ERR_INVALID_ARG, "NULL argument");
     if (cfg->n_layers <= 0) return fail(MT_ERR_INVALID_ARG, "n_layers must be positive");
-    *n = (cfg->qkv_bias ? 12 : 9) * cfg->n_layers + 3;
+    *n = dims_of(cfg).n_tensors();
     return MT_OK;
 }
 
 mt_status mt_tensor_info(const mt_model_cfg *cfg, int32_t idx, int64_t *rows, int64_t *cols, const char **name) {
     if (!cfg || !rows || !cols) return fail(MT_ERR_INVALID_ARG, "NULL argument");
-    if (cfg->n_layers <= 0 || idx < 0 || idx >= (cfg->qkv_bias ? 12 : 9) * cfg->n_layers + 3)
+    if (cfg->n_layers <= 0 || idx < 0 || idx >= dims_of(cfg).n_tensors())
         return fail(MT_ERR_INVALID_ARG, "tensor index out of range");
     static thread_local std::string nm;
     const Dims D = dims_of(cfg);
@@ -757,7 +762,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     if (cfg->max_batch <= 0 || cfg->max_seq <= 0) return fail(MT_ERR_INVALID_ARG, "max_batch and max_seq must be positive");
     if (cfg->max_seq & 7) return fail(MT_ERR_UNSUPPORTED, "max_seq must be a multiple of 8");
     const Dims D = dims_of(cfg);
-    const int nt = D.PL * D.L + 3;
+    const int nt = D.n_tensors();
     for (int i = 0; i < nt; ++i)
         if (!host_param_ptrs[i]) return fail(MT_ERR_INVALID_ARG, "host_param_ptrs[%d] is NULL", i);
     const int64_t n = (int64_t)cfg->max_batch * cfg->max_seq;
@@ -777,7 +782,8 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     h->units.resize(D.L + 2);
     h->units[0].numel = (size_t)D.V * D.d;
     for (int l = 1; l <= D.L; ++l) h->units[l].numel = h->lo.total;
-    h->units[D.L + 1].numel = (size_t)D.V * D.d + D.d;
+    // head unit: lm_head | final_norm; with tied embeddings only final_norm (the table is unit 0)
+    h->units[D.L + 1].numel = D.tied ? (size_t)D.d : (size_t)D.V * D.d + D.d;
     h->tref.resize(nt);
     h->tref[0] = {0, 0, (size_t)D.V * D.d};
     for (int l = 0; l < D.L; ++l) {
@@ -798,9 +804,13 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
             h->tref[b + 11] = {u, o.bqkv + (size_t)(D.Nq + D.Nkv), (size_t)D.Nkv};
         }
     }
-    h->tref[nt - 2] = {D.L + 1, (size_t)D.V * D.d, (size_t)D.d};
-    h->tref[nt - 1] = {D.L + 1, 0, (size_t)D.V * D.d};
-    h->pmax = 0;
+    if (D.tied) {
+        h->tref[nt - 1] = {D.L + 1, 0, (size_t)D.d};
+    } else {
+        h->tref[nt - 2] = {D.L + 1, (size_t)D.V * D.d, (size_t)D.d};
+        h->tref[nt - 1] = {D.L + 1, 0, (size_t)D.V * D.d};
+    }
+    h->pmax = (size_t)D.V * D.d + D.d;  // the head's device image (table | final norm), also when the table is tied
     size_t total = 0;
     for (auto &u : h->units) {
         h->pmax = std::max(h->pmax, u.numel);
@@ -1161,6 +1171,19 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     std::vector<char> load_issued(nloads, 0);
     h->resident[0] = h->resident[1] = -1;
     uint64_t h2d_bytes = 0, d2h_bytes = 0;
+    // What load s copies: (unit, element offset inside the weight buffer).  With tied embeddings the head's
+    // image is the embedding unit's table followed by the head unit (the final norm gain).
+    auto load_pieces = [&](int s) {
+        std::vector<std::pair<int, size_t>> v;
+        const int u = load_unit[s];
+        if (D.tied && u == D.L + 1) {
+            v.push_back({0, 0});
+            v.push_back({u, (size_t)D.V * D.d});
+        } else {
+            v.push_back({u, 0});
+        }
+        return v;
+    };
     std::unique_ptr<PackWorker> packer;
     if (h->staged) packer.reset(new PackWorker(h));
     std::vector<int> load_slab(nloads, -1);  // staged mode: slab of a requested load
@@ -1169,7 +1192,7 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
         if (!packer || s >= nloads || load_slab[s] >= 0) return;
         const int resident_then = s >= 2 ? load_unit[s - 2] : -1;  // loads alternate between the two buffers
         if (resident_then == load_unit[s]) return;
-        load_slab[s] = packer->request(s, load_unit[s]);
+        load_slab[s] = packer->request(s, load_pieces(s));
     };
     if (no_copy) {
         // weights of block 1 in both buffers once, so the kernels see finite numbers
@@ -1187,22 +1210,24 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     auto issue_load = [&](int s) -> mt_status {
         const int u = load_unit[s], b = s & 1;
         if (no_copy || h->resident[b] == u) return MT_OK;
-        const uint16_t *src = h->units[u].h_shadow;
         if (packer) {
             request_pack(s);
             request_pack(s + 1);  // one load of lookahead keeps the packer busy while this copy runs
             if (load_slab[s] < 0 || !packer->wait_packed(s))
                 return fail(MT_ERR_HIP, "the weight packing thread failed before load %d", s);
-            src = h->wslabs[load_slab[s]];
         }
         if (s >= 2) HIPCHK(hipStreamWaitEvent(sh, h->w_free[s - 2], 0));
         HIPCHK(hipEventRecord(h->h2d_start[s], sh));
-        HIPCHK(hipMemcpyAsync(h->Wbuf[b], src, h->units[u].numel * 2, hipMemcpyHostToDevice, sh));
+        for (const auto &pc : load_pieces(s)) {
+            const size_t cnt = h->units[pc.first].numel;
+            const uint16_t *src = packer ? h->wslabs[load_slab[s]] + pc.second : h->units[pc.first].h_shadow;
+            HIPCHK(hipMemcpyAsync(h->Wbuf[b] + pc.second, src, cnt * 2, hipMemcpyHostToDevice, sh));
+            h2d_bytes += cnt * 2;
+        }
         HIPCHK(hipEventRecord(h->w_ready[s], sh));
         if (packer) packer->copy_enqueued(s);
         h->resident[b] = u;
         load_issued[s] = 1;
-        h2d_bytes += h->units[u].numel * 2;
         if (serial) HIPCHK(hipDeviceSynchronize());
         return MT_OK;
     };
@@ -1210,30 +1235,48 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     std::unique_ptr<HostWorker> worker;
     const bool apply_opt = opt && !no_copy && !no_kern;
     // accumulation needs a host-side add, so the copies of such a step go through the slab pool too
-    const bool use_slabs = (h->grad_slabs || accumulate) && !no_copy;
+    const bool use_slabs = (h->grad_slabs || accumulate || D.tied) && !no_copy;
     if (use_slabs) {
         const mt_status es = ensure_slabs(h);
         if (es != MT_OK) return es;
     }
     if (apply_opt || use_slabs) worker.reset(new HostWorker(h, apply_opt ? opt : nullptr));
+    // Gradient block r lives in Gbuf[r & 1] as the image of unit u.  It normally goes to the host as one piece;
+    // with tied embeddings the head's image (table gradient | final norm gradient) goes to two units, and the
+    // embedding's scatter-add is added to the table gradient that the head left there.
+    struct GPiece { int unit; size_t dev_off, count; bool add, run_adam; };
+    size_t slab_seq = 0;
     auto issue_offload = [&](int r, int u) -> mt_status {
         HIPCHK(hipEventRecord(h->g_ready[r], sc));
         if (no_copy) return MT_OK;
+        std::vector<GPiece> pieces;
+        if (D.tied && u == D.L + 1) {
+            pieces.push_back({0, 0, (size_t)D.V * D.d, accumulate, false});
+            pieces.push_back({u, (size_t)D.V * D.d, (size_t)D.d, accumulate, true});
+        } else {
+            pieces.push_back({u, 0, h->units[u].numel, accumulate || (D.tied && u == 0), true});
+        }
         HIPCHK(hipStreamWaitEvent(sd, h->g_ready[r], 0));
         HIPCHK(hipEventRecord(h->d2h_start[r], sd));
-        int slab = -1;
-        float *dst = h->units[u].h_grad;
-        if (use_slabs) {
-            // back-pressure of the slab pool: wait (on the host) until the slab's previous content is folded away
-            slab = r % h->n_slabs;
-            if (!worker->acquire_slab(slab)) return fail(MT_ERR_HIP, "the host worker failed while draining a gradient slab");
-            dst = h->slabs[slab];
+        std::vector<int> slab_of(pieces.size(), -1);
+        for (size_t i = 0; i < pieces.size(); ++i) {
+            const GPiece &pc = pieces[i];
+            float *dst = h->units[pc.unit].h_grad;
+            if (h->grad_slabs || pc.add) {
+                // back-pressure of the slab pool: wait (on the host) until the slab's previous content is folded away
+                const int slab = (int)(slab_seq++ % (size_t)h->n_slabs);
+                if (!worker->acquire_slab(slab)) return fail(MT_ERR_HIP, "the host worker failed while draining a gradient slab");
+                dst = h->slabs[slab];
+                slab_of[i] = slab;
+            }
+            HIPCHK(hipMemcpyAsync(dst, h->Gbuf[r & 1] + pc.dev_off, pc.count * 4, hipMemcpyDeviceToHost, sd));
+            d2h_bytes += pc.count * 4;
         }
-        HIPCHK(hipMemcpyAsync(dst, h->Gbuf[r & 1], h->units[u].numel * 4, hipMemcpyDeviceToHost, sd));
         HIPCHK(hipEventRecord(h->g_free[r], sd));
         grad_issued[r] = 1;
-        d2h_bytes += h->units[u].numel * 4;
-        if (worker) worker->push(r, u, slab, accumulate);
+        if (worker)
+            for (size_t i = 0; i < pieces.size(); ++i)
+                worker->push(r, pieces[i].unit, slab_of[i], pieces[i].add, pieces[i].count, pieces[i].run_adam);
         if (serial) HIPCHK(hipDeviceSynchronize());
         return MT_OK;
     };

@@ -25,7 +25,7 @@ LOSS_RTOL, GRAD_COS, GRAD_L2, PARAM_L2 = 1e-2, 0.999, 3e-2, 1e-3
 def make_cfg(shape, B, T, flags=0, **kw):
     return ModelCfg.make(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
                          shape.vocab, B, T, rope_base=shape.rope_base, rms_eps=shape.rms_eps, flags=flags,
-                         qkv_bias=shape.qkv_bias, **kw)
+                         qkv_bias=shape.qkv_bias, tie_embeddings=shape.tie_embeddings, **kw)
 
 
 def gpu_step(shape, B, T, params, tok, lab, flags=0):
@@ -211,6 +211,42 @@ def test_qkv_bias_layers_match_oracle(orc64, K, flags):
         loss2 = h.train_step(tok, lab)          # the updated biases are streamed in the next step
         ref2, _ = orc64.train_step(shape, ps, tok, lab, mode=1)
         assert abs(loss2 - ref2) <= LOSS_RTOL * abs(ref2)
+
+
+@pytest.mark.parametrize("K,flags", [(1, 0), (2, mt.FLAG_STAGED_WEIGHTS), (1, mt.FLAG_GRAD_SLABS), (3, mt.FLAG_SERIAL)])
+def test_tied_embeddings_match_oracle(orc64, K, flags):
+    """Output projection tied to the embedding table: one tensor fewer, the table streamed a second time for the
+    loss, its gradient = head weight gradient + scatter-add (summed on the host).  Loss, gradients, separate and
+    overlapped Adam, and micro-batch accumulation."""
+    shape = ModelShape(3, 128, 4, 2, 64, 264, 520, qkv_bias=True, tie_embeddings=True)
+    table = mt_inputs.tensor_table(shape)
+    assert len(table) == 12 * 3 + 2 and table[-1][0] == "final_norm"
+    params = mt_inputs.make_params(shape, seed=71, std=0.05)
+    tok, lab = mt_inputs.make_batch(shape.vocab, 2, 72, seed=72)
+    pa, pb = [p.copy() for p in params], [p.copy() for p in params]
+    with mt.TrainHandle(make_cfg(shape, 2, 72, flags=flags, ckpt_interval=K), pa) as ha, \
+            mt.TrainHandle(make_cfg(shape, 2, 72, flags=flags, ckpt_interval=K), pb) as hb:
+        loss = ha.train_step(tok, lab)
+        grads = [g.copy() for g in ha.grads()]
+        ref_loss, ref_grads = check_against_oracle(orc64, shape, 2, 72, params, tok, lab, loss, grads)
+        # the table gradient really has both parts: it differs from the scatter-add alone (rows of unseen tokens)
+        unseen = np.setdiff1d(np.arange(shape.vocab), tok.ravel())
+        assert np.linalg.norm(grads[0][unseen]) > 0
+        ha.adam_step(1e-3, step=1)
+        assert hb.train_step_adam(tok, lab, 1e-3, step=1) == loss
+        for i, (a, b) in enumerate(zip(pa, pb)):
+            assert np.array_equal(a, b), i
+        # second step sees the updated table in both of its roles
+        l2 = ha.train_step(tok, lab)
+        ref2, _ = orc64.train_step(shape, pa, tok, lab, mode=1)
+        assert abs(l2 - ref2) <= LOSS_RTOL * abs(ref2)
+        g2 = [g.copy() for g in ha.grads()]
+        ha.train_step_accumulate(tok, lab)
+        for i, (a, g) in enumerate(zip(ha.grads(), g2)):
+            if i == 0:      # ((head + scatter) + head) + scatter: same sum, another order of fp32 additions
+                assert np.allclose(a, g + g, rtol=1e-5, atol=1e-9)
+            else:
+                assert np.array_equal(a, g + g)
 
 
 def test_staged_weights_equal_pinned_bf16_copy():
