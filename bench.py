@@ -29,7 +29,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
-SAMPLE_TOKENS = {"tiny": 256, "1.3B": 2048, "7B": 1024, "14B": 768, "7B-128k": 1024}
+SAMPLE_TOKENS = {"tiny": 256, "1.3B": 2048, "7B": 1024, "14B": 768, "7B-128k": 1024, "7B-256k": 1024, "7B-512k": 1024}
 
 
 def mem_available_gb() -> float:
@@ -63,7 +63,7 @@ def cpu_baseline(name: str) -> dict:
     import oracle
     import paper_2604_05091_amd as mt
     oracle.build()
-    shape, _, T = mt_inputs.CONFIGS[name]
+    shape, _, T = {**mt_inputs.CONFIGS, **mt_inputs.LONG_CONTEXT}[name]
     Ls = 2 if name in ("tiny", "1.3B") else 1
     Ts = min(T, SAMPLE_TOKENS[name])
     Bs = 2 if name == "tiny" else 1
@@ -92,6 +92,7 @@ def main() -> int:
     ap.add_argument("--config", default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flags", type=int, default=0, help="extra MT_FLAG_* bits (diagnostics)")
+    ap.add_argument("--mlp-chunk", type=int, default=0, help="chunked MLP: tokens per chunk (0 = off)")
     ap.add_argument("--ckpt-interval", type=int, default=1,
                     help="checkpoint interval K of Algorithm 1 (the headline number is quoted at K = 1)")
     ap.add_argument("--separate-adam", action="store_true",
@@ -112,14 +113,15 @@ def main() -> int:
         return 3
 
     name = pick_config(args.config)
-    shape, B, T = mt_inputs.CONFIGS[name]
+    shape, B, T = {**mt_inputs.CONFIGS, **mt_inputs.LONG_CONTEXT}[name]
     n_params = mt_inputs.n_params(shape)
     t_setup = time.time()
     params = mt_inputs.make_params(shape, seed=0)
     tok, lab = mt_inputs.make_batch(shape.vocab, B, T, seed=1)
     cfg = mt.ModelCfg.make(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
                            shape.vocab, B, T, rope_base=shape.rope_base, rms_eps=shape.rms_eps,
-                           flags=mt.FLAG_KERNEL_TIMING | args.flags, ckpt_interval=args.ckpt_interval)
+                           flags=mt.FLAG_KERNEL_TIMING | args.flags, ckpt_interval=args.ckpt_interval,
+                           mlp_chunk=args.mlp_chunk)
     link = mt.link_probe(256 << 20, 4)     # copy-bandwidth probe of this session: the host-link roofline
     h = mt.TrainHandle(cfg, params)
     t_setup = time.time() - t_setup
@@ -203,7 +205,7 @@ def main() -> int:
                                f"{shape.n_kv_heads} heads x {shape.head_dim}, ffn {shape.ffn}, vocab {shape.vocab}, "
                                f"batch {B} x seq {T}", "n_params": n_params, "tokens_per_step": B * T,
                    "host_state": "fp32 master/grad/Adam on host, bf16 streamed weights",
-                   "ckpt_interval": args.ckpt_interval},
+                   "ckpt_interval": args.ckpt_interval, "mlp_chunk": args.mlp_chunk},
         "roofline": roofline,
         "train_step_ms": mean("step_ms"), "adam_step_ms": mean("adam_ms"),
         "train_only_tflops": (flops / (mean("step_ms") * 1e-3) / 1e12) if args.separate_adam else None,

@@ -110,7 +110,10 @@ typedef struct {
                                 * the tensor list ends with final_norm (no lm_head); the table is streamed again for
                                 * the loss, and its gradient is the head's weight gradient plus the embedding's
                                 * scatter-add, summed on the host */
-    uint32_t reserved;         /* 0 */
+    uint32_t mlp_chunk;        /* 0: the MLP of a block runs on all tokens at once.  m > 0 (multiple of 8): it runs in chunks of m
+                                * tokens (chunked MLP of the long-context runs, Section 4.6): gate/up/activation buffers are chunk-sized, nothing of
+                                * the MLP is saved, and the backward recomputes each chunk right before differentiating it
+                                * (same FLOPs: the block recomputation then skips the MLP) */
 } mt_model_cfg;
 
 typedef struct {

@@ -79,6 +79,11 @@ CONFIGS = {
     "14B": (ModelShape(48, 5120, 40, 8, 128, 13824, 32000, rope_base=1.0e6), 16, 4096),
     "7B-128k": (ModelShape(32, 4096, 32, 32, 128, 11008, 32000), 1, 131072),
 }
+# Longer contexts of the paper's long-context table (Section 4.6), beyond the five workloads above.
+LONG_CONTEXT = {
+    "7B-256k": (ModelShape(32, 4096, 32, 32, 128, 11008, 32000), 1, 262144),
+    "7B-512k": (ModelShape(32, 4096, 32, 32, 128, 11008, 32000), 1, 524288),
+}
 
 
 def tensor_table(s: ModelShape):

@@ -37,15 +37,15 @@ class ModelCfg(ctypes.Structure):
                 ("max_batch", c_int32), ("max_seq", c_int32),
                 ("rope_base", c_float), ("rms_eps", c_float),
                 ("ckpt_interval", c_int32), ("device_id", c_int32), ("flags", c_uint32), ("qkv_bias", c_uint32),
-                ("max_device_bytes", c_uint64), ("tie_embeddings", c_uint32), ("reserved", c_uint32)]
+                ("max_device_bytes", c_uint64), ("tie_embeddings", c_uint32), ("mlp_chunk", c_uint32)]
 
     @classmethod
     def make(cls, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, max_batch, max_seq,
              rope_base=10000.0, rms_eps=1e-5, ckpt_interval=1, device_id=0, flags=0, max_device_bytes=0, qkv_bias=False,
-             tie_embeddings=False):
+             tie_embeddings=False, mlp_chunk=0):
         return cls(ctypes.sizeof(cls), ABI_VERSION, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab,
                    max_batch, max_seq, rope_base, rms_eps, ckpt_interval, device_id, flags, int(bool(qkv_bias)),
-                   max_device_bytes, int(bool(tie_embeddings)), 0)
+                   max_device_bytes, int(bool(tie_embeddings)), int(mlp_chunk))
 
 
 class Stats(ctypes.Structure):

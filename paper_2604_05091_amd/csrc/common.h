@@ -68,10 +68,12 @@ struct TransposeArgs {
 hipError_t transpose_bf16(const TransposeArgs &t, hipStream_t s);
 
 hipError_t rmsnorm_fwd(bf16_t *y, const bf16_t *x, const bf16_t *gain, int64_t n, int32_t d, float eps, hipStream_t s);
-// dx_out = dres + rmsnorm_backward(dy; x, gain); dgain[d] fp32 (written). partial: >= rmsnorm_bwd_ws_floats(d) floats.
+// dx_out = dres + rmsnorm_backward(dy; x, gain); dgain[d] fp32 (written, or added to when accumulate_dgain:
+// rows processed in several calls). partial: >= rmsnorm_bwd_ws_floats(d) floats.
 size_t rmsnorm_bwd_ws_floats(int32_t d);
 hipError_t rmsnorm_bwd(bf16_t *dx_out, float *dgain, const bf16_t *dy, const bf16_t *x, const bf16_t *gain,
-                       const bf16_t *dres, float *partial, int64_t n, int32_t d, float eps, hipStream_t s);
+                       const bf16_t *dres, float *partial, int64_t n, int32_t d, float eps, hipStream_t s,
+                       int accumulate_dgain = 0);
 
 // In-place rotation of the first n_heads heads of each row of x [n, ld]; cos/sin tables [T, hd/2] fp32;
 // position of row r is r % T; sign +1 forward, -1 inverse.

@@ -183,12 +183,12 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(bf16_t *dx, float *par
     for (int j = threadIdx.x; j < d; j += 256) partial[(int64_t)blockIdx.x * d + j] = red[j];
 }
 
-__global__ __launch_bounds__(256) void colsum_kernel(float *out, const float *partial, int nrows, int d) {
+__global__ __launch_bounds__(256) void colsum_kernel(float *out, const float *partial, int nrows, int d, int accumulate) {
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= d) return;
     float s = 0.f;
     for (int r = 0; r < nrows; ++r) s += partial[(int64_t)r * d + j];
-    out[j] = s;
+    out[j] = accumulate ? out[j] + s : s;
 }
 
 // ------------------------------------------------------------------ bias gradient (column sums of a bf16 matrix)
@@ -444,7 +444,8 @@ hipError_t rmsnorm_fwd(bf16_t *y, const bf16_t *x, const bf16_t *gain, int64_t n
 size_t rmsnorm_bwd_ws_floats(int32_t d) { return (size_t)kNormBwdBlocks * (size_t)d; }
 
 hipError_t rmsnorm_bwd(bf16_t *dx_out, float *dgain, const bf16_t *dy, const bf16_t *x, const bf16_t *gain,
-                       const bf16_t *dres, float *partial, int64_t n, int32_t d, float eps, hipStream_t s) {
+                       const bf16_t *dres, float *partial, int64_t n, int32_t d, float eps, hipStream_t s,
+                       int accumulate_dgain) {
     if (n <= 0 || d <= 0 || (d & 7) || d > 8192) return hipErrorInvalidValue;
     const unsigned grid = (unsigned)((n + 3) / 4 < kNormBwdBlocks ? (n + 3) / 4 : kNormBwdBlocks);
     const size_t lds = (size_t)d * sizeof(float);
@@ -459,7 +460,8 @@ hipError_t rmsnorm_bwd(bf16_t *dx_out, float *dgain, const bf16_t *dy, const bf1
                            n, d, eps);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(d, 256)), dim3(256), 0, s, dgain, partial, (int)grid, d);
+    hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(d, 256)), dim3(256), 0, s, dgain, partial, (int)grid, d,
+                       accumulate_dgain);
     return hipGetLastError();
 }
 
@@ -472,7 +474,7 @@ hipError_t bias_grad(float *db, const bf16_t *x, int64_t ld, int64_t n, int32_t 
                        ld, n, cols, rpb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(cols, 256)), dim3(256), 0, s, db, ws, kBiasGradRowBlocks, cols);
+    hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(cols, 256)), dim3(256), 0, s, db, ws, kBiasGradRowBlocks, cols, 0);
     return hipGetLastError();
 }
 

@@ -108,6 +108,7 @@ mt_status check_cfg(const mt_model_cfg *c) {
         return fail(MT_ERR_UNSUPPORTED, "hidden, ffn and vocab must be multiples of 8");
     if (c->hidden > 8192) return fail(MT_ERR_UNSUPPORTED, "hidden > 8192 is not supported");
     if (c->ckpt_interval < 1) return fail(MT_ERR_INVALID_ARG, "ckpt_interval must be >= 1");
+    if (c->mlp_chunk & 7) return fail(MT_ERR_INVALID_ARG, "mlp_chunk must be a multiple of 8");
     if (!(c->rope_base > 0.f) || !(c->rms_eps > 0.f)) return fail(MT_ERR_INVALID_ARG, "rope_base and rms_eps must be > 0");
     return MT_OK;
 }
@@ -195,7 +196,9 @@ struct mt_handle {
         xn = a.xn; yn = a.yn; qkv = a.qkv; att = a.att; h1 = a.h1; gu = a.gu; sact = a.sact; lse = a.lse;
     }
     uint16_t *xn, *yn, *qkv, *att, *h1, *gu, *sact;
-    uint16_t *dsact, *dgu, *dyn, *dh1, *datt, *dqkv, *dxn, *gA, *gB, *tA, *tB, *wT;
+    uint16_t *dsact, *dgu, *dyn, *dh1, *datt, *dqkv, *dxn, *gA, *gB, *tA, *tB, *wT, *wT2;
+    int64_t mlp_rows = 0;  // rows of the MLP buffers: all tokens, or cfg.mlp_chunk
+    bool mlp_chunked = false;
     uint16_t *dlogits, *dlT;
     float *lse, *delta, *logits, *loss_rows, *loss_dev, *norm_ws, *bias_ws, *rope_cos, *rope_sin;
     int32_t *tok_dev, *lab_dev, *rowstart_dev, *order_dev;
@@ -323,6 +326,16 @@ AttnArgs attn_args(const mt_handle *h, int B, int T) {
     return a;
 }
 
+// yn, gu, sact of m rows starting at h1 (the block's MLP up to the activation)
+mt_status mlp_forward_rows(mt_handle *h, const LayerW &w, const uint16_t *h1, int64_t m) {
+    const Dims &D = h->D;
+    hipStream_t s = h->s_comp;
+    KCHK(rmsnorm_fwd(h->yn, h1, w.g2, m, D.d, h->cfg.rms_eps, s));
+    KCHK(gemm(h, h->yn, D.d, w.wgu, D.d, h->gu, 2 * D.F, m, 2 * D.F, D.d));
+    KCHK(swiglu_fwd(h->sact, h->gu, m, D.F, s));
+    return MT_OK;
+}
+
 // f_i of Algorithm 1.  y may be NULL (recompute before backward does not need the block output).
 mt_status layer_forward(mt_handle *h, const LayerW &w, const uint16_t *x, uint16_t *y, int B, int T) {
     const Dims &D = h->D;
@@ -338,10 +351,17 @@ mt_status layer_forward(mt_handle *h, const LayerW &w, const uint16_t *x, uint16
         KCHK(flash_fwd(a, s));
     }
     KCHK(gemm(h, h->att, D.Nq, w.wo, D.Nq, h->h1, D.d, n, D.d, D.Nq, false, false, x, D.d));
-    KCHK(rmsnorm_fwd(h->yn, h->h1, w.g2, n, D.d, h->cfg.rms_eps, s));
-    KCHK(gemm(h, h->yn, D.d, w.wgu, D.d, h->gu, 2 * D.F, n, 2 * D.F, D.d));
-    KCHK(swiglu_fwd(h->sact, h->gu, n, D.F, s));
-    if (y) KCHK(gemm(h, h->sact, D.F, w.wd, D.F, y, D.d, n, D.d, D.F, false, false, h->h1, D.d));
+    // MLP, in chunks of mlp_rows tokens (one chunk unless cfg.mlp_chunk is set).  A chunked MLP saves nothing for
+    // the backward, so the recomputation pass (y == NULL) skips it.
+    if (h->mlp_chunked && !y) return MT_OK;
+    for (int64_t r0 = 0; r0 < n; r0 += h->mlp_rows) {
+        const int64_t m = std::min(h->mlp_rows, n - r0);
+        {
+            const mt_status st = mlp_forward_rows(h, w, h->h1 + r0 * D.d, m);
+            if (st != MT_OK) return st;
+        }
+        if (y) KCHK(gemm(h, h->sact, D.F, w.wd, D.F, y + r0 * D.d, D.d, m, D.d, D.F, false, false, h->h1 + r0 * D.d, D.d));
+    }
     return MT_OK;
 }
 
@@ -353,20 +373,29 @@ mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t
     const LayerOff &o = h->lo;
     const int64_t n = (int64_t)B * T;
     hipStream_t s = h->s_comp;
-    // y = h1 + s Wd^T
-    KCHK(transpose2d(s, gy, h->tA, n, D.d, D.d, n));
-    KCHK(transpose2d(s, h->sact, h->tB, n, D.F, D.F, n));
-    KCHK(gemm(h, h->tA, n, h->tB, n, G + o.wd, D.F, D.d, D.F, n, true));
+    // MLP: y = h1 + s Wd^T, gu = yn Wgu^T, in chunks of mlp_rows tokens.  Weight and gain gradients of the second
+    // and later chunks are added to the first chunk's; a chunked MLP is recomputed chunk by chunk here.
     KCHK(transpose2d(s, w.wd, h->wT, D.d, D.F, D.F, D.d));
-    KCHK(gemm(h, gy, D.d, h->wT, D.d, h->dsact, D.F, n, D.F, D.d));
-    KCHK(swiglu_bwd(h->dgu, h->dsact, h->gu, n, D.F, s));
-    // gu = yn Wgu^T
-    KCHK(transpose2d(s, h->dgu, h->tA, n, 2 * D.F, 2 * D.F, n));
-    KCHK(transpose2d(s, h->yn, h->tB, n, D.d, D.d, n));
-    KCHK(gemm(h, h->tA, n, h->tB, n, G + o.wgu, D.d, 2 * D.F, D.d, n, true));
-    KCHK(transpose2d(s, w.wgu, h->wT, 2 * D.F, D.d, D.d, 2 * D.F));
-    KCHK(gemm(h, h->dgu, 2 * D.F, h->wT, 2 * D.F, h->dyn, D.d, n, D.d, 2 * D.F));
-    KCHK(rmsnorm_bwd(h->dh1, G + o.g2, h->dyn, h->h1, w.g2, gy, h->norm_ws, n, D.d, h->cfg.rms_eps, s));
+    KCHK(transpose2d(s, w.wgu, h->wT2, 2 * D.F, D.d, D.d, 2 * D.F));
+    for (int64_t r0 = 0; r0 < n; r0 += h->mlp_rows) {
+        const int64_t m = std::min(h->mlp_rows, n - r0);
+        const bool acc = r0 > 0;
+        const uint16_t *gyc = gy + r0 * D.d, *h1c = h->h1 + r0 * D.d;
+        if (h->mlp_chunked) {
+            const mt_status st = mlp_forward_rows(h, w, h1c, m);
+            if (st != MT_OK) return st;
+        }
+        KCHK(transpose2d(s, gyc, h->tA, m, D.d, D.d, m));
+        KCHK(transpose2d(s, h->sact, h->tB, m, D.F, D.F, m));
+        KCHK(gemm(h, h->tA, m, h->tB, m, G + o.wd, D.F, D.d, D.F, m, true, acc));
+        KCHK(gemm(h, gyc, D.d, h->wT, D.d, h->dsact, D.F, m, D.F, D.d));
+        KCHK(swiglu_bwd(h->dgu, h->dsact, h->gu, m, D.F, s));
+        KCHK(transpose2d(s, h->dgu, h->tA, m, 2 * D.F, 2 * D.F, m));
+        KCHK(transpose2d(s, h->yn, h->tB, m, D.d, D.d, m));
+        KCHK(gemm(h, h->tA, m, h->tB, m, G + o.wgu, D.d, 2 * D.F, D.d, m, true, acc));
+        KCHK(gemm(h, h->dgu, 2 * D.F, h->wT2, 2 * D.F, h->dyn, D.d, m, D.d, 2 * D.F));
+        KCHK(rmsnorm_bwd(h->dh1 + r0 * D.d, G + o.g2, h->dyn, h1c, w.g2, gyc, h->norm_ws, m, D.d, h->cfg.rms_eps, s, acc));
+    }
     // h1 = x + att Wo^T
     KCHK(transpose2d(s, h->dh1, h->tA, n, D.d, D.d, n));
     KCHK(transpose2d(s, h->att, h->tB, n, D.Nq, D.Nq, n));
@@ -828,14 +857,12 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
         return o;
     };
     const size_t e2 = sizeof(uint16_t), e4 = sizeof(float);
-    const size_t tA_rows = (size_t)std::max<int64_t>(std::max<int64_t>(2 * D.F, D.Nqkv), D.d);
-    const size_t tB_rows = (size_t)std::max<int64_t>(std::max<int64_t>(D.F, D.Nq), D.d);
     const size_t wT_elems = std::max<size_t>(std::max<size_t>((size_t)2 * D.F * D.d, (size_t)D.Nqkv * D.d),
                                             std::max<size_t>((size_t)D.V * D.d, (size_t)D.d * D.Nq));
     struct ActPlan { size_t xn, yn, qkv, att, h1, gu, sact, lse; };
     struct Plan {
         size_t W[2], G[2], anchors, blk_h, dsact, dgu, dyn, dh1, datt, dqkv,
-            dxn, gA, gB, tA, tB, wT, dlogits, dlT, delta, logits, loss_rows, loss_dev, norm_ws, bias_ws, rope_cos, rope_sin,
+            dxn, gA, gB, tA, tB, wT, wT2, dlogits, dlT, delta, logits, loss_rows, loss_dev, norm_ws, bias_ws, rope_cos, rope_sin,
             tok, lab, rowstart, order;
     } P;
     const int K = std::min<int>(cfg->ckpt_interval, D.L);
@@ -846,18 +873,30 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     for (int i = 0; i < 2; ++i) P.G[i] = plan(h->pmax * e4);
     P.anchors = plan((size_t)n_ck * n * D.d * e2);
     P.blk_h = plan((size_t)(K - 1) * n * D.d * e2);
-    for (auto &ap : AP) {
-        ap.xn = plan(n * D.d * e2); ap.yn = plan(n * D.d * e2);
+    // MLP buffers hold all tokens, or one chunk; a chunked MLP keeps nothing per activation set
+    h->mlp_chunked = cfg->mlp_chunk > 0 && (int64_t)cfg->mlp_chunk < n;
+    const size_t mm = h->mlp_chunked ? (size_t)cfg->mlp_chunk : (size_t)n;
+    h->mlp_rows = (int64_t)mm;
+    for (size_t i = 0; i < AP.size(); ++i) {
+        ActPlan &ap = AP[i];
+        ap.xn = plan(n * D.d * e2);
         ap.qkv = plan(n * D.Nqkv * e2); ap.att = plan(n * D.Nq * e2); ap.h1 = plan(n * D.d * e2);
-        ap.gu = plan(n * 2 * D.F * e2); ap.sact = plan(n * D.F * e2);
         ap.lse = plan((size_t)n * D.Hq * e4);
+        if (h->mlp_chunked && i > 0) {
+            ap.yn = AP[0].yn; ap.gu = AP[0].gu; ap.sact = AP[0].sact;
+        } else {
+            ap.yn = plan(mm * D.d * e2); ap.gu = plan(mm * 2 * D.F * e2); ap.sact = plan(mm * D.F * e2);
+        }
     }
-    P.dsact = plan(n * D.F * e2); P.dgu = plan(n * 2 * D.F * e2);
-    P.dyn = plan(n * D.d * e2); P.dh1 = plan(n * D.d * e2); P.datt = plan(n * D.Nq * e2);
+    P.dsact = plan(mm * D.F * e2); P.dgu = plan(mm * 2 * D.F * e2);
+    P.dyn = plan(mm * D.d * e2); P.dh1 = plan(n * D.d * e2); P.datt = plan(n * D.Nq * e2);
     P.dqkv = plan(n * D.Nqkv * e2); P.dxn = plan(n * D.d * e2);
     P.gA = plan(n * D.d * e2); P.gB = plan(n * D.d * e2);
-    P.tA = plan(tA_rows * n * e2); P.tB = plan(tB_rows * n * e2);
+    // transposed-operand scratch: MLP operands have mlp_rows columns, the attention-side ones all tokens
+    P.tA = plan(std::max<size_t>((size_t)2 * D.F * mm, (size_t)std::max<int64_t>(D.Nqkv, D.d) * n) * e2);
+    P.tB = plan(std::max<size_t>((size_t)D.F * mm, (size_t)std::max<int64_t>(D.Nq, D.d) * n) * e2);
     P.wT = plan(wT_elems * e2);
+    P.wT2 = plan((size_t)2 * D.F * D.d * e2);
     P.dlogits = plan((size_t)chunk * D.V * e2); P.dlT = plan((size_t)chunk * D.V * e2);
     P.delta = plan((size_t)n * D.Hq * e4);
     P.logits = plan((size_t)chunk * D.V * e4);
@@ -919,7 +958,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     h->dgu = (uint16_t *)(A + P.dgu); h->dyn = (uint16_t *)(A + P.dyn); h->dh1 = (uint16_t *)(A + P.dh1);
     h->datt = (uint16_t *)(A + P.datt); h->dqkv = (uint16_t *)(A + P.dqkv); h->dxn = (uint16_t *)(A + P.dxn);
     h->gA = (uint16_t *)(A + P.gA); h->gB = (uint16_t *)(A + P.gB); h->tA = (uint16_t *)(A + P.tA);
-    h->tB = (uint16_t *)(A + P.tB); h->wT = (uint16_t *)(A + P.wT); h->dlogits = (uint16_t *)(A + P.dlogits);
+    h->tB = (uint16_t *)(A + P.tB); h->wT = (uint16_t *)(A + P.wT); h->wT2 = (uint16_t *)(A + P.wT2); h->dlogits = (uint16_t *)(A + P.dlogits);
     h->dlT = (uint16_t *)(A + P.dlT); h->delta = (float *)(A + P.delta);
     h->logits = (float *)(A + P.logits); h->loss_rows = (float *)(A + P.loss_rows);
     h->loss_dev = (float *)(A + P.loss_dev); h->norm_ws = (float *)(A + P.norm_ws);

@@ -249,6 +249,34 @@ def test_tied_embeddings_match_oracle(orc64, K, flags):
                 assert np.array_equal(a, g + g)
 
 
+def test_chunked_mlp_matches_unchunked_and_oracle(orc64):
+    """cfg.mlp_chunk: the MLP runs (and is recomputed in the backward) in token chunks, ragged last chunk.  The
+    forward is row-wise identical, so the loss is bit-identical; weight gradients are sums over chunks in a
+    different order; the device arena shrinks."""
+    shape = ModelShape(3, 128, 2, 2, 64, 264, 520)
+    params = mt_inputs.make_params(shape, seed=81, std=0.05)
+    tok, lab = mt_inputs.make_batch(shape.vocab, 2, 72, seed=82)     # 144 tokens: chunks 64 + 64 + 16
+
+    def run(chunk, K=1, flags=0):
+        ps = [p.copy() for p in params]
+        with mt.TrainHandle(make_cfg(shape, 2, 72, flags=flags, ckpt_interval=K, mlp_chunk=chunk), ps) as h:
+            loss = h.train_step(tok, lab)
+            return loss, [g.copy() for g in h.grads()], h.stats()
+
+    l0, g0, s0 = run(0)
+    for chunk, K in ((64, 1), (64, 2), (8, 3), (144, 1), (1024, 1)):
+        lc, gc, sc = run(chunk, K)
+        assert lc == l0, (chunk, K)
+        for i, (a, b) in enumerate(zip(g0, gc)):
+            assert rel_l2(b, a) < 1e-5, (chunk, K, i)
+            if chunk >= 144:        # a single chunk is the unchunked path
+                assert np.array_equal(a, b), (chunk, i)
+        if chunk < 144 and K == 1:
+            assert sc["device_arena_bytes"] < s0["device_arena_bytes"]
+    lc, gc, _ = run(64, 2, mt.FLAG_SERIAL | mt.FLAG_STAGED_WEIGHTS)
+    check_against_oracle(orc64, shape, 2, 72, params, tok, lab, lc, gc)
+
+
 def test_staged_weights_equal_pinned_bf16_copy():
     """MT_FLAG_STAGED_WEIGHTS: weights converted just in time into three recycled pinned slabs instead of
     being read from a persistent pinned bf16 copy.  Same bytes reach the GPU, so losses, gradients and the
