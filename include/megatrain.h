@@ -23,6 +23,10 @@
  *     throw.  After an error the handle can still be destroyed; outputs are unspecified.
  *     mt_last_error() gives a human-readable message for the calling thread.
  *   - One handle must be used by one thread at a time.
+ *   - Environment (read once): MT_HOST_THREADS = threads of the host Adam / conversion loops (default: all
+ *     cores); MT_PINNED_BUDGET_GB = pinned host memory the library may take before it switches to the
+ *     gradient slab pool (default 56); MT_PROGRESS=1 prints one line to stderr whenever the GPU finishes a
+ *     unit of a step (for steps that run for minutes); MT_GEMM_VARIANT forces one GEMM kernel (diagnostics).
  *
  * Canonical tensor order (index -> tensor), all fp32, row-major, matrices stored
  * [out_features, in_features] like a linear layer's weight:

@@ -1143,6 +1143,12 @@ mt_status ensure_slabs(mt_handle *h) {
     return MT_OK;
 }
 
+void progress_line(void *arg) {
+    const intptr_t v = (intptr_t)arg;
+    fprintf(stderr, "[megatrain] unit slot %d of %d done\n", (int)(v >> 16) + 1, (int)(v & 0xffff));
+    fflush(stderr);
+}
+
 mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
                           float *loss, const AdamHyper *opt, bool accumulate) {
     if (!h || !tokens || !labels || !loss) return fail(MT_ERR_INVALID_ARG, "NULL argument");
@@ -1223,6 +1229,10 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
         }
         return v;
     };
+    static const bool progress = [] {
+        const char *e = getenv("MT_PROGRESS");
+        return e && atoi(e) != 0;
+    }();
     std::unique_ptr<PackWorker> packer;
     if (h->staged) packer.reset(new PackWorker(h));
     std::vector<int> load_slab(nloads, -1);  // staged mode: slab of a requested load
@@ -1326,6 +1336,8 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     };
     auto end_unit = [&](int s) -> mt_status {
         HIPCHK(hipEventRecord(h->w_free[s], sc));
+        // MT_PROGRESS=1: one line on stderr when the GPU has finished a unit (steps that take minutes)
+        if (progress) HIPCHK(hipLaunchHostFunc(sc, progress_line, (void *)(intptr_t)((s << 16) | (nloads & 0xffff))));
         if (serial) HIPCHK(hipDeviceSynchronize());
         return MT_OK;
     };
