@@ -65,19 +65,13 @@ __attribute__((target_clones("avx512f", "avx2", "default"))) void adam_chunk(flo
                                                                             float decay, float lr, float b1, float b2,
                                                                             float eps, float inv_c1, float inv_c2) {
     const float ob1 = 1.0f - b1, ob2 = 1.0f - b2;
-    if (shadow) {
-        for (size_t i = 0; i < n; ++i) {
-            const float gi = g[i];
-            const float mi = b1 * m[i] + ob1 * gi;
-            const float vi = b2 * v[i] + ob2 * gi * gi;
-            const float pi = p[i] * decay - lr * (mi * inv_c1) / (sqrtf(vi * inv_c2) + eps);
-            m[i] = mi;
-            v[i] = vi;
-            p[i] = pi;
-            shadow[i] = bf16_rne(pi);
-        }
-    } else {
-        for (size_t i = 0; i < n; ++i) {
+    // Blocks of 2048 elements: the update loop and the bf16 conversion loop each vectorise fully on their own
+    // (fused into one loop the mixed 32/16-bit stores halve the throughput); the block is still in L1 when
+    // the conversion reads it back.
+    constexpr size_t kBlock = 2048;
+    for (size_t b0 = 0; b0 < n; b0 += kBlock) {
+        const size_t b1e = b0 + kBlock < n ? b0 + kBlock : n;
+        for (size_t i = b0; i < b1e; ++i) {
             const float gi = g[i];
             const float mi = b1 * m[i] + ob1 * gi;
             const float vi = b2 * v[i] + ob2 * gi * gi;
@@ -86,6 +80,8 @@ __attribute__((target_clones("avx512f", "avx2", "default"))) void adam_chunk(flo
             v[i] = vi;
             p[i] = pi;
         }
+        if (shadow)
+            for (size_t i = b0; i < b1e; ++i) shadow[i] = bf16_rne(p[i]);
     }
 }
 
