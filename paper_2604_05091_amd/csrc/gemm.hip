@@ -227,6 +227,77 @@ constexpr int W4_A_BYTES = W4_BM * LDT * 2, W4_STAGE_BYTES = 2 * W4_A_BYTES;
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// Epilogue of the 4-wave kernels.  The MFMAs are issued with the operands swapped (B fragment first), so each
+// 32x32 block holds C transposed: the lane owns row l32 of the block and, per group q = r/4, the four
+// consecutive columns 8 q + 4 hl + (0..3): one 8-byte (bf16) or 16-byte (fp32) store each.
+__device__ __forceinline__ void w4_store(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int n0, int wm, int wn,
+                                         int l32, int hl) {
+    constexpr int BM = W4_BM, BN = W4_BN;
+    const int row_l = m0 + wm * 128 + l32, col_l = n0 + wn * 128 + hl * 4;
+    const bool full = (m0 + BM <= g.M) && (n0 + BN <= g.N);
+    const bool vec = full && !(g.ldc & 3) && !((uintptr_t)g.C & 15) && (!g.R || (!(g.ldr & 3) && !((uintptr_t)g.R & 7))) &&
+                     !((uintptr_t)g.bias & 7);
+    if (g.out_fp32) {
+        float *cw = reinterpret_cast<float *>(g.C);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = row_l + i * 32;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = col_l + j * 32 + q * 8;
+                    float *cp = cw + (int64_t)row * g.ldc + col;
+                    if (vec) {
+                        f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                        if (g.accumulate) v += *reinterpret_cast<const f32x4 *>(cp);
+                        *reinterpret_cast<f32x4 *>(cp) = v;
+                    } else if (row < g.M) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < g.N) cp[e] = acc[i][j][4 * q + e] + (g.accumulate ? cp[e] : 0.f);
+                    }
+                }
+        }
+    } else {
+        bf16_t *cw = reinterpret_cast<bf16_t *>(g.C);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = row_l + i * 32;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = col_l + j * 32 + q * 8;
+                    bf16_t *cp = cw + (int64_t)row * g.ldc + col;
+                    const bf16_t *rp = g.R ? g.R + (int64_t)row * g.ldr + col : nullptr;
+                    if (vec) {
+                        float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2],
+                              v3 = acc[i][j][4 * q + 3];
+                        if (g.bias) {
+                            const uint2 bv = *reinterpret_cast<const uint2 *>(g.bias + col);
+                            v0 += bflo(bv.x); v1 += bfhi(bv.x); v2 += bflo(bv.y); v3 += bfhi(bv.y);
+                        }
+                        if (rp) {
+                            const uint2 rv = *reinterpret_cast<const uint2 *>(rp);
+                            v0 += bflo(rv.x); v1 += bfhi(rv.x); v2 += bflo(rv.y); v3 += bfhi(rv.y);
+                        }
+                        uint2 o;
+                        o.x = pack2bf(v0, v1);
+                        o.y = pack2bf(v2, v3);
+                        *reinterpret_cast<uint2 *>(cp) = o;
+                    } else if (row < g.M) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < g.N)
+                                cp[e] = f2bf(acc[i][j][4 * q + e] + (g.bias ? bf2f(g.bias[col + e]) : 0.f) +
+                                             (rp ? bf2f(rp[e]) : 0.f));
+                    }
+                }
+        }
+    }
+}
+
 __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles_m, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     constexpr int BM = W4_BM, BN = W4_BN;
@@ -368,72 +439,7 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
 #undef W4_PHASE
 #undef W4_STEP
 
-    // ---- epilogue.  The MFMAs were issued with the operands swapped (B fragment first), so each
-    // 32x32 block holds C transposed: the lane owns row l32 of the block and, per group q = r/4, the
-    // four consecutive columns 8 q + 4 hl + (0..3): one 8-byte (bf16) or 16-byte (fp32) store each.
-    const int row_l = m0 + wm * 128 + l32, col_l = n0 + wn * 128 + hl * 4;
-    const bool full = (m0 + BM <= g.M) && (n0 + BN <= g.N);
-    const bool vec = full && !(g.ldc & 3) && !((uintptr_t)g.C & 15) && (!g.R || (!(g.ldr & 3) && !((uintptr_t)g.R & 7))) &&
-                     !((uintptr_t)g.bias & 7);
-    if (g.out_fp32) {
-        float *cw = reinterpret_cast<float *>(g.C);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = row_l + i * 32;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int col = col_l + j * 32 + q * 8;
-                    float *cp = cw + (int64_t)row * g.ldc + col;
-                    if (vec) {
-                        f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                        if (g.accumulate) v += *reinterpret_cast<const f32x4 *>(cp);
-                        *reinterpret_cast<f32x4 *>(cp) = v;
-                    } else if (row < g.M) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < g.N) cp[e] = acc[i][j][4 * q + e] + (g.accumulate ? cp[e] : 0.f);
-                    }
-                }
-        }
-    } else {
-        bf16_t *cw = reinterpret_cast<bf16_t *>(g.C);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = row_l + i * 32;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int col = col_l + j * 32 + q * 8;
-                    bf16_t *cp = cw + (int64_t)row * g.ldc + col;
-                    const bf16_t *rp = g.R ? g.R + (int64_t)row * g.ldr + col : nullptr;
-                    if (vec) {
-                        float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2],
-                              v3 = acc[i][j][4 * q + 3];
-                        if (g.bias) {
-                            const uint2 bv = *reinterpret_cast<const uint2 *>(g.bias + col);
-                            v0 += bflo(bv.x); v1 += bfhi(bv.x); v2 += bflo(bv.y); v3 += bfhi(bv.y);
-                        }
-                        if (rp) {
-                            const uint2 rv = *reinterpret_cast<const uint2 *>(rp);
-                            v0 += bflo(rv.x); v1 += bfhi(rv.x); v2 += bflo(rv.y); v3 += bfhi(rv.y);
-                        }
-                        uint2 o;
-                        o.x = pack2bf(v0, v1);
-                        o.y = pack2bf(v2, v3);
-                        *reinterpret_cast<uint2 *>(cp) = o;
-                    } else if (row < g.M) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < g.N)
-                                cp[e] = f2bf(acc[i][j][4 * q + e] + (g.bias ? bf2f(g.bias[col + e]) : 0.f) +
-                                             (rp ? bf2f(rp[e]) : 0.f));
-                    }
-                }
-        }
-    }
+    w4_store(g, acc, m0, n0, wm, wn, l32, hl);
 }
 
 hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
@@ -449,6 +455,7 @@ hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
     hipLaunchKernelGGL(gemm_nt_w4_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(W4_NT), lds, s, g, tiles_m, tiles_n);
     return hipGetLastError();
 }
+
 
 int variant_override() {
     static int v = [] {
