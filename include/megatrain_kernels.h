@@ -39,6 +39,11 @@ int32_t mt_k_gemm_nt(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t 
  * projections of layers with biases. */
 int32_t mt_k_gemm_nt_bias(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, uint16_t *C, int64_t ldc,
                           const uint16_t *bias, int32_t M, int32_t N, int32_t K, void *stream);
+/* Weight-gradient form: C[M,N] fp32 = At^T . Bt with At [K, M] bf16 (lda) and Bt [K, N] bf16 (ldb), both
+ * token-major as the other kernels leave them (dW = dY^T X); accumulate != 0 adds to the existing C.
+ * Requires K % 64 == 0, M % 8 == 0, N % 8 == 0: MT_ERR_UNSUPPORTED otherwise (transpose and use mt_k_gemm_nt). */
+int32_t mt_k_gemm_tn(const uint16_t *At, int64_t lda, const uint16_t *Bt, int64_t ldb, float *C, int64_t ldc, int32_t M,
+                     int32_t N, int32_t K, int32_t accumulate, void *stream);
 /* db[cols] fp32 (written) = sum over the n rows of x [n, ld] bf16 (the gradient of such a bias); cols % 8 == 0;
  * ws: device scratch of at least mt_k_bias_grad_ws_bytes(cols) bytes.  Fixed summation order. */
 size_t mt_k_bias_grad_ws_bytes(int32_t cols);

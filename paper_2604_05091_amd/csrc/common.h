@@ -38,6 +38,32 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+#ifdef __HIPCC__
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// Transposing fragment read.  `tile` is a natural-layout LDS tile [reduction index][LDP] (e.g. V[kv][hd]).
+// The result is the A operand of an MFMA whose output rows are the tile's columns col0 .. col0+31 (lane
+// l%32 <-> column) and whose eight reduction slots of lane-half hl are the tile rows
+// row0 + 4 hl + {0..3} and row0 + 8 + 4 hl + {0..3}: the order in which a lane holds the matching
+// accumulator registers of a 32x32 block.  ds_read_b64_tr_b16 works on groups of 16 lanes: lane r' of a
+// group supplies the address of 4 consecutive columns of one row; lane i receives column i of the 4 x 16
+// block so formed, rows 0..3.  lane_off is tr_lane_offset(lane, LDP), hoisted out of the loops.
+__device__ __forceinline__ int tr_lane_offset(int lane, int ldp) {
+    const int g = lane >> 4, i = lane & 15;
+    return ((g >> 1) * 4 + (i >> 2)) * ldp + (g & 1) * 16 + (i & 3) * 4;
+}
+__device__ __forceinline__ bf16x8 read_tr_frag(const bf16_t *tile, int lane_off, int ldp, int row0, int col0) {
+    typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
+    const bf16_t *p = tile + lane_off + row0 * ldp + col0;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * ldp));
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+#endif  // __HIPCC__
+
 // ---------------------------------------------------------------- launchers (host side)
 // Every launcher validates nothing: callers (engine, C ABI wrappers) check shapes first.
 
@@ -55,6 +81,11 @@ struct GemmArgs {
     const bf16_t *bias = nullptr;  // optional bf16 [N], added to every row (bf16 output only)
 };
 hipError_t gemm_nt(const GemmArgs &g, hipStream_t s);
+// C[M,N] = A^T . B with A given as [K, M] and B as [K, N] (lda, ldb their row pitches): the weight-gradient
+// form dW = dY^T X taken straight from token-major activations.  fp32 output (accumulate optional);
+// needs K % 64 == 0, M % 8 == 0, N % 8 == 0; returns hipErrorNotSupported otherwise (callers then transpose
+// the operands and use gemm_nt).
+hipError_t gemm_tn(const GemmArgs &g, hipStream_t s);
 
 // out[b][c][r] = in[b][r][c] for r < rows, c < cols (bf16); leading dimensions in elements.
 // Two batch levels (b0 < nb0, b1 < nb1) with independent strides on each side.

@@ -299,6 +299,34 @@ hipError_t transpose2d(hipStream_t s, const uint16_t *in, uint16_t *out, int64_t
     return transpose_bf16(t, s);
 }
 
+#define WG(expr)                      \
+    do {                              \
+        const mt_status st_ = (expr); \
+        if (st_ != MT_OK) return st_; \
+    } while (0)
+
+// Weight gradient dW[out,in] (fp32, row pitch in) (+)= dY^T X from token-major dY [rows, out] (ldy) and
+// X [rows, in] (ldx).  Taken straight from the operands when the token count allows it, otherwise through
+// transposed copies (tA, tB) and the general kernel.
+mt_status weight_grad(mt_handle *h, const uint16_t *dY, int64_t ldy, const uint16_t *X, int64_t ldx, float *dW,
+                      int64_t out, int64_t in, int64_t rows, bool accumulate) {
+    hipStream_t s = h->s_comp;
+    if (rows % 64 == 0 && !(out & 7) && !(in & 7)) {
+        GemmArgs g;
+        g.A = dY; g.lda = ldy; g.B = X; g.ldb = ldx; g.C = dW; g.ldc = in; g.R = nullptr; g.ldr = 0;
+        g.M = (int32_t)out; g.N = (int32_t)in; g.K = (int32_t)rows;
+        g.out_fp32 = 1; g.accumulate = accumulate;
+        const double bytes = 2.0 * ((double)out * rows + (double)in * rows) + (double)out * in * (accumulate ? 8.0 : 4.0);
+        Timed t(h, CLS_GEMM, 2.0 * (double)out * (double)in * (double)rows, bytes);
+        KCHK(gemm_tn(g, s));
+        return MT_OK;
+    }
+    KCHK(transpose2d(s, dY, h->tA, rows, out, ldy, rows));
+    KCHK(transpose2d(s, X, h->tB, rows, in, ldx, rows));
+    KCHK(gemm(h, h->tA, rows, h->tB, rows, dW, in, out, in, rows, true, accumulate));
+    return MT_OK;
+}
+
 struct LayerW {
     const uint16_t *wqkv, *wo, *wgu, *wd, *g1, *g2, *bqkv;  // bqkv = NULL without biases
 };
@@ -385,21 +413,15 @@ mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t
             const mt_status st = mlp_forward_rows(h, w, h1c, m);
             if (st != MT_OK) return st;
         }
-        KCHK(transpose2d(s, gyc, h->tA, m, D.d, D.d, m));
-        KCHK(transpose2d(s, h->sact, h->tB, m, D.F, D.F, m));
-        KCHK(gemm(h, h->tA, m, h->tB, m, G + o.wd, D.F, D.d, D.F, m, true, acc));
+        WG(weight_grad(h, gyc, D.d, h->sact, D.F, G + o.wd, D.d, D.F, m, acc));
         KCHK(gemm(h, gyc, D.d, h->wT, D.d, h->dsact, D.F, m, D.F, D.d));
         KCHK(swiglu_bwd(h->dgu, h->dsact, h->gu, m, D.F, s));
-        KCHK(transpose2d(s, h->dgu, h->tA, m, 2 * D.F, 2 * D.F, m));
-        KCHK(transpose2d(s, h->yn, h->tB, m, D.d, D.d, m));
-        KCHK(gemm(h, h->tA, m, h->tB, m, G + o.wgu, D.d, 2 * D.F, D.d, m, true, acc));
+        WG(weight_grad(h, h->dgu, 2 * D.F, h->yn, D.d, G + o.wgu, 2 * D.F, D.d, m, acc));
         KCHK(gemm(h, h->dgu, 2 * D.F, h->wT2, 2 * D.F, h->dyn, D.d, m, D.d, 2 * D.F));
         KCHK(rmsnorm_bwd(h->dh1 + r0 * D.d, G + o.g2, h->dyn, h1c, w.g2, gyc, h->norm_ws, m, D.d, h->cfg.rms_eps, s, acc));
     }
     // h1 = x + att Wo^T
-    KCHK(transpose2d(s, h->dh1, h->tA, n, D.d, D.d, n));
-    KCHK(transpose2d(s, h->att, h->tB, n, D.Nq, D.Nq, n));
-    KCHK(gemm(h, h->tA, n, h->tB, n, G + o.wo, D.Nq, D.d, D.Nq, n, true));
+    WG(weight_grad(h, h->dh1, D.d, h->att, D.Nq, G + o.wo, D.d, D.Nq, n, false));
     KCHK(transpose2d(s, w.wo, h->wT, D.d, D.Nq, D.Nq, D.d));
     KCHK(gemm(h, h->dh1, D.d, h->wT, D.d, h->datt, D.Nq, n, D.Nq, D.d));
     // attention
@@ -415,9 +437,7 @@ mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t
     KCHK(rope_inplace(h->dqkv, D.Nqkv, n, T, D.Hq + D.Hkv, D.hd, h->rope_cos, h->rope_sin, -1, s));
     if (D.bias) KCHK(bias_grad(G + o.bqkv, h->dqkv, D.Nqkv, n, (int32_t)D.Nqkv, h->bias_ws, s));
     // qkv = xn Wqkv^T + b
-    KCHK(transpose2d(s, h->dqkv, h->tA, n, D.Nqkv, D.Nqkv, n));
-    KCHK(transpose2d(s, h->xn, h->tB, n, D.d, D.d, n));
-    KCHK(gemm(h, h->tA, n, h->tB, n, G + o.wqkv, D.d, D.Nqkv, D.d, n, true));
+    WG(weight_grad(h, h->dqkv, D.Nqkv, h->xn, D.d, G + o.wqkv, D.Nqkv, D.d, n, false));
     KCHK(transpose2d(s, w.wqkv, h->wT, D.Nqkv, D.d, D.d, D.Nqkv));
     KCHK(gemm(h, h->dqkv, D.Nqkv, h->wT, D.Nqkv, h->dxn, D.d, n, D.d, D.Nqkv));
     KCHK(rmsnorm_bwd(gx, G + o.g1, h->dxn, x, w.g1, h->dh1, h->norm_ws, n, D.d, h->cfg.rms_eps, s));
@@ -434,14 +454,18 @@ mt_status head_forward_backward(mt_handle *h, const uint16_t *W, float *G, const
     uint16_t *zn = h->xn, *dzn = h->dxn;
     KCHK(rmsnorm_fwd(zn, x, gf, n, D.d, h->cfg.rms_eps, s));
     KCHK(transpose2d(s, wlm, h->wT, D.V, D.d, D.d, D.V));   // [d, V]
-    KCHK(transpose2d(s, zn, h->tB, n, D.d, D.d, n));        // [d, n]
     for (int64_t c0 = 0; c0 < n; c0 += h->ce_chunk) {
         const int64_t rows = std::min<int64_t>(h->ce_chunk, n - c0);
         KCHK(gemm(h, zn + c0 * D.d, D.d, wlm, D.d, h->logits, D.V, rows, D.V, D.d, true));
         KCHK(cross_entropy(h->loss_rows + c0, h->dlogits, h->logits, h->lab_dev + c0, rows, D.V, inv_n, s));
         KCHK(gemm(h, h->dlogits, D.V, h->wT, D.V, dzn + c0 * D.d, D.d, rows, D.d, D.V));
-        KCHK(transpose2d(s, h->dlogits, h->dlT, rows, D.V, D.V, rows));  // [V, rows]
-        KCHK(gemm(h, h->dlT, rows, h->tB + c0, n, dWlm, D.d, D.V, D.d, rows, true, c0 > 0));
+        if (rows % 64 == 0) {
+            WG(weight_grad(h, h->dlogits, D.V, zn + c0 * D.d, D.d, dWlm, D.V, D.d, rows, c0 > 0));
+        } else {  // ragged chunk: transposed copies (dlT holds [V, rows], tB [d, rows])
+            KCHK(transpose2d(s, h->dlogits, h->dlT, rows, D.V, D.V, rows));
+            KCHK(transpose2d(s, zn + c0 * D.d, h->tB, rows, D.d, D.d, rows));
+            KCHK(gemm(h, h->dlT, rows, h->tB, rows, dWlm, D.d, D.V, D.d, rows, true, c0 > 0));
+        }
     }
     KCHK(reduce_sum(h->loss_dev, h->loss_rows, n, inv_n, 0, s));
     KCHK(rmsnorm_bwd(gx, dgf, dzn, x, gf, nullptr, h->norm_ws, n, D.d, h->cfg.rms_eps, s));

@@ -457,6 +457,162 @@ hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
 }
 
 
+// ---------------------------------------------------------------------------------------------
+// Weight-gradient form: C[M,N] = sum_k At[k][m] Bt[k][n] with both operands token-major ([K, M] and [K, N]),
+// i.e. dW = dY^T X straight from the activations as the other kernels produce them.  Same tile, waves and
+// in-wave pipeline as gemm_nt_w4_kernel; the LDS tiles are [64 k][256 m] (pitch 296 elements: rows 20 banks
+// apart, the spacing that keeps the transposing reads nearly conflict-free) and the MFMA operands are read
+// with ds_read_b64_tr_b16 (read_tr_frag), which hands a lane eight reduction indices of one output row: two
+// reads per fragment instead of one.  fp32 output only.
+constexpr int TN_LDT = 256 + 40;
+constexpr int TN_TILE_BYTES = BK * TN_LDT * 2, TN_STAGE_BYTES = 2 * TN_TILE_BYTES;
+
+__global__ __launch_bounds__(W4_NT) void gemm_tn_w4_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    constexpr int BM = W4_BM, BN = W4_BN;
+    const int nb = tiles_m * tiles_n;
+    int pid = blockIdx.x;
+    {
+        const int q = nb / kXcd, r = nb % kXcd, x = pid % kXcd;
+        pid = x * q + (x < r ? x : r) + pid / kXcd;
+    }
+    const int group = kGroupM * tiles_n;
+    const int first_m = (pid / group) * kGroupM;
+    const int gsz = min(tiles_m - first_m, kGroupM);
+    const int tm = first_m + (pid % group) % gsz;
+    const int tn = (pid % group) / gsz;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, hl = lane >> 5;
+    const int tr_off = tr_lane_offset(lane, TN_LDT);
+
+    // loader: thread owns the 16-byte chunk (tid & 31) (8 consecutive m or n) of the k rows (tid >> 5) + 8 j.
+    // Chunks past the matrix edge re-read the last chunk; they only feed outputs that are never stored.
+    const int lk = tid >> 5, lc = (tid & 31) * 8;
+    const bf16_t *abase = g.A + min(m0 + lc, g.M - 8);
+    const bf16_t *bbase = g.B + min(n0 + lc, g.N - 8);
+    u32x4 st[16];
+    bf16x8 fr[2][8];
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    char *const lds = reinterpret_cast<char *>(smem);
+    const uint32_t wr_off = (uint32_t)((lk * TN_LDT + lc) * 2);
+    uint32_t cur = 0;
+
+#define TN_LOAD(J, K0)                                                                                  \
+    st[J] = *reinterpret_cast<const u32x4 *>(                                                           \
+        ((J) < 8 ? abase + (int64_t)((K0) + lk + 8 * ((J) & 7)) * g.lda : bbase + (int64_t)((K0) + lk + 8 * ((J) & 7)) * g.ldb));
+#define TN_WRITE(J, BUFOFF)                                                                             \
+    *reinterpret_cast<u32x4 *>(lds + (BUFOFF) + wr_off + ((J) < 8 ? 0 : TN_TILE_BYTES) + ((J) & 7) * 8 * TN_LDT * 2) = st[J];
+#define TN_READ(SET, BUFOFF, KS)                                                                        \
+    {                                                                                                   \
+        const bf16_t *ta_ = reinterpret_cast<const bf16_t *>(lds + (BUFOFF));                           \
+        const bf16_t *tb_ = reinterpret_cast<const bf16_t *>(lds + (BUFOFF) + TN_TILE_BYTES);           \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
+            fr[SET][i] = read_tr_frag(ta_, tr_off, TN_LDT, (KS) * 16, wm * 128 + i * 32);               \
+            fr[SET][4 + i] = read_tr_frag(tb_, tr_off, TN_LDT, (KS) * 16, wn * 128 + i * 32);           \
+        }                                                                                               \
+    }
+#define TN_MMA_ROWS(SET, I0, I1)                                                                        \
+    {                                                                                                   \
+        _Pragma("unroll") for (int i = I0; i < I1; ++i)                                                 \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[SET][4 + j], fr[SET][i], acc[i][j], 0, 0, 0); \
+    }
+#define TN_PHASE(P, SET, C0, C1, COMMIT, LOAD)                                                          \
+    {                                                                                                   \
+        TN_READ((SET) ^ 1, cur, (P) + 1);                                                               \
+        _Pragma("unroll") for (int c = C0; c < C1; ++c) {                                               \
+            if (COMMIT) TN_WRITE(c, nxt);                                                               \
+            if (LOAD) TN_LOAD(c, (kt + 2) * BK);                                                        \
+        }                                                                                               \
+        TN_MMA_ROWS(SET, 0, 4);                                                                         \
+        _Pragma("unroll") for (int c = 0; c < 8; ++c) {                                                 \
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                          \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                          \
+        }                                                                                               \
+        _Pragma("unroll") for (int c = C0; c < C1; ++c) {                                               \
+            if (COMMIT) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                              \
+            if (LOAD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                          \
+        }                                                                                               \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8 - ((C1) - (C0)), 0);                              \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+    }
+#define TN_STEP(COMMIT, LOAD)                                                                           \
+    {                                                                                                   \
+        const uint32_t nxt = TN_STAGE_BYTES - cur;                                                      \
+        TN_PHASE(0, 0, 0, 4, COMMIT, LOAD);                                                             \
+        TN_PHASE(1, 1, 4, 8, COMMIT, LOAD);                                                             \
+        TN_PHASE(2, 0, 8, 12, COMMIT, LOAD);                                                            \
+        _Pragma("unroll") for (int c = 12; c < 16; ++c) {                                               \
+            if (COMMIT) TN_WRITE(c, nxt);                                                               \
+            if (LOAD) TN_LOAD(c, (kt + 2) * BK);                                                        \
+        }                                                                                               \
+        TN_MMA_ROWS(1, 0, 3);                                                                           \
+        _Pragma("unroll") for (int c = 12; c < 16; ++c) {                                               \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                          \
+            if (COMMIT) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                              \
+            if (LOAD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                \
+        }                                                                                               \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        lds_barrier();                                                                                  \
+        if (COMMIT) TN_READ(0, nxt, 0);                                                                 \
+        TN_MMA_ROWS(1, 3, 4);                                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        cur = nxt;                                                                                      \
+    }
+
+    const int nk = g.K / BK;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) TN_LOAD(c, 0);
+#pragma unroll
+    for (int c = 0; c < 16; ++c) TN_WRITE(c, 0);
+    if (nk > 1) {
+#pragma unroll
+        for (int c = 0; c < 16; ++c) TN_LOAD(c, BK);
+    }
+    lds_barrier();
+    TN_READ(0, 0, 0);
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) TN_STEP(true, true);
+    if (kt + 1 < nk) {
+        TN_STEP(true, false);
+        ++kt;
+    }
+    TN_STEP(false, false);
+#undef TN_LOAD
+#undef TN_WRITE
+#undef TN_READ
+#undef TN_MMA_ROWS
+#undef TN_PHASE
+#undef TN_STEP
+    w4_store(g, acc, m0, n0, wm, wn, l32, hl);
+}
+
+hipError_t launch_tn(const GemmArgs &g, hipStream_t s) {
+    constexpr size_t lds = (size_t)2 * TN_STAGE_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tn_w4_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = (g.N + W4_BN - 1) / W4_BN;
+    hipLaunchKernelGGL(gemm_tn_w4_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(W4_NT), lds, s, g, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
 int variant_override() {
     static int v = [] {
         const char *e = getenv("MT_GEMM_VARIANT");
@@ -485,6 +641,14 @@ hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
     }
     if (big_tiles >= 192) return (g.K % BK == 0) ? launch_w4(g, s) : launch<256, 256, 2, 4>(g, s);
     return launch<128, 128, 2, 2>(g, s);
+}
+
+hipError_t gemm_tn(const GemmArgs &g, hipStream_t s) {
+    if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
+    if ((g.lda & 7) || (g.ldb & 7) || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
+    if (g.lda < g.M || g.ldb < g.N || g.ldc < g.N || !g.out_fp32 || g.R || g.bias) return hipErrorInvalidValue;
+    if ((g.K % BK) || (g.M & 7) || (g.N & 7)) return hipErrorNotSupported;
+    return launch_tn(g, s);
 }
 
 }  // namespace mt

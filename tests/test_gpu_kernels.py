@@ -102,6 +102,23 @@ def test_gemm_bias_epilogue_and_bias_gradient(orc64, M, N, K):
     assert np.max(np.abs(host(DB) - want)) <= 1e-5 * np.sqrt(M) * np.max(np.abs(host(C)))
 
 
+@pytest.mark.parametrize("n,out,inn", [(2048, 136, 264), (576, 520, 1376), (64, 8, 8), (4096, 2056, 4104)])
+def test_gemm_token_major_weight_gradient(orc64, n, out, inn):
+    """dW[out,in] = sum_t dy[t,out] x[t,in] straight from the token-major operands (no transposes): ragged
+    and tiny edges, strides, accumulate; unsupported reduction lengths are refused."""
+    rng = np.random.default_rng(n + out + inn)
+    ldy, ldx = out + 8, inn + 16
+    dy, x = bf16_round(rng.standard_normal((n, ldy))), bf16_round(rng.standard_normal((n, ldx)))
+    ref = orc64.linear_bwd_w(np.ascontiguousarray(dy[:, :out]), np.ascontiguousarray(x[:, :inn]))
+    DY, X = dev_bf16(dy), dev_bf16(x)
+    DW = torch.full((out, inn), 7.0, dtype=torch.float32, device="cuda")
+    ok(L.mt_k_gemm_tn(DY.data_ptr(), ldy, X.data_ptr(), ldx, DW.data_ptr(), inn, out, inn, n, 0, None))
+    assert rel_l2(host(DW), ref) < 5e-6
+    ok(L.mt_k_gemm_tn(DY.data_ptr(), ldy, X.data_ptr(), ldx, DW.data_ptr(), inn, out, inn, n, 1, None))
+    assert rel_l2(host(DW), 2 * ref) < 5e-6
+    assert L.mt_k_gemm_tn(DY.data_ptr(), ldy, X.data_ptr(), ldx, DW.data_ptr(), inn, out, inn, n - 8, 0, None) == -2
+
+
 def test_gemm_weight_gradient_form_long_reduction(orc64):
     """dW[out,in] = sum_t dy[t,out] x[t,in]: both operands transposed first, fp32 result."""
     rng = np.random.default_rng(2)
