@@ -168,13 +168,15 @@ def main() -> int:
     names = ["gemm_nt_w4_kernel + gemm_tn_w4_kernel (bf16 MFMA GEMM)", "flash_fwd_kernel", "flash_bwd_dkdv_kernel + flash_bwd_dq_kernel"]
     dom = int(np.argmax(cls_ms))
     achieved = cls_fl[dom] / (cls_ms[dom] * 1e-3) / 1e12 if cls_ms[dom] > 0 else 0.0
+    # HBM-side bytes per launch of the dominant kernel, measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE,
+    # calibrated against a copy kernel); the summary under profiles/ carries the figure for the GEMM class of
+    # the 7B workload in a line "traffic_bytes_per_launch[7B] = N".
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(name)
-        except Exception:
-            traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gemm_kernels_7B_hbm_traffic.md")
+    if dom == 0 and os.path.exists(tpath):
+        import re
+        m = re.search(r"traffic_bytes_per_launch\[%s\] = ([0-9.eE+]+)" % re.escape(name), open(tpath).read())
+        traffic = float(m.group(1)) if m else None
     roofline = {"bound": "mfma", "kernel": names[dom], "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
                 "launches_per_step": int(cls_n[dom] / args.steps),
