@@ -95,6 +95,8 @@ def main() -> int:
     ap.add_argument("--mlp-chunk", type=int, default=0, help="chunked MLP: tokens per chunk (0 = off)")
     ap.add_argument("--ckpt-interval", type=int, default=1,
                     help="checkpoint interval K of Algorithm 1 (the headline number is quoted at K = 1)")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="diagnostic: no HIP event pairs around the GEMM / attention launches (the roofline object is then empty)")
     ap.add_argument("--separate-adam", action="store_true",
                     help="call mt_train_step then mt_adam_step instead of the overlapped mt_train_step_adam")
     args = ap.parse_args()
@@ -120,7 +122,7 @@ def main() -> int:
     tok, lab = mt_inputs.make_batch(shape.vocab, B, T, seed=1)
     cfg = mt.ModelCfg.make(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
                            shape.vocab, B, T, rope_base=shape.rope_base, rms_eps=shape.rms_eps,
-                           flags=mt.FLAG_KERNEL_TIMING | args.flags, ckpt_interval=args.ckpt_interval,
+                           flags=(0 if args.no_kernel_timing else mt.FLAG_KERNEL_TIMING) | args.flags, ckpt_interval=args.ckpt_interval,
                            mlp_chunk=args.mlp_chunk)
     link = mt.link_probe(256 << 20, 4)     # copy-bandwidth probe of this session: the host-link roofline
     h = mt.TrainHandle(cfg, params)

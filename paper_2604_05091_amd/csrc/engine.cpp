@@ -4,10 +4,13 @@
 //
 // Units.  The model is cut into L+2 streamed units: E (embedding table), blocks 1..L and
 // H (final norm + LM head).  Each unit owns one contiguous pinned bf16 block on the host
-// (what StreamIn copies, one DMA per unit) and one contiguous pinned fp32 gradient block
-// (what Offload fills, one DMA per unit).  Inside a block the tensors are ordered
-//     wq | wk | wv | wo | w_gate | w_up | w_down | attn_norm | mlp_norm
-// so q/k/v and gate/up form single [out,in] matrices and run as one GEMM each.  The device
+// (what StreamIn copies, one DMA per unit) and one contiguous fp32 gradient block (what
+// Offload fills).  Inside a block the tensors are ordered
+//     wq | wk | wv | wo | attn_norm | (bq | bk | bv) | mlp_norm | w_gate | w_up | w_down
+// so q/k/v and gate/up form single [out,in] matrices and run as one GEMM each, and the MLP
+// part is one contiguous tail: its gradients are complete half-way through the block's
+// backward and leave as an early DMA of their own (gm_ready / gm_free below), the attention
+// part follows at the end of the block.  The device
 // "templates" are just kernels taking pointers: binding a streamed buffer is pointer
 // arithmetic on the buffer base, done at launch.
 //
@@ -18,6 +21,8 @@
 //   w_free[s]   recorded on S_comp after its last use    -> S_h2d waits before load s+2
 //   g_ready[r]  recorded on S_comp after grads r exist   -> S_d2h waits before copying
 //   g_free[r]   recorded on S_d2h after the copy         -> S_comp waits before grads r+2
+//   gm_ready[r] / gm_free[r]: the same pair for the early MLP piece of a layer's block; the host
+//   optimizer waits for gm_free[r] or g_free[r], whichever covers the tensors it updates next
 // The paper names three of these (Weights-Ready, Backward-Done, Buffer-Free); w_free is the
 // event behind its "Release(theta_i)".
 #include <hip/hip_runtime.h>
@@ -34,6 +39,7 @@
 #include <vector>
 #include <condition_variable>
 #include <deque>
+#include <functional>
 #include <set>
 #include <mutex>
 #include <thread>
@@ -91,6 +97,7 @@ struct Unit {
 // element offsets inside a block unit
 struct LayerOff {
     size_t wqkv, wo, wgu, wd, g1, g2, bqkv, total;  // bqkv: bq | bk | bv (only with biases)
+    size_t mlp;  // first element of the MLP part (g2 | wgu | wd), which ends the block
 };
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -125,15 +132,18 @@ Dims dims_of(const mt_model_cfg *c) {
 }
 
 LayerOff layer_off(const Dims &D) {
+    // attention part first, MLP part last: the MLP gradients are complete half-way through a block's backward and
+    // leave for the host as one contiguous piece while the attention part is still being computed
     LayerOff o;
     o.wqkv = 0;
     o.wo = o.wqkv + (size_t)D.Nqkv * D.d;
-    o.wgu = o.wo + (size_t)D.d * D.Nq;
+    o.g1 = o.wo + (size_t)D.d * D.Nq;
+    o.bqkv = o.g1 + D.d;
+    o.g2 = o.bqkv + (D.bias ? (size_t)D.Nqkv : 0);
+    o.mlp = o.g2;
+    o.wgu = o.g2 + D.d;
     o.wd = o.wgu + (size_t)2 * D.F * D.d;
-    o.g1 = o.wd + (size_t)D.d * D.F;
-    o.g2 = o.g1 + D.d;
-    o.bqkv = o.g2 + D.d;
-    o.total = o.bqkv + (D.bias ? (size_t)D.Nqkv : 0);
+    o.total = o.wd + (size_t)D.d * D.F;
     return o;
 }
 
@@ -221,6 +231,7 @@ struct mt_handle {
 
     hipStream_t s_comp = nullptr, s_h2d = nullptr, s_d2h = nullptr;
     std::vector<hipEvent_t> w_ready, w_free, g_ready, g_free, h2d_start, comp_start, d2h_start;
+    std::vector<hipEvent_t> gm_ready, gm_free, d2hm_start;  // the same three for a block's early (MLP) gradient piece
     hipEvent_t ev_ref = nullptr, ev_inputs = nullptr;
     int resident[2] = {-1, -1};
 
@@ -332,7 +343,7 @@ struct LayerW {
 };
 LayerW bind_layer(const uint16_t *base, const LayerOff &o) {
     return {base + o.wqkv, base + o.wo, base + o.wgu, base + o.wd, base + o.g1, base + o.g2,
-            o.total > o.bqkv ? base + o.bqkv : nullptr};
+            o.g2 > o.bqkv ? base + o.bqkv : nullptr};  // the bias slot is empty without biases
 }
 
 AttnArgs attn_args(const mt_handle *h, int B, int T) {
@@ -395,8 +406,9 @@ mt_status layer_forward(mt_handle *h, const LayerW &w, const uint16_t *x, uint16
 
 // LocalBackward of Algorithm 1: the block's internals are in the work buffers (just recomputed).
 // gy = dl/dy, gx receives dl/dx; fp32 weight gradients go to G (unit layout).
+// mlp_grads_done is called once the MLP part of G (gain, gate/up and down weights) is complete.
 mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t *x, const uint16_t *gy, uint16_t *gx,
-                         int B, int T) {
+                         int B, int T, const std::function<mt_status()> &mlp_grads_done) {
     const Dims &D = h->D;
     const LayerOff &o = h->lo;
     const int64_t n = (int64_t)B * T;
@@ -419,6 +431,10 @@ mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t
         WG(weight_grad(h, h->dgu, 2 * D.F, h->yn, D.d, G + o.wgu, 2 * D.F, D.d, m, acc));
         KCHK(gemm(h, h->dgu, 2 * D.F, h->wT2, 2 * D.F, h->dyn, D.d, m, D.d, 2 * D.F));
         KCHK(rmsnorm_bwd(h->dh1 + r0 * D.d, G + o.g2, h->dyn, h1c, w.g2, gyc, h->norm_ws, m, D.d, h->cfg.rms_eps, s, acc));
+    }
+    {
+        const mt_status st = mlp_grads_done();
+        if (st != MT_OK) return st;
     }
     // h1 = x + att Wo^T
     WG(weight_grad(h, h->dh1, D.d, h->att, D.Nq, G + o.wo, D.d, D.Nq, n, false));
@@ -492,6 +508,7 @@ void free_handle(mt_handle *h) {
         v.clear();
     };
     kill_events(h->w_ready); kill_events(h->w_free); kill_events(h->g_ready); kill_events(h->g_free);
+    kill_events(h->gm_ready); kill_events(h->gm_free); kill_events(h->d2hm_start);
     kill_events(h->h2d_start); kill_events(h->comp_start); kill_events(h->d2h_start);
     for (auto &sp : h->spans) {
         if (sp.a) (void)hipEventDestroy(sp.a);
@@ -545,10 +562,11 @@ struct AdamHyper {
     int64_t step;
 };
 
-void adam_unit(mt_handle *h, int unit, const AdamHyper &hp) {
+// Adam on the tensors of a unit that lie inside [off, off + count) of its block
+void adam_range(mt_handle *h, int unit, size_t off, size_t count, const AdamHyper &hp) {
     for (int i = 0; i < h->n_tensors; ++i) {
         const TensorRef &t = h->tref[i];
-        if (t.unit != unit) continue;
+        if (t.unit != unit || t.off < off || t.off + t.numel > off + count) continue;
         Unit &u = h->units[unit];
         host_adam(h->params[i], u.h_grad + t.off, h->adam_m[unit] + t.off, h->adam_v[unit] + t.off,
                   u.h_shadow ? u.h_shadow + t.off : nullptr, t.numel, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.wd, hp.step);
@@ -557,8 +575,8 @@ void adam_unit(mt_handle *h, int unit, const AdamHyper &hp) {
 
 // Host optimizer running beside the GPU (Algorithm 1, "CPU-side optimizer update (asynchronous)";
 // Section 3.3: a background CPU thread applies the update as gradient blocks land).  The step pushes
-// (gradient block r, unit u) right after enqueueing the block's device-to-host copy; the worker waits
-// for that copy's event and updates the unit.  A unit's weights are never streamed again in the same
+// (copy-done event, unit u, element range) right after enqueueing a device-to-host copy of gradients; the worker
+// waits for that event and updates the tensors of the unit inside the range.  A unit's weights are never streamed again in the same
 // step once its gradients exist, so updating its master copy and bf16 copy in place is safe.
 class HostWorker {
   public:
@@ -578,10 +596,10 @@ class HostWorker {
     }
     // add = true: the slab is added to the gradient block instead of replacing it (micro-batch accumulation)
     // run_adam = false: only land the gradient (a tied table's head part; its update follows the embedding part)
-    void push(int r, int unit, int slab, bool add, size_t count, bool run_adam) {
+    void push(hipEvent_t copied, int unit, size_t off, size_t count, int slab, bool add, bool run_adam) {
         {
             std::lock_guard<std::mutex> lk(mu_);
-            q_.push_back({r, unit, slab, add, count, run_adam});
+            q_.push_back({copied, unit, off, count, slab, add, run_adam});
         }
         cv_.notify_one();
     }
@@ -602,7 +620,7 @@ class HostWorker {
     bool failed() const { return failed_; }
 
   private:
-    struct Item { int r, unit, slab; bool add; size_t count; bool run_adam; };
+    struct Item { hipEvent_t copied; int unit; size_t off, count; int slab; bool add, run_adam; };
     void run() {
         if (hipSetDevice(h_->cfg.device_id) != hipSuccess) set_failed();
         for (;;) {
@@ -615,7 +633,7 @@ class HostWorker {
                 q_.pop_front();
             }
             if (failed_) continue;
-            if (hipEventSynchronize(h_->g_free[item.r]) != hipSuccess) {
+            if (hipEventSynchronize(item.copied) != hipSuccess) {
                 (void)hipGetLastError();
                 set_failed();
                 continue;
@@ -625,10 +643,10 @@ class HostWorker {
                 // "Acc" of the paper's slab pool: fold the slab into the master gradient store, then recycle it
                 Unit &u = h_->units[item.unit];
                 const char *src = reinterpret_cast<const char *>(h_->slabs[item.slab]);
-                char *dst = reinterpret_cast<char *>(u.h_grad);
+                char *dst = reinterpret_cast<char *>(u.h_grad + item.off);
                 if (item.add) {
                     const float *sf = h_->slabs[item.slab];
-                    float *df = u.h_grad;
+                    float *df = u.h_grad + item.off;
                     parallel_for(item.count, 1 << 20, [&](size_t b, size_t e) {
                         for (size_t i = b; i < e; ++i) df[i] += sf[i];
                     });
@@ -641,7 +659,7 @@ class HostWorker {
                 }
                 cv_main_.notify_all();
             }
-            if (has_opt_ && item.run_adam) adam_unit(h_, item.unit, hp_);
+            if (has_opt_ && item.run_adam) adam_range(h_, item.unit, item.off, item.count, hp_);
             busy_ms_ += now_ms() - t0;
         }
     }
@@ -1010,6 +1028,9 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     CREATE_HIP(make_events(h->g_ready, ngrads));
     CREATE_HIP(make_events(h->g_free, ngrads));
     CREATE_HIP(make_events(h->d2h_start, ngrads));
+    CREATE_HIP(make_events(h->gm_ready, ngrads));
+    CREATE_HIP(make_events(h->gm_free, ngrads));
+    CREATE_HIP(make_events(h->d2hm_start, ngrads));
     CREATE_HIP(hipEventCreate(&h->ev_ref));
     CREATE_HIP(hipEventCreate(&h->ev_inputs));
 
@@ -1317,24 +1338,20 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     // Gradient block r lives in Gbuf[r & 1] as the image of unit u.  It normally goes to the host as one piece;
     // with tied embeddings the head's image (table gradient | final norm gradient) goes to two units, and the
     // embedding's scatter-add is added to the table gradient that the head left there.
-    struct GPiece { int unit; size_t dev_off, count; bool add, run_adam; };
+    // A layer's block leaves in two pieces: the MLP part (two thirds of it) as soon as the MLP backward is done,
+    // the rest at the end of the block, so the host update of the step's last block is mostly over when the GPU stops.
+    struct GPiece { int unit; size_t dev_off, off, count; bool add, run_adam; };  // offsets in Gbuf and in the unit's block
     size_t slab_seq = 0;
-    auto issue_offload = [&](int r, int u) -> mt_status {
-        HIPCHK(hipEventRecord(h->g_ready[r], sc));
-        if (no_copy) return MT_OK;
-        std::vector<GPiece> pieces;
-        if (D.tied && u == D.L + 1) {
-            pieces.push_back({0, 0, (size_t)D.V * D.d, accumulate, false});
-            pieces.push_back({u, (size_t)D.V * D.d, (size_t)D.d, accumulate, true});
-        } else {
-            pieces.push_back({u, 0, h->units[u].numel, accumulate || (D.tied && u == 0), true});
-        }
-        HIPCHK(hipStreamWaitEvent(sd, h->g_ready[r], 0));
-        HIPCHK(hipEventRecord(h->d2h_start[r], sd));
+    std::vector<char> early_issued(D.L + 2, 0);
+    // copies the pieces on S_d2h after `ready`, brackets them with `start` / `copied`, hands them to the host worker
+    auto offload_pieces = [&](int r, const std::vector<GPiece> &pieces, hipEvent_t ready, hipEvent_t start,
+                              hipEvent_t copied) -> mt_status {
+        HIPCHK(hipStreamWaitEvent(sd, ready, 0));
+        HIPCHK(hipEventRecord(start, sd));
         std::vector<int> slab_of(pieces.size(), -1);
         for (size_t i = 0; i < pieces.size(); ++i) {
             const GPiece &pc = pieces[i];
-            float *dst = h->units[pc.unit].h_grad;
+            float *dst = h->units[pc.unit].h_grad + pc.off;
             if (h->grad_slabs || pc.add) {
                 // back-pressure of the slab pool: wait (on the host) until the slab's previous content is folded away
                 const int slab = (int)(slab_seq++ % (size_t)h->n_slabs);
@@ -1345,13 +1362,36 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
             HIPCHK(hipMemcpyAsync(dst, h->Gbuf[r & 1] + pc.dev_off, pc.count * 4, hipMemcpyDeviceToHost, sd));
             d2h_bytes += pc.count * 4;
         }
-        HIPCHK(hipEventRecord(h->g_free[r], sd));
-        grad_issued[r] = 1;
+        HIPCHK(hipEventRecord(copied, sd));
         if (worker)
             for (size_t i = 0; i < pieces.size(); ++i)
-                worker->push(r, pieces[i].unit, slab_of[i], pieces[i].add, pieces[i].count, pieces[i].run_adam);
+                worker->push(copied, pieces[i].unit, pieces[i].off, pieces[i].count, slab_of[i], pieces[i].add, pieces[i].run_adam);
         if (serial) HIPCHK(hipDeviceSynchronize());
         return MT_OK;
+    };
+    // the MLP part of layer unit u (gradient block r), called from inside the block's backward
+    auto issue_offload_early = [&](int r, int u) -> mt_status {
+        if (no_copy) return MT_OK;
+        HIPCHK(hipEventRecord(h->gm_ready[r], sc));
+        early_issued[r] = 1;
+        return offload_pieces(r, {{u, h->lo.mlp, h->lo.mlp, h->lo.total - h->lo.mlp, accumulate, true}}, h->gm_ready[r],
+                              h->d2hm_start[r], h->gm_free[r]);
+    };
+    auto issue_offload = [&](int r, int u) -> mt_status {
+        HIPCHK(hipEventRecord(h->g_ready[r], sc));
+        if (no_copy) return MT_OK;
+        std::vector<GPiece> pieces;
+        if (D.tied && u == D.L + 1) {
+            // head image: table gradient | final norm gradient; they belong to units 0 and L+1
+            pieces.push_back({0, 0, 0, (size_t)D.V * D.d, accumulate, false});
+            pieces.push_back({u, (size_t)D.V * D.d, 0, (size_t)D.d, accumulate, true});
+        } else if (early_issued[r]) {
+            pieces.push_back({u, 0, 0, h->lo.mlp, accumulate, true});
+        } else {
+            pieces.push_back({u, 0, 0, h->units[u].numel, accumulate || (D.tied && u == 0), true});
+        }
+        grad_issued[r] = 1;
+        return offload_pieces(r, pieces, h->g_ready[r], h->d2h_start[r], h->g_free[r]);
     };
     auto begin_unit = [&](int s) -> mt_status {
         if (load_issued[s]) HIPCHK(hipStreamWaitEvent(sc, h->w_ready[s], 0));
@@ -1417,7 +1457,8 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
             if (bslots[i].recompute)  // RecomputeBlock: the last layer of a block needs no output
                 STEP(layer_forward(h, w, h->boundary(l - 1), bslots[i].backward ? nullptr : h->boundary(l), batch, seq));
             if (bslots[i].backward) {
-                STEP(layer_backward(h, w, h->Gbuf[r & 1], h->boundary(l - 1), gcur, gnext, batch, seq));
+                STEP(layer_backward(h, w, h->Gbuf[r & 1], h->boundary(l - 1), gcur, gnext, batch, seq,
+                                    [&]() -> mt_status { return issue_offload_early(r, l); }));
                 std::swap(gcur, gnext);
             }
         }
@@ -1482,6 +1523,11 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
         if (ok && grad_issued[r]) {
             Iv c;
             ok = ts(h->d2h_start[r], &c.a) && ts(h->g_free[r], &c.b);
+            if (ok) d2h.push_back(c);
+        }
+        if (ok && early_issued[r]) {
+            Iv c;
+            ok = ts(h->d2hm_start[r], &c.a) && ts(h->gm_free[r], &c.b);
             if (ok) d2h.push_back(c);
         }
     }
