@@ -39,6 +39,14 @@ int32_t mt_k_gemm_nt(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t 
  * projections of layers with biases. */
 int32_t mt_k_gemm_nt_bias(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, uint16_t *C, int64_t ldc,
                           const uint16_t *bias, int32_t M, int32_t N, int32_t K, void *stream);
+/* The q, k, v projection of a block (Section 3.2, layer forward) with the rotary embedding applied in the store:
+ * C[M,N] bf16 = A . B^T (+ bias if not NULL), then in columns [0, rope_cols) every head of 128 columns has its
+ * pairs (j, j + 64) rotated by the angle of position (row % T); tables cos/sin [T, 64] fp32 from mt_k_rope_table,
+ * 16-byte aligned.  Only for large grids (at least 192 tiles of 256 x 256), K % 64 == 0, N % 128 == 0,
+ * rope_cols % 128 == 0: MT_ERR_UNSUPPORTED otherwise (use mt_k_gemm_nt_bias / mt_k_gemm_nt, then mt_k_rope). */
+int32_t mt_k_gemm_nt_rope(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, uint16_t *C, int64_t ldc,
+                          const uint16_t *bias, const float *cos_tab, const float *sin_tab, int32_t T,
+                          int32_t rope_cols, int32_t M, int32_t N, int32_t K, void *stream);
 /* Weight-gradient form: C[M,N] fp32 = At^T . Bt with At [K, M] bf16 (lda) and Bt [K, N] bf16 (ldb), both
  * token-major as the other kernels leave them (dW = dY^T X); accumulate != 0 adds to the existing C.
  * Requires K % 64 == 0, M % 8 == 0, N % 8 == 0: MT_ERR_UNSUPPORTED otherwise (transpose and use mt_k_gemm_nt). */
@@ -106,6 +114,16 @@ int32_t mt_k_flash_bwd(uint16_t *dq, int64_t lddq, uint16_t *dk, int64_t lddk, u
                        int64_t ldk, const uint16_t *v, int64_t ldv, const uint16_t *o, int64_t ldo, const float *lse,
                        float *delta, int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, float scale,
                        void *stream);
+
+/* The same with the backward of a rotary embedding folded into the stores: q and k are the rotated tensors the
+ * forward attended with, and dq, dk come out as gradients of the unrotated ones (rotated back by the angle of
+ * position t; pairs (j, j + hd/2)); tables cos/sin [T, hd/2] fp32, 16-byte aligned.  Equal to mt_k_flash_bwd
+ * followed by mt_k_rope(sign = -1) on dq and dk, without the extra rounding to bf16 in between. */
+int32_t mt_k_flash_bwd_rope(uint16_t *dq, int64_t lddq, uint16_t *dk, int64_t lddk, uint16_t *dv, int64_t lddv,
+                            const uint16_t *dout, int64_t lddo, const uint16_t *q, int64_t ldq, const uint16_t *k,
+                            int64_t ldk, const uint16_t *v, int64_t ldv, const uint16_t *o, int64_t ldo,
+                            const float *lse, float *delta, const float *cos_tab, const float *sin_tab, int32_t B,
+                            int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, float scale, void *stream);
 
 /* Host Adam on one array (the arithmetic of mt_adam_step; all HOST pointers).  shadow may be
  * NULL, otherwise it receives the updated parameters rounded to bf16 (nearest even). */

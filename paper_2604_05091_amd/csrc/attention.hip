@@ -122,6 +122,33 @@ __device__ __forceinline__ void store_owned_rows(bf16_t *out_row, const f32x16 *
         }
 }
 
+// The same store with the backward of the rotary embedding: the pair (j, j + HD/2) of the row is rotated by minus
+// the row's angle; cs / sn point at the row's HD/2 table entries.
+template <int HD>
+__device__ __forceinline__ void store_owned_rows_unrotated(bf16_t *out_row, const f32x16 *acc, float mul, int hl,
+                                                           const float *cs, const float *sn) {
+    constexpr int HB2 = HD / 64;
+#pragma unroll
+    for (int hb = 0; hb < HB2; ++hb)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int j = hb * 32 + r4 * 8 + hl * 4;
+            const float4 c4 = *reinterpret_cast<const float4 *>(cs + j), s4 = *reinterpret_cast<const float4 *>(sn + j);
+            const float c[4] = {c4.x, c4.y, c4.z, c4.w}, sv[4] = {s4.x, s4.y, s4.z, s4.w};
+            float xa[4], xb[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float ya = acc[hb][r4 * 4 + e] * mul, yb = acc[hb + HB2][r4 * 4 + e] * mul;
+                xa[e] = ya * c[e] + yb * sv[e];
+                xb[e] = yb * c[e] - ya * sv[e];
+            }
+            const uint2 ua = {pack2bf(xa[0], xa[1]), pack2bf(xa[2], xa[3])};
+            const uint2 ub = {pack2bf(xb[0], xb[1]), pack2bf(xb[2], xb[3])};
+            *reinterpret_cast<uint2 *>(out_row + j) = ua;
+            *reinterpret_cast<uint2 *>(out_row + j + HD / 2) = ub;
+        }
+}
+
 // acc[hb] += X^T (columns hb*32.. of the natural tile X, reduction rows rb*32 + cch*16 ..) * frag, for all hb
 template <int HD, int LDP>
 __device__ __forceinline__ void mfma_tr_accumulate(f32x16 *acc, const bf16_t *tile, int tr_off, int rb, int cch,
@@ -410,7 +437,14 @@ __global__ __launch_bounds__(64 * NW) void flash_bwd_dq_kernel(AttnArgs a) {
         }
         __syncthreads();
     }
-    if (qok) store_owned_rows<HD>(a.dq + ((int64_t)b * T + q) * a.lddq + (int64_t)h * HD, dqacc, a.scale, hl);
+    if (qok) {
+        bf16_t *dqrow = a.dq + ((int64_t)b * T + q) * a.lddq + (int64_t)h * HD;
+        if (a.rope_cos)
+            store_owned_rows_unrotated<HD>(dqrow, dqacc, a.scale, hl, a.rope_cos + (int64_t)q * (HD / 2),
+                                           a.rope_sin + (int64_t)q * (HD / 2));
+        else
+            store_owned_rows<HD>(dqrow, dqacc, a.scale, hl);
+    }
 }
 
 // ------------------------------------------------------------------ backward: dK, dV, software-pipelined
@@ -595,7 +629,12 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
     }
 #undef DKDV_SLOT
     if (kvok) {
-        store_owned_rows<HD>(a.dk + ((int64_t)b * T + kv) * a.lddk + (int64_t)hk * HD, dkacc, a.scale, hl);
+        bf16_t *dkrow = a.dk + ((int64_t)b * T + kv) * a.lddk + (int64_t)hk * HD;
+        if (a.rope_cos)
+            store_owned_rows_unrotated<HD>(dkrow, dkacc, a.scale, hl, a.rope_cos + (int64_t)kv * (HD / 2),
+                                           a.rope_sin + (int64_t)kv * (HD / 2));
+        else
+            store_owned_rows<HD>(dkrow, dkacc, a.scale, hl);
         store_owned_rows<HD>(a.dv + ((int64_t)b * T + kv) * a.lddv + (int64_t)hk * HD, dvacc, 1.0f, hl);
     }
 }
@@ -608,6 +647,11 @@ bool attn_shape_ok(const AttnArgs &a) {
     return true;
 }
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+// both rotary tables or none, read 16 bytes at a time
+bool rope_tables_ok(const AttnArgs &a) {
+    if (!a.rope_cos && !a.rope_sin) return true;
+    return a.rope_cos && a.rope_sin && aligned16(a.rope_cos) && aligned16(a.rope_sin);
+}
 
 }  // namespace
 
@@ -642,6 +686,7 @@ hipError_t flash_fwd(const AttnArgs &a, hipStream_t s) {
 }
 
 hipError_t flash_bwd_dq(const AttnArgs &a, hipStream_t s) {
+    if (!rope_tables_ok(a)) return hipErrorInvalidValue;
     if (!attn_shape_ok(a) || (a.ldq & 7) || (a.ldk & 7) || (a.ldv & 7) || (a.lddo & 7) || (a.lddq & 3))
         return hipErrorInvalidValue;
     if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.dout) || ((uintptr_t)a.dq & 7))
@@ -665,6 +710,7 @@ hipError_t flash_bwd_dq(const AttnArgs &a, hipStream_t s) {
 }
 
 hipError_t flash_bwd_dkdv(const AttnArgs &a, hipStream_t s) {
+    if (!rope_tables_ok(a)) return hipErrorInvalidValue;
     if (!attn_shape_ok(a) || (a.ldq & 7) || (a.ldk & 7) || (a.ldv & 7) || (a.lddo & 7) || (a.lddk & 3) ||
         (a.lddv & 3))
         return hipErrorInvalidValue;

@@ -79,8 +79,16 @@ struct GemmArgs {
     int32_t M, N, K;
     int32_t out_fp32, accumulate;
     const bf16_t *bias = nullptr;  // optional bf16 [N], added to every row (bf16 output only)
+    // optional rotary embedding fused into the store (gemm_nt only, see gemm_nt_fuses_rope): columns
+    // [0, rope_cols) are heads of 128 whose pairs (j, j + 64) are rotated by the angle of position
+    // row % rope_T; tables cos/sin [rope_T][64] fp32
+    const float *rope_cos = nullptr, *rope_sin = nullptr;
+    int32_t rope_T = 0, rope_cols = 0;
 };
 hipError_t gemm_nt(const GemmArgs &g, hipStream_t s);
+// true when gemm_nt would apply g.rope_* in its epilogue for this problem (large grid, K % 64 == 0, head-aligned
+// columns); otherwise a call with rope_cos set fails with hipErrorNotSupported and the caller rotates separately
+bool gemm_nt_fuses_rope(const GemmArgs &g);
 // C[M,N] = A^T . B with A given as [K, M] and B as [K, N] (lda, ldb their row pitches): the weight-gradient
 // form dW = dY^T X taken straight from token-major activations.  fp32 output (accumulate optional);
 // needs K % 64 == 0, M % 8 == 0, N % 8 == 0; returns hipErrorNotSupported otherwise (callers then transpose
@@ -147,6 +155,9 @@ struct AttnArgs {
     bf16_t *dq; int64_t lddq;
     bf16_t *dk; int64_t lddk;
     bf16_t *dv; int64_t lddv;
+    // optional, backward only: q and k had a rotary embedding applied before the attention (pairs (j, j + hd/2),
+    // tables cos/sin [T][hd/2] fp32); dq and dk are then rotated back by the row's angle as they are stored
+    const float *rope_cos = nullptr, *rope_sin = nullptr;
 };
 hipError_t flash_fwd(const AttnArgs &a, hipStream_t s);
 // delta[b,h,t] = sum_j do[b,t,h,j] * o[b,t,h,j]

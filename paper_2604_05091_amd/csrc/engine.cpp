@@ -301,6 +301,28 @@ hipError_t gemm(mt_handle *h, const uint16_t *A, int64_t lda, const uint16_t *B,
     return gemm_raw(h->s_comp, A, lda, B, ldb, C, ldc, M, N, K, out_fp32, accumulate, R, ldr, bias);
 }
 
+// qkv = xn Wqkv^T (+ b) followed by the rotary embedding of the q and k heads: in the GEMM's store where that
+// kernel supports it (head_dim 128, large grids), otherwise as a pass of its own over q and k.
+hipError_t qkv_projection(mt_handle *h, const uint16_t *xn, const uint16_t *wqkv, const uint16_t *bqkv, int64_t n, int T) {
+    const Dims &D = h->D;
+    GemmArgs g;
+    g.A = xn; g.lda = D.d; g.B = wqkv; g.ldb = D.d; g.C = h->qkv; g.ldc = D.Nqkv; g.R = nullptr; g.ldr = 0;
+    g.M = (int32_t)n; g.N = (int32_t)D.Nqkv; g.K = D.d;
+    g.out_fp32 = 0; g.accumulate = 0;
+    g.bias = bqkv;
+    g.rope_cos = h->rope_cos; g.rope_sin = h->rope_sin; g.rope_T = T; g.rope_cols = (int32_t)(D.Nq + D.Nkv);
+    const bool fused = D.hd == 128 && gemm_nt_fuses_rope(g);
+    if (!fused) g.rope_cos = g.rope_sin = nullptr;
+    {
+        const double M = (double)n, N = (double)D.Nqkv, K = (double)D.d;
+        Timed t(h, CLS_GEMM, 2.0 * M * N * K, 2.0 * (M * K + N * K) + 2.0 * M * N);
+        const hipError_t e = gemm_nt(g, h->s_comp);
+        if (e != hipSuccess) return e;
+    }
+    if (fused) return hipSuccess;
+    return rope_inplace(h->qkv, D.Nqkv, n, T, D.Hq + D.Hkv, D.hd, h->rope_cos, h->rope_sin, +1, h->s_comp);
+}
+
 // out[cols, rows] = in[rows, cols]^T
 hipError_t transpose2d(hipStream_t s, const uint16_t *in, uint16_t *out, int64_t rows, int64_t cols, int64_t ld_in,
                        int64_t ld_out) {
@@ -381,8 +403,7 @@ mt_status layer_forward(mt_handle *h, const LayerW &w, const uint16_t *x, uint16
     const int64_t n = (int64_t)B * T;
     hipStream_t s = h->s_comp;
     KCHK(rmsnorm_fwd(h->xn, x, w.g1, n, D.d, h->cfg.rms_eps, s));
-    KCHK(gemm(h, h->xn, D.d, w.wqkv, D.d, h->qkv, D.Nqkv, n, D.Nqkv, D.d, false, false, nullptr, 0, w.bqkv));
-    KCHK(rope_inplace(h->qkv, D.Nqkv, n, T, D.Hq + D.Hkv, D.hd, h->rope_cos, h->rope_sin, +1, s));
+    KCHK(qkv_projection(h, h->xn, w.wqkv, w.bqkv, n, T));
     const AttnArgs a = attn_args(h, B, T);
     {
         Timed t(h, CLS_ATTN_FWD, 2.0 * (double)B * D.Hq * D.hd * (double)T * ((double)T + 1.0),
@@ -441,7 +462,9 @@ mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t
     KCHK(transpose2d(s, w.wo, h->wT, D.d, D.Nq, D.Nq, D.d));
     KCHK(gemm(h, h->dh1, D.d, h->wT, D.d, h->datt, D.Nq, n, D.Nq, D.d));
     // attention
-    const AttnArgs a = attn_args(h, B, T);
+    AttnArgs a = attn_args(h, B, T);
+    a.rope_cos = h->rope_cos;  // dq and dk leave the kernels already rotated back
+    a.rope_sin = h->rope_sin;
     KCHK(attn_delta(h->delta, h->datt, D.Nq, h->att, D.Nq, B, T, D.Hq, D.hd, s));
     {
         // 7 tile products (4 in the dK/dV kernel, 3 in the dQ kernel), causal half of T^2
@@ -450,7 +473,6 @@ mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t
         KCHK(flash_bwd_dkdv(a, s));
         KCHK(flash_bwd_dq(a, s));
     }
-    KCHK(rope_inplace(h->dqkv, D.Nqkv, n, T, D.Hq + D.Hkv, D.hd, h->rope_cos, h->rope_sin, -1, s));
     if (D.bias) KCHK(bias_grad(G + o.bqkv, h->dqkv, D.Nqkv, n, (int32_t)D.Nqkv, h->bias_ws, s));
     // qkv = xn Wqkv^T + b
     WG(weight_grad(h, h->dqkv, D.Nqkv, h->xn, D.d, G + o.wqkv, D.Nqkv, D.d, n, false));

@@ -298,6 +298,58 @@ __device__ __forceinline__ void w4_store(const GemmArgs &g, const f32x16 (&acc)[
     }
 }
 
+// bf16 store with the rotary embedding applied on the way out (g.rope_*): the wave's 128 columns are one head,
+// the lane holds both members (j, j + 64) of every pair of its rows: blocks j4 and j4 + 2 of acc.  Columns are
+// complete (N % 128 == 0, checked on the host); rows are guarded.  Heads at or beyond rope_cols (the value
+// projection) are stored unrotated.  Bias, if any, is added before the rotation.
+__device__ __forceinline__ void w4_store_rope(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int n0, int wm, int wn,
+                                              int l32, int hl) {
+    const int row_l = m0 + wm * 128 + l32, col_w = n0 + wn * 128;
+    if (col_w >= g.N) return;
+    const bool rot = col_w < g.rope_cols;
+    bf16_t *cw = reinterpret_cast<bf16_t *>(g.C);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = row_l + i * 32;
+        if (row >= g.M) continue;
+        const int64_t tpos = (int64_t)(row % g.rope_T) * 64;
+#pragma unroll
+        for (int jp = 0; jp < 2; ++jp)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int jc = jp * 32 + q * 8 + hl * 4;  // pair index inside the head, < 64
+                float a[4], b[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    a[e] = acc[i][jp][4 * q + e];
+                    b[e] = acc[i][jp + 2][4 * q + e];
+                }
+                if (g.bias) {
+                    const uint2 ba = *reinterpret_cast<const uint2 *>(g.bias + col_w + jc);
+                    const uint2 bb = *reinterpret_cast<const uint2 *>(g.bias + col_w + jc + 64);
+                    a[0] += bflo(ba.x); a[1] += bfhi(ba.x); a[2] += bflo(ba.y); a[3] += bfhi(ba.y);
+                    b[0] += bflo(bb.x); b[1] += bfhi(bb.x); b[2] += bflo(bb.y); b[3] += bfhi(bb.y);
+                }
+                if (rot) {
+                    const f32x4 c = *reinterpret_cast<const f32x4 *>(g.rope_cos + tpos + jc);
+                    const f32x4 sn = *reinterpret_cast<const f32x4 *>(g.rope_sin + tpos + jc);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float ya = a[e] * c[e] - b[e] * sn[e], yb = b[e] * c[e] + a[e] * sn[e];
+                        a[e] = ya;
+                        b[e] = yb;
+                    }
+                }
+                bf16_t *cp = cw + (int64_t)row * g.ldc + col_w + jc;
+                uint2 oa, ob;
+                oa.x = pack2bf(a[0], a[1]); oa.y = pack2bf(a[2], a[3]);
+                ob.x = pack2bf(b[0], b[1]); ob.y = pack2bf(b[2], b[3]);
+                *reinterpret_cast<uint2 *>(cp) = oa;
+                *reinterpret_cast<uint2 *>(cp + 64) = ob;
+            }
+    }
+}
+
 __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles_m, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     constexpr int BM = W4_BM, BN = W4_BN;
@@ -439,7 +491,8 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
 #undef W4_PHASE
 #undef W4_STEP
 
-    w4_store(g, acc, m0, n0, wm, wn, l32, hl);
+    if (g.rope_cos) w4_store_rope(g, acc, m0, n0, wm, wn, l32, hl);
+    else w4_store(g, acc, m0, n0, wm, wn, l32, hl);
 }
 
 hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
@@ -623,8 +676,22 @@ int variant_override() {
 
 }  // namespace
 
+static bool takes_w4(const GemmArgs &g) {
+    const int64_t big_tiles = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256);
+    const int v = variant_override();
+    return g.K % BK == 0 && (v == 6 || (v == 0 && big_tiles >= 192));
+}
+
+bool gemm_nt_fuses_rope(const GemmArgs &g) {
+    return g.M > 0 && g.N > 0 && g.K > 0 && takes_w4(g) && !g.out_fp32 && !g.R && g.rope_T > 0 && (g.N % 128) == 0 &&
+           (g.rope_cols % 128) == 0 && g.rope_cols <= g.N && !(g.ldc & 3) && !((uintptr_t)g.C & 7) &&
+           !((uintptr_t)g.bias & 7) && g.rope_cos && g.rope_sin && !((uintptr_t)g.rope_cos & 15) &&
+           !((uintptr_t)g.rope_sin & 15);
+}
+
 hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
+    if ((g.rope_cos || g.rope_sin) && !gemm_nt_fuses_rope(g)) return hipErrorNotSupported;
     if ((g.K & 7) || (g.lda & 7) || (g.ldb & 7)) return hipErrorInvalidValue;
     if (((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
     if (g.lda < g.K || g.ldb < g.K || g.ldc < g.N) return hipErrorInvalidValue;
@@ -646,7 +713,8 @@ hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
 hipError_t gemm_tn(const GemmArgs &g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
     if ((g.lda & 7) || (g.ldb & 7) || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
-    if (g.lda < g.M || g.ldb < g.N || g.ldc < g.N || !g.out_fp32 || g.R || g.bias) return hipErrorInvalidValue;
+    if (g.lda < g.M || g.ldb < g.N || g.ldc < g.N || !g.out_fp32 || g.R || g.bias || g.rope_cos || g.rope_sin)
+        return hipErrorInvalidValue;
     if ((g.K % BK) || (g.M & 7) || (g.N & 7)) return hipErrorNotSupported;
     return launch_tn(g, s);
 }

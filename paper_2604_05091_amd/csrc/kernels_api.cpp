@@ -41,6 +41,19 @@ int32_t mt_k_gemm_nt_bias(const uint16_t *A, int64_t lda, const uint16_t *B, int
     return to_status(gemm_nt(g, S(stream)));
 }
 
+int32_t mt_k_gemm_nt_rope(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, uint16_t *C, int64_t ldc,
+                          const uint16_t *bias, const float *cos_tab, const float *sin_tab, int32_t T,
+                          int32_t rope_cols, int32_t M, int32_t N, int32_t K, void *stream) {
+    if (!A || !B || !C || !cos_tab || !sin_tab || T <= 0 || rope_cols < 0) return MT_ERR_INVALID_ARG;
+    GemmArgs g;
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.R = nullptr; g.ldr = 0;
+    g.M = M; g.N = N; g.K = K; g.out_fp32 = 0; g.accumulate = 0; g.bias = bias;
+    g.rope_cos = cos_tab; g.rope_sin = sin_tab; g.rope_T = T; g.rope_cols = rope_cols;
+    const hipError_t e = gemm_nt(g, S(stream));
+    if (e == hipErrorNotSupported) return MT_ERR_UNSUPPORTED;
+    return to_status(e);
+}
+
 int32_t mt_k_gemm_tn(const uint16_t *At, int64_t lda, const uint16_t *Bt, int64_t ldb, float *C, int64_t ldc, int32_t M,
                      int32_t N, int32_t K, int32_t accumulate, void *stream) {
     if (!At || !Bt || !C) return MT_ERR_INVALID_ARG;
@@ -140,27 +153,38 @@ int32_t mt_k_flash_fwd(uint16_t *o, int64_t ldo, float *lse, const uint16_t *q, 
     return to_status(flash_fwd(a, S(stream)));
 }
 
-int32_t mt_k_flash_bwd(uint16_t *dq, int64_t lddq, uint16_t *dk, int64_t lddk, uint16_t *dv, int64_t lddv,
-                       const uint16_t *dout, int64_t lddo, const uint16_t *q, int64_t ldq, const uint16_t *k,
-                       int64_t ldk, const uint16_t *v, int64_t ldv, const uint16_t *o, int64_t ldo, const float *lse,
-                       float *delta, int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, float scale,
-                       void *stream) {
+int32_t mt_k_flash_bwd_rope(uint16_t *dq, int64_t lddq, uint16_t *dk, int64_t lddk, uint16_t *dv, int64_t lddv,
+                            const uint16_t *dout, int64_t lddo, const uint16_t *q, int64_t ldq, const uint16_t *k,
+                            int64_t ldk, const uint16_t *v, int64_t ldv, const uint16_t *o, int64_t ldo,
+                            const float *lse, float *delta, const float *cos_tab, const float *sin_tab, int32_t B,
+                            int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, float scale, void *stream) {
     if (!dq || !dk || !dv || !dout || !q || !k || !v || !o || !lse || !delta) return MT_ERR_INVALID_ARG;
     if (B <= 0 || T <= 0 || Hq <= 0 || (hd != 64 && hd != 128) || (T & 7) || (lddo & 7) || (ldo & 7) || !al16(dout) ||
         !al16(o))
         return MT_ERR_INVALID_ARG;
+    if ((cos_tab == nullptr) != (sin_tab == nullptr)) return MT_ERR_INVALID_ARG;
     AttnArgs a = {};
     a.B = B; a.T = T; a.Hq = Hq; a.Hkv = Hkv; a.hd = hd; a.scale = scale;
     a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.v = v; a.ldv = ldv;
     a.o = const_cast<uint16_t *>(o); a.ldo = ldo; a.lse = const_cast<float *>(lse);
     a.dout = dout; a.lddo = lddo; a.delta = delta;
     a.dq = dq; a.lddq = lddq; a.dk = dk; a.lddk = lddk; a.dv = dv; a.lddv = lddv;
+    a.rope_cos = cos_tab; a.rope_sin = sin_tab;
     hipStream_t s = S(stream);
     hipError_t e = attn_delta(delta, dout, lddo, o, ldo, B, T, Hq, hd, s);
     if (e != hipSuccess) return to_status(e);
     e = flash_bwd_dkdv(a, s);
     if (e != hipSuccess) return to_status(e);
     return to_status(flash_bwd_dq(a, s));
+}
+
+int32_t mt_k_flash_bwd(uint16_t *dq, int64_t lddq, uint16_t *dk, int64_t lddk, uint16_t *dv, int64_t lddv,
+                       const uint16_t *dout, int64_t lddo, const uint16_t *q, int64_t ldq, const uint16_t *k,
+                       int64_t ldk, const uint16_t *v, int64_t ldv, const uint16_t *o, int64_t ldo, const float *lse,
+                       float *delta, int32_t B, int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, float scale,
+                       void *stream) {
+    return mt_k_flash_bwd_rope(dq, lddq, dk, lddk, dv, lddv, dout, lddo, q, ldq, k, ldk, v, ldv, o, ldo, lse, delta, nullptr,
+                               nullptr, B, T, Hq, Hkv, hd, scale, stream);
 }
 
 int32_t mt_k_host_adam(float *host_p, const float *host_g, float *host_m, float *host_v, uint16_t *host_shadow,

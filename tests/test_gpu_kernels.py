@@ -212,6 +212,40 @@ def test_rope_forward_and_inverse(orc64, hd, base):
     assert rel_l2(host(X)[:, :H * hd], x[:, :H * hd]) < 2 * BF16_TOL
 
 
+@pytest.mark.parametrize("M,N,K,T,rope_cols,with_bias", [(3200, 4096, 128, 640, 3072, False),
+                                                            (4100, 3072, 64, 4100, 2560, True)])
+def test_gemm_with_rotary_embedding_in_the_store(orc64, M, N, K, T, rope_cols, with_bias):
+    """q|k|v projection with RoPE applied by the GEMM's store (heads of 128): equals the oracle's
+    linear -> (bias) -> rope on the first rope_cols columns; the remaining heads are stored unrotated.
+    Ragged last row tile, positions wrapping at T, small problems refused."""
+    rng = np.random.default_rng(M + N + K)
+    hd, base = 128, 10000.0
+    a, b = bf16_round(rng.standard_normal((M, K))), bf16_round(rng.standard_normal((N, K)))
+    bias = bf16_round(rng.standard_normal(N)) if with_bias else None
+    lin = orc64.linear_fwd(a, b) + (bias[None, :] if with_bias else 0.0)
+    pad = (-M) % T                     # the oracle rotates whole sequences: pad the rows up to a multiple of T
+    linp = np.concatenate([lin, np.zeros((pad, N))]) if pad else lin
+    ref = linp.copy()
+    ref[:, :rope_cols] = orc64.rope(np.ascontiguousarray(linp[:, :rope_cols]), linp.shape[0] // T, T, rope_cols // hd, hd,
+                                    base, +1)
+    ref = ref[:M]
+    cs, sn = np.empty((T, hd // 2), np.float32), np.empty((T, hd // 2), np.float32)
+    assert L.mt_k_rope_table(cs.ctypes.data, sn.ctypes.data, T, hd, base) == 0
+    A, B, CS, SN = dev_bf16(a), dev_bf16(b), dev_f32(cs), dev_f32(sn)
+    BI = dev_bf16(bias) if with_bias else None
+    C = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_gemm_nt_rope(A.data_ptr(), K, B.data_ptr(), K, C.data_ptr(), N, BI.data_ptr() if with_bias else None,
+                           CS.data_ptr(), SN.data_ptr(), T, rope_cols, M, N, K, None))
+    got = host(C)
+    assert rel_l2(got, ref) < BF16_TOL
+    assert rel_l2(got[:, rope_cols:], lin[:, rope_cols:]) < BF16_TOL
+    # a grid too small for the kernel that rotates, or heads that do not line up: refused, nothing silently skipped
+    assert L.mt_k_gemm_nt_rope(A.data_ptr(), K, B.data_ptr(), K, C.data_ptr(), N, None, CS.data_ptr(), SN.data_ptr(), T,
+                               rope_cols, 256, N, K, None) == -2
+    assert L.mt_k_gemm_nt_rope(A.data_ptr(), K, B.data_ptr(), K, C.data_ptr(), N, None, CS.data_ptr(), SN.data_ptr(), T,
+                               rope_cols - 64, M, N, K, None) == -2
+
+
 # ----------------------------------------------------------------------------- SwiGLU
 def test_swiglu_forward_backward(orc64):
     rng = np.random.default_rng(6)
@@ -310,6 +344,43 @@ def _attention_case(orc64, B, T, Hq, Hkv, hd, seed):
                                            (1, 392, 5, 1, 128), (1, 8, 2, 1, 64)])
 def test_flash_attention_forward_backward(orc64, B, T, Hq, Hkv, hd):
     _attention_case(orc64, B, T, Hq, Hkv, hd, seed=T + hd)
+
+
+@pytest.mark.parametrize("B,T,Hq,Hkv,hd", [(2, 136, 4, 2, 64), (1, 264, 3, 1, 128)])
+def test_flash_attention_backward_with_rotary_backward_in_the_store(orc64, B, T, Hq, Hkv, hd):
+    """dq, dk rotated back inside the attention backward: q, k are the rotated tensors; the result is the
+    oracle's attention backward followed by its inverse rotation (dv is untouched)."""
+    rng = np.random.default_rng(B * T + hd)
+    nq, nkv, base = Hq * hd, Hkv * hd, 10000.0
+    ld = nq + 2 * nkv
+    qkv = bf16_round(rng.standard_normal((B * T, ld)))
+    q, k, v = qkv[:, :nq], qkv[:, nq:nq + nkv], qkv[:, nq + nkv:]
+    scale = 1.0 / np.sqrt(hd)
+    dout = bf16_round(rng.standard_normal((B * T, nq)))
+    dq_ref, dk_ref, dv_ref = orc64.attention_bwd(dout, q, k, v, B, T, Hq, Hkv, hd)
+    dq_ref = orc64.rope(np.ascontiguousarray(dq_ref), B, T, Hq, hd, base, -1)
+    dk_ref = orc64.rope(np.ascontiguousarray(dk_ref), B, T, Hkv, hd, base, -1)
+    cs, sn = np.empty((T, hd // 2), np.float32), np.empty((T, hd // 2), np.float32)
+    assert L.mt_k_rope_table(cs.ctypes.data, sn.ctypes.data, T, hd, base) == 0
+    QKV, DO, CS, SN = dev_bf16(qkv), dev_bf16(dout), dev_f32(cs), dev_f32(sn)
+    pq, pk, pv = QKV.data_ptr(), QKV.data_ptr() + 2 * nq, QKV.data_ptr() + 2 * (nq + nkv)
+    O = torch.zeros((B * T, nq), dtype=torch.bfloat16, device="cuda")
+    LSE = torch.zeros((B, Hq, T), dtype=torch.float32, device="cuda")
+    ok(L.mt_k_flash_fwd(O.data_ptr(), nq, LSE.data_ptr(), pq, ld, pk, ld, pv, ld, B, T, Hq, Hkv, hd, scale, None))
+    DELTA = torch.empty((B, Hq, T), dtype=torch.float32, device="cuda")
+    DQKV = torch.zeros((B * T, ld), dtype=torch.bfloat16, device="cuda")
+    pdq, pdk, pdv = DQKV.data_ptr(), DQKV.data_ptr() + 2 * nq, DQKV.data_ptr() + 2 * (nq + nkv)
+    ok(L.mt_k_flash_bwd_rope(pdq, ld, pdk, ld, pdv, ld, DO.data_ptr(), nq, pq, ld, pk, ld, pv, ld, O.data_ptr(), nq,
+                             LSE.data_ptr(), DELTA.data_ptr(), CS.data_ptr(), SN.data_ptr(), B, T, Hq, Hkv, hd, scale,
+                             None))
+    got = host(DQKV)
+    assert rel_l2(got[:, :nq], dq_ref) < 2e-2 and cosine(got[:, :nq], dq_ref) > 0.9995
+    assert rel_l2(got[:, nq:nq + nkv], dk_ref) < 2e-2 and cosine(got[:, nq:nq + nkv], dk_ref) > 0.9995
+    assert rel_l2(got[:, nq + nkv:], dv_ref) < 1e-2 and cosine(got[:, nq + nkv:], dv_ref) > 0.9995
+    # one table without the other is an argument error
+    assert L.mt_k_flash_bwd_rope(pdq, ld, pdk, ld, pdv, ld, DO.data_ptr(), nq, pq, ld, pk, ld, pv, ld, O.data_ptr(), nq,
+                                 LSE.data_ptr(), DELTA.data_ptr(), CS.data_ptr(), None, B, T, Hq, Hkv, hd, scale,
+                                 None) != 0
 
 
 def test_flash_attention_rejects_bad_shapes():

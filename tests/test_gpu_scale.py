@@ -26,6 +26,20 @@ def test_one_block_at_real_width_matches_oracle(orc64, name, T):
     check_against_oracle(orc64, shape, 1, T, params, tok, lab, loss, grads)
 
 
+@pytest.mark.parametrize("qkv_bias", [False, True])
+def test_many_tokens_take_the_large_grid_kernels_and_match_oracle(orc64, qkv_bias):
+    """A narrow model (heads of 128) on 12 x 1024 tokens: every projection then runs in the large-grid GEMM
+    kernels that the benchmark workloads use, including the q|k|v projection whose store applies the rotary
+    embedding, and the token-major weight-gradient kernel."""
+    shape = mt_inputs.ModelShape(2, 256, 4, 2, 128, 512, 512, qkv_bias=qkv_bias)
+    B, T = 12, 1024
+    params = mt_inputs.make_params(shape, seed=5, std=0.05)
+    tok, lab = mt_inputs.make_batch(shape.vocab, B, T, seed=6)
+    print(f"[scale] narrow model, {B} x {T} tokens, qkv_bias={qkv_bias}", flush=True)
+    loss, grads, _ = gpu_step(shape, B, T, params, tok, lab)
+    check_against_oracle(orc64, shape, B, T, params, tok, lab, loss, grads)
+
+
 def test_attention_rows_at_128k_context(orc64):
     """Forward output and dq of sampled query rows at T = 131072 (one sequence, 7B head layout reduced to
     2 query heads sharing nothing): each row needs only its own keys, so the oracle can do it row by row."""
