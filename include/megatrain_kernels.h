@@ -47,6 +47,13 @@ int32_t mt_k_gemm_nt_bias(const uint16_t *A, int64_t lda, const uint16_t *B, int
 int32_t mt_k_gemm_nt_rope(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, uint16_t *C, int64_t ldc,
                           const uint16_t *bias, const float *cos_tab, const float *sin_tab, int32_t T,
                           int32_t rope_cols, int32_t M, int32_t N, int32_t K, void *stream);
+/* The gate|up projection of a block's MLP with the activation computed in the store: W [2F, K] bf16 holds the gate
+ * rows then the up rows; s [M, F] bf16 (lds) = silu(gate) * up from the bf16-rounded gate and up, exactly what
+ * mt_k_gemm_nt into gu followed by mt_k_swiglu_fwd gives; gu [M, 2F] bf16 (ldgu) receives gate | up unless it is
+ * NULL.  Only for large grids (at least 192 tiles of 256 x 256 over M x 2F), K % 64 == 0, F % 128 == 0:
+ * MT_ERR_UNSUPPORTED otherwise. */
+int32_t mt_k_gemm_nt_swiglu(const uint16_t *A, int64_t lda, const uint16_t *W, int64_t ldw, uint16_t *gu, int64_t ldgu,
+                            uint16_t *s, int64_t lds, int32_t M, int32_t F, int32_t K, void *stream);
 /* Weight-gradient form: C[M,N] fp32 = At^T . Bt with At [K, M] bf16 (lda) and Bt [K, N] bf16 (ldb), both
  * token-major as the other kernels leave them (dW = dY^T X); accumulate != 0 adds to the existing C.
  * Requires K % 64 == 0, M % 8 == 0, N % 8 == 0: MT_ERR_UNSUPPORTED otherwise (transpose and use mt_k_gemm_nt). */

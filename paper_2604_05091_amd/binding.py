@@ -120,6 +120,8 @@ def lib():
         "mt_k_flash_bwd_rope": ([p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, p16,
                                  c_int64, p16, c_int64, pf, pf, pf, pf, c_int32, c_int32, c_int32, c_int32, c_int32,
                                  c_float, c_void_p], c_int32),
+        "mt_k_gemm_nt_swiglu": ([p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, c_int32, c_int32, c_int32, c_void_p],
+                                c_int32),
         "mt_k_gemm_tn": ([p16, c_int64, p16, c_int64, pf, c_int64, c_int32, c_int32, c_int32, c_int32, c_void_p], c_int32),
         "mt_k_bias_grad_ws_bytes": ([c_int32], c_size_t),
         "mt_k_bias_grad": ([pf, p16, c_int64, c_int64, c_int32, c_void_p, c_void_p], c_int32),

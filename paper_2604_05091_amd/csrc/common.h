@@ -84,11 +84,19 @@ struct GemmArgs {
     // row % rope_T; tables cos/sin [rope_T][64] fp32
     const float *rope_cos = nullptr, *rope_sin = nullptr;
     int32_t rope_T = 0, rope_cols = 0;
+    // optional SwiGLU fused into the store (gemm_nt only, see gemm_nt_fuses_glu): B is [2 glu_F, K], gate rows
+    // then up rows (N = 2 glu_F); a tile computes the gate and the up columns of the same 128 indices and stores
+    // glu_out[M, glu_F] = silu(gate) * up (bf16, from the bf16-rounded gate and up, as a separate pass over C would).
+    // C may then be NULL (gate | up themselves are not stored).
+    int32_t glu_F = 0;
+    bf16_t *glu_out = nullptr; int64_t ld_glu = 0;
 };
 hipError_t gemm_nt(const GemmArgs &g, hipStream_t s);
 // true when gemm_nt would apply g.rope_* in its epilogue for this problem (large grid, K % 64 == 0, head-aligned
 // columns); otherwise a call with rope_cos set fails with hipErrorNotSupported and the caller rotates separately
 bool gemm_nt_fuses_rope(const GemmArgs &g);
+// the same for g.glu_*: large grid, K % 64 == 0, glu_F % 128 == 0, bf16 output without residual or bias
+bool gemm_nt_fuses_glu(const GemmArgs &g);
 // C[M,N] = A^T . B with A given as [K, M] and B as [K, N] (lda, ldb their row pitches): the weight-gradient
 // form dW = dY^T X taken straight from token-major activations.  fp32 output (accumulate optional);
 // needs K % 64 == 0, M % 8 == 0, N % 8 == 0; returns hipErrorNotSupported otherwise (callers then transpose

@@ -350,6 +350,43 @@ __device__ __forceinline__ void w4_store_rope(const GemmArgs &g, const f32x16 (&
     }
 }
 
+// SwiGLU store (g.glu_*): the tile's 256 B rows are gate columns c .. c+63, up columns c .. c+63, gate c+64 ..,
+// up c+64 .. with c = 128 tn, so a wave holds gate (blocks 0, 1) and up (blocks 2, 3) of the same 64 columns and a
+// lane both values of every element it owns.  Rows are guarded; columns are complete (glu_F % 128 == 0).
+__device__ __forceinline__ void w4_store_glu(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int tn, int wm, int wn,
+                                             int l32, int hl) {
+    const int row_l = m0 + wm * 128 + l32, col_w = tn * 128 + wn * 64 + hl * 4;
+    bf16_t *cw = reinterpret_cast<bf16_t *>(g.C);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = row_l + i * 32;
+        if (row >= g.M) continue;
+#pragma unroll
+        for (int jp = 0; jp < 2; ++jp)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = col_w + jp * 32 + q * 8;
+                uint2 pg, pu, ps;
+                pg.x = pack2bf(acc[i][jp][4 * q], acc[i][jp][4 * q + 1]);
+                pg.y = pack2bf(acc[i][jp][4 * q + 2], acc[i][jp][4 * q + 3]);
+                pu.x = pack2bf(acc[i][jp + 2][4 * q], acc[i][jp + 2][4 * q + 1]);
+                pu.y = pack2bf(acc[i][jp + 2][4 * q + 2], acc[i][jp + 2][4 * q + 3]);
+                if (cw) {
+                    *reinterpret_cast<uint2 *>(cw + (int64_t)row * g.ldc + col) = pg;
+                    *reinterpret_cast<uint2 *>(cw + (int64_t)row * g.ldc + g.glu_F + col) = pu;
+                }
+                const float gv[4] = {bflo(pg.x), bfhi(pg.x), bflo(pg.y), bfhi(pg.y)};
+                const float uv[4] = {bflo(pu.x), bfhi(pu.x), bflo(pu.y), bfhi(pu.y)};
+                float sv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sv[e] = gv[e] * (1.0f / (1.0f + __expf(-gv[e]))) * uv[e];
+                ps.x = pack2bf(sv[0], sv[1]);
+                ps.y = pack2bf(sv[2], sv[3]);
+                *reinterpret_cast<uint2 *>(g.glu_out + (int64_t)row * g.ld_glu + col) = ps;
+            }
+    }
+}
+
 __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles_m, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     constexpr int BM = W4_BM, BN = W4_BN;
@@ -373,12 +410,16 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
     // loader: thread owns 16-byte chunk (tid & 7) of rows (tid >> 3) + 32 j, j < 8, of A and of B
     const int lrow = tid >> 3, lkc = (tid & 7) * 8;
     const bf16_t *abase = g.A + (int64_t)m0 * g.lda;
-    const bf16_t *bbase = g.B + (int64_t)n0 * g.ldb;
+    const bool glu = g.glu_F > 0;
+    const bf16_t *bbase = g.B + (glu ? 0 : (int64_t)n0 * g.ldb);
     uint32_t off[16];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         off[j] = (uint32_t)(min(lrow + 32 * j, g.M - 1 - m0) * (int)g.lda + lkc);
-        off[8 + j] = (uint32_t)(min(lrow + 32 * j, g.N - 1 - n0) * (int)g.ldb + lkc);
+        // SwiGLU pairing: tile rows in blocks of 64 = gate c.., up c.., gate c+64.., up c+64.. (c = 128 tn)
+        const int brow = glu ? ((j >> 1) & 1) * g.glu_F + tn * 128 + (j >> 2) * 64 + lrow + 32 * (j & 1)
+                             : min(lrow + 32 * j, g.N - 1 - n0);
+        off[8 + j] = (uint32_t)(brow * (int)g.ldb + lkc);
     }
     u32x4 st[16];
     bf16x8 fr[2][8];   // [set][A block 0..3 | B block 0..3]
@@ -491,7 +532,8 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
 #undef W4_PHASE
 #undef W4_STEP
 
-    if (g.rope_cos) w4_store_rope(g, acc, m0, n0, wm, wn, l32, hl);
+    if (glu) w4_store_glu(g, acc, m0, tn, wm, wn, l32, hl);
+    else if (g.rope_cos) w4_store_rope(g, acc, m0, n0, wm, wn, l32, hl);
     else w4_store(g, acc, m0, n0, wm, wn, l32, hl);
 }
 
@@ -504,7 +546,8 @@ hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = (g.N + W4_BN - 1) / W4_BN;
+    // with the SwiGLU pairing a tile covers 128 gate and the matching 128 up columns
+    const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = g.glu_F > 0 ? g.glu_F / 128 : (g.N + W4_BN - 1) / W4_BN;
     hipLaunchKernelGGL(gemm_nt_w4_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(W4_NT), lds, s, g, tiles_m, tiles_n);
     return hipGetLastError();
 }
@@ -689,12 +732,21 @@ bool gemm_nt_fuses_rope(const GemmArgs &g) {
            !((uintptr_t)g.rope_sin & 15);
 }
 
+bool gemm_nt_fuses_glu(const GemmArgs &g) {
+    return g.M > 0 && g.K > 0 && g.glu_F > 0 && g.N == 2 * g.glu_F && (g.glu_F % 128) == 0 && takes_w4(g) && !g.out_fp32 &&
+           !g.R && !g.bias && !g.rope_cos && !g.rope_sin && g.glu_out && !(g.ld_glu & 3) && g.ld_glu >= g.glu_F &&
+           !((uintptr_t)g.glu_out & 7) && (!g.C || (!(g.ldc & 3) && !((uintptr_t)g.C & 7))) &&
+           (int64_t)g.N * g.ldb < ((int64_t)1 << 31);
+}
+
 hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
     if ((g.rope_cos || g.rope_sin) && !gemm_nt_fuses_rope(g)) return hipErrorNotSupported;
+    if ((g.glu_F || g.glu_out) && !gemm_nt_fuses_glu(g)) return hipErrorNotSupported;
+    if (!g.C && !g.glu_F) return hipErrorInvalidValue;
     if ((g.K & 7) || (g.lda & 7) || (g.ldb & 7)) return hipErrorInvalidValue;
     if (((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
-    if (g.lda < g.K || g.ldb < g.K || g.ldc < g.N) return hipErrorInvalidValue;
+    if (g.lda < g.K || g.ldb < g.K || (g.C && g.ldc < g.N)) return hipErrorInvalidValue;
     if (g.R && (g.out_fp32 || g.ldr < g.N)) return hipErrorInvalidValue;
     if (g.bias && g.out_fp32) return hipErrorInvalidValue;
     // offsets inside one tile are 32-bit: 256 rows of either operand must stay below 2^31 elements
@@ -713,7 +765,8 @@ hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
 hipError_t gemm_tn(const GemmArgs &g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
     if ((g.lda & 7) || (g.ldb & 7) || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
-    if (g.lda < g.M || g.ldb < g.N || g.ldc < g.N || !g.out_fp32 || g.R || g.bias || g.rope_cos || g.rope_sin)
+    if (g.lda < g.M || g.ldb < g.N || g.ldc < g.N || !g.out_fp32 || g.R || g.bias || g.rope_cos || g.rope_sin || g.glu_F ||
+        g.glu_out)
         return hipErrorInvalidValue;
     if ((g.K % BK) || (g.M & 7) || (g.N & 7)) return hipErrorNotSupported;
     return launch_tn(g, s);

@@ -246,6 +246,34 @@ def test_gemm_with_rotary_embedding_in_the_store(orc64, M, N, K, T, rope_cols, w
                                rope_cols - 64, M, N, K, None) == -2
 
 
+@pytest.mark.parametrize("M,F,K,keep_gu", [(3300, 2048, 128, True), (6400, 1152, 64, False)])
+def test_gemm_with_swiglu_in_the_store(orc64, M, F, K, keep_gu):
+    """gate|up projection whose store computes silu(gate) * up: the activation equals the oracle's, is bit-identical
+    to the two-kernel route (GEMM into gu, then the SwiGLU kernel), and gu is written only when asked for.
+    Ragged last row tile; small problems and ffn sizes that are not multiples of 128 are refused."""
+    rng = np.random.default_rng(M + F + K)
+    a, w = bf16_round(rng.standard_normal((M, K))), bf16_round(rng.standard_normal((2 * F, K)) * 0.3)
+    gu_ref = orc64.linear_fwd(a, w)
+    gur = bf16_round(gu_ref)
+    s_ref = orc64.swiglu_fwd(np.ascontiguousarray(gur[:, :F]), np.ascontiguousarray(gur[:, F:]))
+    A, W = dev_bf16(a), dev_bf16(w)
+    GU = torch.full((M, 2 * F), 3.0, dtype=torch.bfloat16, device="cuda")
+    S = torch.zeros((M, F), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_gemm_nt_swiglu(A.data_ptr(), K, W.data_ptr(), K, GU.data_ptr() if keep_gu else None, 2 * F, S.data_ptr(), F,
+                             M, F, K, None))
+    assert rel_l2(host(S), s_ref) < 2 * BF16_TOL
+    GU2 = torch.zeros((M, 2 * F), dtype=torch.bfloat16, device="cuda")
+    S2 = torch.zeros((M, F), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_gemm_nt(A.data_ptr(), K, W.data_ptr(), K, GU2.data_ptr(), 2 * F, None, 0, M, 2 * F, K, 0, 0, None))
+    ok(L.mt_k_swiglu_fwd(S2.data_ptr(), GU2.data_ptr(), M, F, None))
+    assert torch.equal(S, S2)
+    if keep_gu:
+        assert torch.equal(GU, GU2)
+        assert rel_l2(host(GU), gu_ref) < BF16_TOL
+    assert L.mt_k_gemm_nt_swiglu(A.data_ptr(), K, W.data_ptr(), K, None, 0, S.data_ptr(), F, 256, F, K, None) == -2
+    assert L.mt_k_gemm_nt_swiglu(A.data_ptr(), K, W.data_ptr(), K, None, 0, S.data_ptr(), F - 64, M, F - 64, K, None) == -2
+
+
 # ----------------------------------------------------------------------------- SwiGLU
 def test_swiglu_forward_backward(orc64):
     rng = np.random.default_rng(6)
