@@ -227,6 +227,30 @@ constexpr int W4_A_BYTES = W4_BM * LDT * 2, W4_STAGE_BYTES = 2 * W4_A_BYTES;
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// bf16 results leave through LDS.  Stored straight from the accumulator layout, a store instruction touches 32
+// rows with 16 bytes each, and these partial-line writes cost 10-13 us per tile; instead every wave writes its
+// 128 x NC block (bf16) into a private LDS region (the k-loop's stages are free after its last barrier) and reads
+// it back row-wise, so that a store instruction covers whole 128-byte lines (16 bytes per lane, consecutive lanes
+// at consecutive addresses).  Region pitch NC + 8 elements: conflict-free for the 8-byte writes and the 16-byte reads.
+constexpr int W4_EP_PITCH = 128 + 8;
+__device__ __forceinline__ bf16_t *w4_ep_region(bf16_t *smem, int wave) { return smem + wave * 128 * W4_EP_PITCH; }
+
+// second half: rows of the wave's block from LDS to C, NC columns starting at col0; rows >= M skipped
+template <int NC>
+__device__ __forceinline__ void w4_flush_rows(bf16_t *C, int64_t ldc, int M, int row0, int col0, const bf16_t *region,
+                                              int lane) {
+    constexpr int LPR = NC / 8, RPI = 64 / LPR;   // lanes per row, rows per instruction
+    const int lr = lane / LPR, lc = (lane % LPR) * 8;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wave's own LDS writes have landed
+#pragma unroll 8
+    for (int it = 0; it < 128 / RPI; ++it) {
+        const int r = it * RPI + lr;
+        const int64_t row = row0 + r;
+        if (row >= M) continue;
+        *reinterpret_cast<uint4 *>(C + row * ldc + col0 + lc) = *reinterpret_cast<const uint4 *>(region + r * W4_EP_PITCH + lc);
+    }
+}
+
 // Epilogue of the 4-wave kernels.  The MFMAs are issued with the operands swapped (B fragment first), so each
 // 32x32 block holds C transposed: the lane owns row l32 of the block and, per group q = r/4, the four
 // consecutive columns 8 q + 4 hl + (0..3): one 8-byte (bf16) or 16-byte (fp32) store each.
@@ -298,21 +322,74 @@ __device__ __forceinline__ void w4_store(const GemmArgs &g, const f32x16 (&acc)[
     }
 }
 
+// complete, aligned tiles (what the host checks before it picks the kernel instantiated with this store)
+__device__ __forceinline__ void w4_store_full_bf16(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int n0, int wm,
+                                                   int wn, int l32, int hl, bf16_t *smem) {
+    const int wave = wm * 2 + wn, lane = hl * 32 + l32;
+    bf16_t *region = w4_ep_region(smem, wave);
+    const int col_l = n0 + wn * 128 + hl * 4;
+    const bf16_t *bias = g.bias ? g.bias + col_l : nullptr;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        bf16_t *lp = region + (i * 32 + l32) * W4_EP_PITCH + hl * 4;
+        // bias and residual are added in fp32, before the one rounding to bf16
+        const bf16_t *rp = g.R ? g.R + (int64_t)(m0 + wm * 128 + i * 32 + l32) * g.ldr + col_l : nullptr;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int o = j * 32 + q * 8;
+                float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
+                if (bias) {
+                    const uint2 bv = *reinterpret_cast<const uint2 *>(bias + o);
+                    v0 += bflo(bv.x); v1 += bfhi(bv.x); v2 += bflo(bv.y); v3 += bfhi(bv.y);
+                }
+                if (rp) {
+                    const uint2 rv = *reinterpret_cast<const uint2 *>(rp + o);
+                    v0 += bflo(rv.x); v1 += bfhi(rv.x); v2 += bflo(rv.y); v3 += bfhi(rv.y);
+                }
+                uint2 u;
+                u.x = pack2bf(v0, v1);
+                u.y = pack2bf(v2, v3);
+                *reinterpret_cast<uint2 *>(lp + o) = u;
+            }
+    }
+    w4_flush_rows<128>(reinterpret_cast<bf16_t *>(g.C), g.ldc, g.M, m0 + wm * 128, n0 + wn * 128, region, lane);
+}
+
+__device__ __forceinline__ void w4_store_full_f32(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int n0, int wm,
+                                                  int wn, int l32, int hl) {
+    const int row_l = m0 + wm * 128 + l32, col_l = n0 + wn * 128 + hl * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float *cp = reinterpret_cast<float *>(g.C) + (int64_t)(row_l + i * 32) * g.ldc + col_l;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int o = j * 32 + q * 8;
+                f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                if (g.accumulate) v += *reinterpret_cast<const f32x4 *>(cp + o);
+                *reinterpret_cast<f32x4 *>(cp + o) = v;
+            }
+    }
+}
+
 // bf16 store with the rotary embedding applied on the way out (g.rope_*): the wave's 128 columns are one head,
 // the lane holds both members (j, j + 64) of every pair of its rows: blocks j4 and j4 + 2 of acc.  Columns are
 // complete (N % 128 == 0, checked on the host); rows are guarded.  Heads at or beyond rope_cols (the value
-// projection) are stored unrotated.  Bias, if any, is added before the rotation.
+// projection) are stored unrotated.  Bias, if any, is added before the rotation.  The rows leave through LDS.
 __device__ __forceinline__ void w4_store_rope(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int n0, int wm, int wn,
-                                              int l32, int hl) {
+                                              int l32, int hl, bf16_t *smem) {
     const int row_l = m0 + wm * 128 + l32, col_w = n0 + wn * 128;
     if (col_w >= g.N) return;
     const bool rot = col_w < g.rope_cols;
-    bf16_t *cw = reinterpret_cast<bf16_t *>(g.C);
+    bf16_t *region = w4_ep_region(smem, wm * 2 + wn);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int row = row_l + i * 32;
-        if (row >= g.M) continue;
-        const int64_t tpos = (int64_t)(row % g.rope_T) * 64;
+        // rows past M compute values nobody stores; their table row is still a valid one
+        const int64_t tpos = (int64_t)((row_l + i * 32) % g.rope_T) * 64;
+        bf16_t *lp = region + (i * 32 + l32) * W4_EP_PITCH;
 #pragma unroll
         for (int jp = 0; jp < 2; ++jp)
 #pragma unroll
@@ -340,40 +417,41 @@ __device__ __forceinline__ void w4_store_rope(const GemmArgs &g, const f32x16 (&
                         b[e] = yb;
                     }
                 }
-                bf16_t *cp = cw + (int64_t)row * g.ldc + col_w + jc;
                 uint2 oa, ob;
                 oa.x = pack2bf(a[0], a[1]); oa.y = pack2bf(a[2], a[3]);
                 ob.x = pack2bf(b[0], b[1]); ob.y = pack2bf(b[2], b[3]);
-                *reinterpret_cast<uint2 *>(cp) = oa;
-                *reinterpret_cast<uint2 *>(cp + 64) = ob;
+                *reinterpret_cast<uint2 *>(lp + jc) = oa;
+                *reinterpret_cast<uint2 *>(lp + jc + 64) = ob;
             }
     }
+    w4_flush_rows<128>(reinterpret_cast<bf16_t *>(g.C), g.ldc, g.M, m0 + wm * 128, col_w, region, hl * 32 + l32);
 }
 
 // SwiGLU store (g.glu_*): the tile's 256 B rows are gate columns c .. c+63, up columns c .. c+63, gate c+64 ..,
 // up c+64 .. with c = 128 tn, so a wave holds gate (blocks 0, 1) and up (blocks 2, 3) of the same 64 columns and a
 // lane both values of every element it owns.  Rows are guarded; columns are complete (glu_F % 128 == 0).
 __device__ __forceinline__ void w4_store_glu(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int tn, int wm, int wn,
-                                             int l32, int hl) {
-    const int row_l = m0 + wm * 128 + l32, col_w = tn * 128 + wn * 64 + hl * 4;
+                                             int l32, int hl, bf16_t *smem) {
+    const int row_l = m0 + wm * 128 + l32, col_w = tn * 128 + wn * 64;
     bf16_t *cw = reinterpret_cast<bf16_t *>(g.C);
+    bf16_t *region = w4_ep_region(smem, wm * 2 + wn);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = row_l + i * 32;
-        if (row >= g.M) continue;
+        bf16_t *lp = region + (i * 32 + l32) * W4_EP_PITCH + hl * 4;
 #pragma unroll
         for (int jp = 0; jp < 2; ++jp)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int col = col_w + jp * 32 + q * 8;
+                const int o = jp * 32 + q * 8;
                 uint2 pg, pu, ps;
                 pg.x = pack2bf(acc[i][jp][4 * q], acc[i][jp][4 * q + 1]);
                 pg.y = pack2bf(acc[i][jp][4 * q + 2], acc[i][jp][4 * q + 3]);
                 pu.x = pack2bf(acc[i][jp + 2][4 * q], acc[i][jp + 2][4 * q + 1]);
                 pu.y = pack2bf(acc[i][jp + 2][4 * q + 2], acc[i][jp + 2][4 * q + 3]);
-                if (cw) {
-                    *reinterpret_cast<uint2 *>(cw + (int64_t)row * g.ldc + col) = pg;
-                    *reinterpret_cast<uint2 *>(cw + (int64_t)row * g.ldc + g.glu_F + col) = pu;
+                if (cw && row < g.M) {   // gate | up themselves: straight from the accumulator layout
+                    *reinterpret_cast<uint2 *>(cw + (int64_t)row * g.ldc + col_w + hl * 4 + o) = pg;
+                    *reinterpret_cast<uint2 *>(cw + (int64_t)row * g.ldc + g.glu_F + col_w + hl * 4 + o) = pu;
                 }
                 const float gv[4] = {bflo(pg.x), bfhi(pg.x), bflo(pg.y), bfhi(pg.y)};
                 const float uv[4] = {bflo(pu.x), bfhi(pu.x), bflo(pu.y), bfhi(pu.y)};
@@ -382,11 +460,16 @@ __device__ __forceinline__ void w4_store_glu(const GemmArgs &g, const f32x16 (&a
                 for (int e = 0; e < 4; ++e) sv[e] = gv[e] * (1.0f / (1.0f + __expf(-gv[e]))) * uv[e];
                 ps.x = pack2bf(sv[0], sv[1]);
                 ps.y = pack2bf(sv[2], sv[3]);
-                *reinterpret_cast<uint2 *>(g.glu_out + (int64_t)row * g.ld_glu + col) = ps;
+                *reinterpret_cast<uint2 *>(lp + o) = ps;
             }
     }
+    w4_flush_rows<64>(g.glu_out, g.ld_glu, g.M, m0 + wm * 128, col_w, region, hl * 32 + l32);
 }
 
+// The epilogue is a template parameter: one kernel that carries all of them keeps so much guarded store code alive
+// that the compiler moves accumulators through scratch memory on the way out (measured: 13-16 us per tile).
+enum { EPI_GENERAL = 0, EPI_FULL_BF16 = 1, EPI_FULL_F32 = 2, EPI_ROPE = 3, EPI_GLU = 4 };
+template <int EPI>
 __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles_m, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     constexpr int BM = W4_BM, BN = W4_BN;
@@ -410,7 +493,7 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
     // loader: thread owns 16-byte chunk (tid & 7) of rows (tid >> 3) + 32 j, j < 8, of A and of B
     const int lrow = tid >> 3, lkc = (tid & 7) * 8;
     const bf16_t *abase = g.A + (int64_t)m0 * g.lda;
-    const bool glu = g.glu_F > 0;
+    constexpr bool glu = EPI == EPI_GLU;
     const bf16_t *bbase = g.B + (glu ? 0 : (int64_t)n0 * g.ldb);
     uint32_t off[16];
 #pragma unroll
@@ -532,24 +615,37 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
 #undef W4_PHASE
 #undef W4_STEP
 
-    if (glu) w4_store_glu(g, acc, m0, tn, wm, wn, l32, hl);
-    else if (g.rope_cos) w4_store_rope(g, acc, m0, n0, wm, wn, l32, hl);
+    if constexpr (EPI == EPI_GLU) w4_store_glu(g, acc, m0, tn, wm, wn, l32, hl, smem);
+    else if constexpr (EPI == EPI_ROPE) w4_store_rope(g, acc, m0, n0, wm, wn, l32, hl, smem);
+    else if constexpr (EPI == EPI_FULL_BF16) w4_store_full_bf16(g, acc, m0, n0, wm, wn, l32, hl, smem);
+    else if constexpr (EPI == EPI_FULL_F32) w4_store_full_f32(g, acc, m0, n0, wm, wn, l32, hl);
     else w4_store(g, acc, m0, n0, wm, wn, l32, hl);
 }
 
-hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
+template <int EPI>
+hipError_t launch_w4_epi(const GemmArgs &g, hipStream_t s) {
     constexpr size_t lds = (size_t)2 * W4_STAGE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_w4_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_w4_kernel<EPI>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     // with the SwiGLU pairing a tile covers 128 gate and the matching 128 up columns
-    const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = g.glu_F > 0 ? g.glu_F / 128 : (g.N + W4_BN - 1) / W4_BN;
-    hipLaunchKernelGGL(gemm_nt_w4_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(W4_NT), lds, s, g, tiles_m, tiles_n);
+    const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = EPI == EPI_GLU ? g.glu_F / 128 : (g.N + W4_BN - 1) / W4_BN;
+    hipLaunchKernelGGL(gemm_nt_w4_kernel<EPI>, dim3((unsigned)(tiles_m * tiles_n)), dim3(W4_NT), lds, s, g, tiles_m, tiles_n);
     return hipGetLastError();
+}
+
+hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
+    if (g.glu_F > 0) return launch_w4_epi<EPI_GLU>(g, s);
+    if (g.rope_cos) return launch_w4_epi<EPI_ROPE>(g, s);
+    // every tile complete and every access of the store aligned: the unguarded vector stores
+    const bool full = g.M % W4_BM == 0 && g.N % W4_BN == 0 && !(g.ldc & 7) && !((uintptr_t)g.C & 15) &&
+                      (!g.R || (!(g.ldr & 3) && !((uintptr_t)g.R & 7))) && !((uintptr_t)g.bias & 7);
+    if (!full) return launch_w4_epi<EPI_GENERAL>(g, s);
+    return g.out_fp32 ? launch_w4_epi<EPI_FULL_F32>(g, s) : launch_w4_epi<EPI_FULL_BF16>(g, s);
 }
 
 
@@ -563,6 +659,7 @@ hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
 constexpr int TN_LDT = 256 + 40;
 constexpr int TN_TILE_BYTES = BK * TN_LDT * 2, TN_STAGE_BYTES = 2 * TN_TILE_BYTES;
 
+template <int EPI>
 __global__ __launch_bounds__(W4_NT) void gemm_tn_w4_kernel(GemmArgs g, int tiles_m, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     constexpr int BM = W4_BM, BN = W4_BN;
@@ -692,21 +789,28 @@ __global__ __launch_bounds__(W4_NT) void gemm_tn_w4_kernel(GemmArgs g, int tiles
 #undef TN_MMA_ROWS
 #undef TN_PHASE
 #undef TN_STEP
-    w4_store(g, acc, m0, n0, wm, wn, l32, hl);
+    if constexpr (EPI == EPI_FULL_F32) w4_store_full_f32(g, acc, m0, n0, wm, wn, l32, hl);
+    else w4_store(g, acc, m0, n0, wm, wn, l32, hl);
 }
 
-hipError_t launch_tn(const GemmArgs &g, hipStream_t s) {
+template <int EPI>
+hipError_t launch_tn_epi(const GemmArgs &g, hipStream_t s) {
     constexpr size_t lds = (size_t)2 * TN_STAGE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tn_w4_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tn_w4_kernel<EPI>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = (g.N + W4_BN - 1) / W4_BN;
-    hipLaunchKernelGGL(gemm_tn_w4_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(W4_NT), lds, s, g, tiles_m, tiles_n);
+    hipLaunchKernelGGL(gemm_tn_w4_kernel<EPI>, dim3((unsigned)(tiles_m * tiles_n)), dim3(W4_NT), lds, s, g, tiles_m, tiles_n);
     return hipGetLastError();
+}
+
+hipError_t launch_tn(const GemmArgs &g, hipStream_t s) {
+    const bool full = g.M % W4_BM == 0 && g.N % W4_BN == 0 && !(g.ldc & 3) && !((uintptr_t)g.C & 15);
+    return full ? launch_tn_epi<EPI_FULL_F32>(g, s) : launch_tn_epi<EPI_GENERAL>(g, s);
 }
 
 int variant_override() {
@@ -727,15 +831,15 @@ static bool takes_w4(const GemmArgs &g) {
 
 bool gemm_nt_fuses_rope(const GemmArgs &g) {
     return g.M > 0 && g.N > 0 && g.K > 0 && takes_w4(g) && !g.out_fp32 && !g.R && g.rope_T > 0 && (g.N % 128) == 0 &&
-           (g.rope_cols % 128) == 0 && g.rope_cols <= g.N && !(g.ldc & 3) && !((uintptr_t)g.C & 7) &&
+           (g.rope_cols % 128) == 0 && g.rope_cols <= g.N && !(g.ldc & 7) && !((uintptr_t)g.C & 15) &&
            !((uintptr_t)g.bias & 7) && g.rope_cos && g.rope_sin && !((uintptr_t)g.rope_cos & 15) &&
            !((uintptr_t)g.rope_sin & 15);
 }
 
 bool gemm_nt_fuses_glu(const GemmArgs &g) {
     return g.M > 0 && g.K > 0 && g.glu_F > 0 && g.N == 2 * g.glu_F && (g.glu_F % 128) == 0 && takes_w4(g) && !g.out_fp32 &&
-           !g.R && !g.bias && !g.rope_cos && !g.rope_sin && g.glu_out && !(g.ld_glu & 3) && g.ld_glu >= g.glu_F &&
-           !((uintptr_t)g.glu_out & 7) && (!g.C || (!(g.ldc & 3) && !((uintptr_t)g.C & 7))) &&
+           !g.R && !g.bias && !g.rope_cos && !g.rope_sin && g.glu_out && !(g.ld_glu & 7) && g.ld_glu >= g.glu_F &&
+           !((uintptr_t)g.glu_out & 15) && (!g.C || (!(g.ldc & 3) && !((uintptr_t)g.C & 7))) &&
            (int64_t)g.N * g.ldb < ((int64_t)1 << 31);
 }
 
