@@ -179,7 +179,9 @@ __device__ __forceinline__ bool decode_block(int per_set, int n_sets, int *set, 
 // position modulo 8, 4 and 2 then carries the same amount of work.  i in [0, n) -> a permutation of [0, n).
 __device__ __forceinline__ int snake8(int i, int n) {
     const int row = i >> 3;
-    if (!(row & 1) || row * 8 + 7 >= n) return i;
+    // long sequences: the classes differ by less than a percent, and the plain order keeps neighbouring blocks
+    // (shared keys) together, which measured 1 % faster at 128k
+    if (n > 128 || !(row & 1) || row * 8 + 7 >= n) return i;
     return row * 8 + 7 - (i & 7);
 }
 inline unsigned grid_blocks(int per_set, int n_sets) { return (unsigned)(((n_sets + kXcds - 1) / kXcds) * kXcds * per_set); }
