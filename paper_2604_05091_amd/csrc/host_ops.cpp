@@ -5,6 +5,8 @@
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
+#include <condition_variable>
+#include <mutex>
 #include <thread>
 #include <vector>
 
@@ -22,6 +24,74 @@ int host_threads() {
     return n;
 }
 
+namespace {
+
+// Fork-join pool: host_threads() - 1 workers created on first use and kept for the life of the process (spawning
+// 15 threads per call costs ~0.2 ms, a third of the Adam update of a 4 M-element tensor).  One job at a time;
+// a caller that finds the pool busy (the optimizer thread and the weight-packing thread can overlap) falls back
+// to threads of its own.
+class ForkJoinPool {
+  public:
+    ForkJoinPool() {
+        const int n = host_threads() - 1;
+        for (int i = 0; i < n; ++i) workers_.emplace_back([this, i] { work(i); });
+    }
+    ~ForkJoinPool() {
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            stop_ = true;
+        }
+        cv_work_.notify_all();
+        for (auto &t : workers_) t.join();
+    }
+    bool try_run(const std::function<void(size_t, size_t)> &fn, size_t n, size_t per, size_t nt) {
+        if (workers_.empty() || !job_mu_.try_lock()) return false;
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            fn_ = &fn; n_ = n; per_ = per; nt_ = nt;
+            pending_ = (int)workers_.size();
+            ++gen_;
+        }
+        cv_work_.notify_all();
+        fn(0, per < n ? per : n);
+        {
+            std::unique_lock<std::mutex> lk(mu_);
+            cv_done_.wait(lk, [this] { return pending_ == 0; });
+        }
+        job_mu_.unlock();
+        return true;
+    }
+
+  private:
+    void work(int id) {
+        uint64_t seen = 0;
+        for (;;) {
+            std::unique_lock<std::mutex> lk(mu_);
+            cv_work_.wait(lk, [&] { return stop_ || gen_ != seen; });
+            if (stop_) return;
+            seen = gen_;
+            const size_t t = (size_t)id + 1, b = t * per_, e = b + per_ < n_ ? b + per_ : n_;
+            const std::function<void(size_t, size_t)> *fn = fn_;
+            if (t < nt_ && b < n_) {
+                lk.unlock();
+                (*fn)(b, e);
+                lk.lock();
+            }
+            if (--pending_ == 0) cv_done_.notify_one();
+        }
+    }
+    std::vector<std::thread> workers_;
+    std::mutex mu_, job_mu_;
+    std::condition_variable cv_work_, cv_done_;
+    const std::function<void(size_t, size_t)> *fn_ = nullptr;
+    size_t n_ = 0, per_ = 0, nt_ = 0;
+    uint64_t gen_ = 0;
+    int pending_ = 0;
+    bool stop_ = false;
+};
+
+}  // namespace
+
 void parallel_for(size_t n, size_t min_chunk, const std::function<void(size_t, size_t)> &fn) {
     if (n == 0) return;
     size_t nt = (size_t)host_threads();
@@ -34,6 +104,8 @@ void parallel_for(size_t n, size_t min_chunk, const std::function<void(size_t, s
     }
     // chunk boundaries on multiples of 64 elements so vector loops stay aligned
     const size_t per = ((n + nt - 1) / nt + 63) & ~(size_t)63;
+    static ForkJoinPool pool;
+    if (pool.try_run(fn, n, per, nt)) return;
     std::vector<std::thread> th;
     th.reserve(nt);
     for (size_t t = 1; t < nt; ++t) {
