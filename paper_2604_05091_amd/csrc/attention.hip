@@ -619,6 +619,9 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
             mfma_tr_accumulate<HD, LDK>(dvacc, dOC, tr_off, rbC, cch, fP[1 - (PAR)][cch]);              \
             mfma_tr_accumulate<HD, LDK>(dkacc, QC, tr_off, rbC, cch, fS[1 - (PAR)][cch]);               \
         }                                                                                               \
+        /* B's results are consumed in the next slot only: without this the compiler sinks B's arithmetic   \
+           below the tile commit that follows the odd slot, out of reach of this slot's MFMAs */            \
+        asm volatile("" : "+v"(fP[PAR][0]), "+v"(fP[PAR][1]), "+v"(fS[PAR][0]), "+v"(fS[PAR][1]));      \
     }
     // B's dependence on the set written by the previous slot's A, and C's on the previous slot's B, are the
     // only links between slots; within a slot the scheduler is free to interleave the three parts.
