@@ -54,6 +54,12 @@ int32_t mt_k_gemm_nt_rope(const uint16_t *A, int64_t lda, const uint16_t *B, int
  * MT_ERR_UNSUPPORTED otherwise. */
 int32_t mt_k_gemm_nt_swiglu(const uint16_t *A, int64_t lda, const uint16_t *W, int64_t ldw, uint16_t *gu, int64_t ldgu,
                             uint16_t *s, int64_t lds, int32_t M, int32_t F, int32_t K, void *stream);
+/* The input gradient of the MLP's down projection with the SwiGLU backward applied in the store: ds = A . B^T
+ * ([M,F], rounded to bf16), then dgu [M, 2F] (lddgu) = dgate | dup from ds and the forward's gate | up in gu [M, 2F]
+ * (ldgu): exactly what mt_k_gemm_nt into ds followed by mt_k_swiglu_bwd gives.  Only for large grids (at least 192
+ * tiles of 256 x 256), K % 64 == 0, F % 8 == 0, 16-byte aligned gu and dgu: MT_ERR_UNSUPPORTED otherwise. */
+int32_t mt_k_gemm_nt_swiglu_bwd(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, uint16_t *dgu, int64_t lddgu,
+                                const uint16_t *gu, int64_t ldgu, int32_t M, int32_t F, int32_t K, void *stream);
 /* Weight-gradient form: C[M,N] fp32 = At^T . Bt with At [K, M] bf16 (lda) and Bt [K, N] bf16 (ldb), both
  * token-major as the other kernels leave them (dW = dY^T X); accumulate != 0 adds to the existing C.
  * Requires K % 64 == 0, M % 8 == 0, N % 8 == 0: MT_ERR_UNSUPPORTED otherwise (transpose and use mt_k_gemm_nt). */

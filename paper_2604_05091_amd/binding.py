@@ -122,6 +122,8 @@ def lib():
                                  c_float, c_void_p], c_int32),
         "mt_k_gemm_nt_swiglu": ([p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, c_int32, c_int32, c_int32, c_void_p],
                                 c_int32),
+        "mt_k_gemm_nt_swiglu_bwd": ([p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, c_int32, c_int32, c_int32,
+                                     c_void_p], c_int32),
         "mt_k_gemm_tn": ([p16, c_int64, p16, c_int64, pf, c_int64, c_int32, c_int32, c_int32, c_int32, c_void_p], c_int32),
         "mt_k_bias_grad_ws_bytes": ([c_int32], c_size_t),
         "mt_k_bias_grad": ([pf, p16, c_int64, c_int64, c_int32, c_void_p, c_void_p], c_int32),

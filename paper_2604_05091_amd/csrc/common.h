@@ -26,6 +26,13 @@ __device__ __forceinline__ uint32_t pack2bf(float a, float b) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 __device__ __forceinline__ bf16_t f2bf(float a) { return __builtin_bit_cast(bf16_t, (__bf16)a); }
+// SwiGLU backward of one element: s = silu(g) * u, ds given -> dg, du (shared by the stand-alone kernel and the
+// GEMM store that applies it, so both round alike)
+__device__ __forceinline__ void swiglu_bwd_elem(float d, float g, float u, float *dg, float *du) {
+    const float sg = 1.0f / (1.0f + __expf(-g));
+    *dg = d * u * sg * (1.0f + g * (1.0f - sg));
+    *du = d * g * sg;
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -90,6 +97,10 @@ struct GemmArgs {
     // C may then be NULL (gate | up themselves are not stored).
     int32_t glu_F = 0;
     bf16_t *glu_out = nullptr; int64_t ld_glu = 0;
+    // optional SwiGLU backward fused into the store (gemm_nt only, see gemm_nt_fuses_glu_bwd): the product is
+    // ds [M, N] (N = F, the gradient of the activation, rounded to bf16 as a stored ds would be); with the forward's
+    // gate | up in glu_bwd_gu [M, 2N] the kernel stores C [M, 2N] = dgate | dup instead of ds
+    const bf16_t *glu_bwd_gu = nullptr; int64_t ld_glu_bwd = 0;
 };
 hipError_t gemm_nt(const GemmArgs &g, hipStream_t s);
 // true when gemm_nt would apply g.rope_* in its epilogue for this problem (large grid, K % 64 == 0, head-aligned
@@ -97,6 +108,8 @@ hipError_t gemm_nt(const GemmArgs &g, hipStream_t s);
 bool gemm_nt_fuses_rope(const GemmArgs &g);
 // the same for g.glu_*: large grid, K % 64 == 0, glu_F % 128 == 0, bf16 output without residual or bias
 bool gemm_nt_fuses_glu(const GemmArgs &g);
+// and for g.glu_bwd_*: large grid, K % 64 == 0, N % 8 == 0, bf16 output without residual or bias
+bool gemm_nt_fuses_glu_bwd(const GemmArgs &g);
 // C[M,N] = A^T . B with A given as [K, M] and B as [K, N] (lda, ldb their row pitches): the weight-gradient
 // form dW = dY^T X taken straight from token-major activations.  fp32 output (accumulate optional);
 // needs K % 64 == 0, M % 8 == 0, N % 8 == 0; returns hipErrorNotSupported otherwise (callers then transpose

@@ -272,11 +272,7 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(bf16_t *dgu, const bf16
     unpack8(*reinterpret_cast<const uint4 *>(gu + row * 2 * F + F + c), u);
     unpack8(*reinterpret_cast<const uint4 *>(ds + row * F + c), d);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const float sg = sigmoidf_(g[k]);
-        og[k] = d[k] * u[k] * sg * (1.0f + g[k] * (1.0f - sg));
-        ou[k] = d[k] * g[k] * sg;
-    }
+    for (int k = 0; k < 8; ++k) swiglu_bwd_elem(d[k], g[k], u[k], &og[k], &ou[k]);
     *reinterpret_cast<uint4 *>(dgu + row * 2 * F + c) = pack8(og);
     *reinterpret_cast<uint4 *>(dgu + row * 2 * F + F + c) = pack8(ou);
 }

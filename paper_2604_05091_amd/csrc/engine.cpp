@@ -466,8 +466,22 @@ mt_status layer_backward(mt_handle *h, const LayerW &w, float *G, const uint16_t
             if (st != MT_OK) return st;
         }
         WG(weight_grad(h, gyc, D.d, h->sact, D.F, G + o.wd, D.d, D.F, m, acc));
-        KCHK(gemm(h, gyc, D.d, h->wT, D.d, h->dsact, D.F, m, D.F, D.d));
-        KCHK(swiglu_bwd(h->dgu, h->dsact, h->gu, m, D.F, s));
+        {
+            // ds = gy Wd, then the SwiGLU backward: in the GEMM's store where that kernel supports it
+            GemmArgs g;
+            g.A = gyc; g.lda = D.d; g.B = h->wT; g.ldb = D.d; g.C = h->dgu; g.ldc = 2 * D.F; g.R = nullptr; g.ldr = 0;
+            g.M = (int32_t)m; g.N = D.F; g.K = D.d;
+            g.out_fp32 = 0; g.accumulate = 0;
+            g.glu_bwd_gu = h->gu; g.ld_glu_bwd = 2 * D.F;
+            if (gemm_nt_fuses_glu_bwd(g)) {
+                const double M = (double)m, N = (double)D.F, K = (double)D.d;
+                Timed t(h, CLS_GEMM, 2.0 * M * N * K, 2.0 * (M * K + N * K) + 8.0 * M * N);
+                KCHK(gemm_nt(g, s));
+            } else {
+                KCHK(gemm(h, gyc, D.d, h->wT, D.d, h->dsact, D.F, m, D.F, D.d));
+                KCHK(swiglu_bwd(h->dgu, h->dsact, h->gu, m, D.F, s));
+            }
+        }
         WG(weight_grad(h, h->dgu, 2 * D.F, h->yn, D.d, G + o.wgu, 2 * D.F, D.d, m, acc));
         KCHK(gemm(h, h->dgu, 2 * D.F, h->wT2, 2 * D.F, h->dyn, D.d, m, D.d, 2 * D.F));
         KCHK(rmsnorm_bwd(h->dh1 + r0 * D.d, G + o.g2, h->dyn, h1c, w.g2, gyc, h->norm_ws, m, D.d, h->cfg.rms_eps, s, acc));

@@ -466,9 +466,57 @@ __device__ __forceinline__ void w4_store_glu(const GemmArgs &g, const f32x16 (&a
     w4_flush_rows<64>(g.glu_out, g.ld_glu, g.M, m0 + wm * 128, col_w, region, hl * 32 + l32);
 }
 
+// SwiGLU backward store (g.glu_bwd_*): the accumulators are ds; they go to the wave's LDS region as bf16, and the
+// row-wise second half reads 8 consecutive ds per lane, loads the forward's gate and up of the same elements
+// (16 bytes each) and stores dgate and dup, all as whole lines.  Rows >= M and column chunks >= N are skipped.
+__device__ __forceinline__ void w4_store_glu_bwd(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int n0, int wm,
+                                                 int wn, int l32, int hl, bf16_t *smem) {
+    const int lane = hl * 32 + l32;
+    bf16_t *region = w4_ep_region(smem, wm * 2 + wn);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        bf16_t *lp = region + (i * 32 + l32) * W4_EP_PITCH + hl * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint2 u;
+                u.x = pack2bf(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+                u.y = pack2bf(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                *reinterpret_cast<uint2 *>(lp + j * 32 + q * 8) = u;
+            }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    const int lr = lane >> 4, lc = (lane & 15) * 8;
+    const int col = n0 + wn * 128 + lc;
+    if (col >= g.N) return;
+    bf16_t *C = reinterpret_cast<bf16_t *>(g.C);
+#pragma unroll 4
+    for (int it = 0; it < 32; ++it) {
+        const int r = it * 4 + lr;
+        const int64_t row = m0 + wm * 128 + r;
+        if (row >= g.M) continue;
+        const uint4 dv = *reinterpret_cast<const uint4 *>(region + r * W4_EP_PITCH + lc);
+        const uint4 gv = *reinterpret_cast<const uint4 *>(g.glu_bwd_gu + row * g.ld_glu_bwd + col);
+        const uint4 uv = *reinterpret_cast<const uint4 *>(g.glu_bwd_gu + row * g.ld_glu_bwd + g.N + col);
+        const uint32_t dw[4] = {dv.x, dv.y, dv.z, dv.w}, gw[4] = {gv.x, gv.y, gv.z, gv.w}, uw[4] = {uv.x, uv.y, uv.z, uv.w};
+        uint32_t og[4], ou[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float a0, b0, a1, b1;
+            swiglu_bwd_elem(bflo(dw[k]), bflo(gw[k]), bflo(uw[k]), &a0, &b0);
+            swiglu_bwd_elem(bfhi(dw[k]), bfhi(gw[k]), bfhi(uw[k]), &a1, &b1);
+            og[k] = pack2bf(a0, a1);
+            ou[k] = pack2bf(b0, b1);
+        }
+        *reinterpret_cast<uint4 *>(C + row * g.ldc + col) = uint4{og[0], og[1], og[2], og[3]};
+        *reinterpret_cast<uint4 *>(C + row * g.ldc + g.N + col) = uint4{ou[0], ou[1], ou[2], ou[3]};
+    }
+}
+
 // The epilogue is a template parameter: one kernel that carries all of them keeps so much guarded store code alive
 // that the compiler moves accumulators through scratch memory on the way out (measured: 13-16 us per tile).
-enum { EPI_GENERAL = 0, EPI_FULL_BF16 = 1, EPI_FULL_F32 = 2, EPI_ROPE = 3, EPI_GLU = 4 };
+enum { EPI_GENERAL = 0, EPI_FULL_BF16 = 1, EPI_FULL_F32 = 2, EPI_ROPE = 3, EPI_GLU = 4, EPI_GLU_BWD = 5 };
 template <int EPI>
 __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles_m, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
@@ -617,6 +665,7 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
 
     if constexpr (EPI == EPI_GLU) w4_store_glu(g, acc, m0, tn, wm, wn, l32, hl, smem);
     else if constexpr (EPI == EPI_ROPE) w4_store_rope(g, acc, m0, n0, wm, wn, l32, hl, smem);
+    else if constexpr (EPI == EPI_GLU_BWD) w4_store_glu_bwd(g, acc, m0, n0, wm, wn, l32, hl, smem);
     else if constexpr (EPI == EPI_FULL_BF16) w4_store_full_bf16(g, acc, m0, n0, wm, wn, l32, hl, smem);
     else if constexpr (EPI == EPI_FULL_F32) w4_store_full_f32(g, acc, m0, n0, wm, wn, l32, hl);
     else w4_store(g, acc, m0, n0, wm, wn, l32, hl);
@@ -641,6 +690,7 @@ hipError_t launch_w4_epi(const GemmArgs &g, hipStream_t s) {
 hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
     if (g.glu_F > 0) return launch_w4_epi<EPI_GLU>(g, s);
     if (g.rope_cos) return launch_w4_epi<EPI_ROPE>(g, s);
+    if (g.glu_bwd_gu) return launch_w4_epi<EPI_GLU_BWD>(g, s);
     // every tile complete and every access of the store aligned: the unguarded vector stores
     const bool full = g.M % W4_BM == 0 && g.N % W4_BN == 0 && !(g.ldc & 7) && !((uintptr_t)g.C & 15) &&
                       (!g.R || (!(g.ldr & 3) && !((uintptr_t)g.R & 7))) && !((uintptr_t)g.bias & 7);
@@ -843,8 +893,16 @@ bool gemm_nt_fuses_glu(const GemmArgs &g) {
            (int64_t)g.N * g.ldb < ((int64_t)1 << 31);
 }
 
+bool gemm_nt_fuses_glu_bwd(const GemmArgs &g) {
+    return g.M > 0 && g.N > 0 && g.K > 0 && (g.N & 7) == 0 && takes_w4(g) && !g.out_fp32 && !g.R && !g.bias && !g.rope_cos &&
+           !g.rope_sin && !g.glu_F && !g.glu_out && g.glu_bwd_gu && g.C && !(g.ldc & 7) && g.ldc >= 2 * (int64_t)g.N &&
+           !((uintptr_t)g.C & 15) && !(g.ld_glu_bwd & 7) && g.ld_glu_bwd >= 2 * (int64_t)g.N &&
+           !((uintptr_t)g.glu_bwd_gu & 15);
+}
+
 hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
+    if (g.glu_bwd_gu && !gemm_nt_fuses_glu_bwd(g)) return hipErrorNotSupported;
     if ((g.rope_cos || g.rope_sin) && !gemm_nt_fuses_rope(g)) return hipErrorNotSupported;
     if ((g.glu_F || g.glu_out) && !gemm_nt_fuses_glu(g)) return hipErrorNotSupported;
     if (!g.C && !g.glu_F) return hipErrorInvalidValue;
@@ -870,7 +928,7 @@ hipError_t gemm_tn(const GemmArgs &g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
     if ((g.lda & 7) || (g.ldb & 7) || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
     if (g.lda < g.M || g.ldb < g.N || g.ldc < g.N || !g.out_fp32 || g.R || g.bias || g.rope_cos || g.rope_sin || g.glu_F ||
-        g.glu_out)
+        g.glu_out || g.glu_bwd_gu)
         return hipErrorInvalidValue;
     if ((g.K % BK) || (g.M & 7) || (g.N & 7)) return hipErrorNotSupported;
     return launch_tn(g, s);

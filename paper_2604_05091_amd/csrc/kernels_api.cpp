@@ -66,6 +66,18 @@ int32_t mt_k_gemm_nt_swiglu(const uint16_t *A, int64_t lda, const uint16_t *W, i
     return to_status(e);
 }
 
+int32_t mt_k_gemm_nt_swiglu_bwd(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, uint16_t *dgu, int64_t lddgu,
+                                const uint16_t *gu, int64_t ldgu, int32_t M, int32_t F, int32_t K, void *stream) {
+    if (!A || !B || !dgu || !gu || F <= 0) return MT_ERR_INVALID_ARG;
+    GemmArgs g;
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = dgu; g.ldc = lddgu; g.R = nullptr; g.ldr = 0;
+    g.M = M; g.N = F; g.K = K; g.out_fp32 = 0; g.accumulate = 0;
+    g.glu_bwd_gu = gu; g.ld_glu_bwd = ldgu;
+    const hipError_t e = gemm_nt(g, S(stream));
+    if (e == hipErrorNotSupported) return MT_ERR_UNSUPPORTED;
+    return to_status(e);
+}
+
 int32_t mt_k_gemm_tn(const uint16_t *At, int64_t lda, const uint16_t *Bt, int64_t ldb, float *C, int64_t ldc, int32_t M,
                      int32_t N, int32_t K, int32_t accumulate, void *stream) {
     if (!At || !Bt || !C) return MT_ERR_INVALID_ARG;

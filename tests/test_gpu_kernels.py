@@ -274,6 +274,29 @@ def test_gemm_with_swiglu_in_the_store(orc64, M, F, K, keep_gu):
     assert L.mt_k_gemm_nt_swiglu(A.data_ptr(), K, W.data_ptr(), K, None, 0, S.data_ptr(), F - 64, M, F - 64, K, None) == -2
 
 
+@pytest.mark.parametrize("M,F,K", [(3300, 4096, 128), (12800, 1000, 64)])
+def test_gemm_with_swiglu_backward_in_the_store(orc64, M, F, K):
+    """ds = A B^T followed by the SwiGLU backward inside the GEMM's store: dgate | dup equal the oracle's and are
+    bit-identical to the two-kernel route.  Ragged last row tile and a ragged last column tile (F = 1000)."""
+    rng = np.random.default_rng(M + F + K)
+    a, w = bf16_round(rng.standard_normal((M, K))), bf16_round(rng.standard_normal((F, K)) * 0.3)
+    gu = bf16_round(rng.standard_normal((M, 2 * F)))
+    ds = bf16_round(orc64.linear_fwd(a, w))
+    dg_ref, du_ref = orc64.swiglu_bwd(ds, np.ascontiguousarray(gu[:, :F]), np.ascontiguousarray(gu[:, F:]))
+    A, W, GU = dev_bf16(a), dev_bf16(w), dev_bf16(gu)
+    DGU = torch.full((M, 2 * F), 3.0, dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_gemm_nt_swiglu_bwd(A.data_ptr(), K, W.data_ptr(), K, DGU.data_ptr(), 2 * F, GU.data_ptr(), 2 * F, M, F, K, None))
+    got = host(DGU)
+    assert rel_l2(got[:, :F], dg_ref) < 2 * BF16_TOL and rel_l2(got[:, F:], du_ref) < 2 * BF16_TOL
+    DS = torch.zeros((M, F), dtype=torch.bfloat16, device="cuda")
+    DGU2 = torch.zeros((M, 2 * F), dtype=torch.bfloat16, device="cuda")
+    ok(L.mt_k_gemm_nt(A.data_ptr(), K, W.data_ptr(), K, DS.data_ptr(), F, None, 0, M, F, K, 0, 0, None))
+    ok(L.mt_k_swiglu_bwd(DGU2.data_ptr(), DS.data_ptr(), GU.data_ptr(), M, F, None))
+    assert torch.equal(DGU, DGU2)
+    assert L.mt_k_gemm_nt_swiglu_bwd(A.data_ptr(), K, W.data_ptr(), K, DGU.data_ptr(), 2 * F, GU.data_ptr(), 2 * F, 256, F, K,
+                                     None) == -2
+
+
 # ----------------------------------------------------------------------------- SwiGLU
 def test_swiglu_forward_backward(orc64):
     rng = np.random.default_rng(6)
