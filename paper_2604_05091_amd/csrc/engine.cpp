@@ -395,17 +395,16 @@ mt_status mlp_forward_rows(mt_handle *h, const LayerW &w, const uint16_t *h1, in
     hipStream_t s = h->s_comp;
     KCHK(rmsnorm_fwd(h->yn, h1, w.g2, m, D.d, h->cfg.rms_eps, s));
     GemmArgs g;
-    g.A = h->yn; g.lda = D.d; g.B = w.wgu; g.ldb = D.d; g.C = nullptr; g.ldc = 2 * D.F;
+    g.A = h->yn; g.lda = D.d; g.B = w.wgu; g.ldb = D.d; g.C = keep_gu ? h->gu : nullptr; g.ldc = 2 * D.F;
     g.R = nullptr; g.ldr = 0;
     g.M = (int32_t)m; g.N = 2 * D.F; g.K = D.d;
     g.out_fp32 = 0; g.accumulate = 0;
     g.glu_F = D.F; g.glu_out = h->sact; g.ld_glu = D.F;
-    // Measured on the 7B shape: with only the activation stored the fused launch costs what the plain GEMM does
-    // (9.9 ms, the 0.7 ms SwiGLU pass is gone); storing gate|up as well makes it slower than the two kernels
-    // (11.4 against 10.6 ms), so the recomputation pass keeps the separate kernel.
-    if (!keep_gu && gemm_nt_fuses_glu(g)) {
+    // Measured on the 7B shape: plain GEMM 9.6 ms, GEMM + SwiGLU kernel 10.35 ms, fused with the activation only
+    // 9.55 ms, fused with gate | up stored as well (what the backward reads) 9.8 ms.
+    if (gemm_nt_fuses_glu(g)) {
         const double M = (double)m, N = 2.0 * D.F, K = (double)D.d;
-        Timed t(h, CLS_GEMM, 2.0 * M * N * K, 2.0 * (M * K + N * K) + M * N);
+        Timed t(h, CLS_GEMM, 2.0 * M * N * K, 2.0 * (M * K + N * K) + (keep_gu ? 3.0 : 1.0) * M * N);
         KCHK(gemm_nt(g, s));
         return MT_OK;
     }

@@ -428,42 +428,52 @@ __device__ __forceinline__ void w4_store_rope(const GemmArgs &g, const f32x16 (&
 }
 
 // SwiGLU store (g.glu_*): the tile's 256 B rows are gate columns c .. c+63, up columns c .. c+63, gate c+64 ..,
-// up c+64 .. with c = 128 tn, so a wave holds gate (blocks 0, 1) and up (blocks 2, 3) of the same 64 columns and a
-// lane both values of every element it owns.  Rows are guarded; columns are complete (glu_F % 128 == 0).
+// up c+64 .. with c = 128 tn, so a wave holds gate (blocks 0, 1) and up (blocks 2, 3) of the same 64 columns.
+// Both go through the wave's LDS region; the row-wise second half computes the activation and stores it (and
+// gate | up if asked for) as whole lines.  Rows are guarded; columns are complete (glu_F % 128 == 0).
 __device__ __forceinline__ void w4_store_glu(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int tn, int wm, int wn,
                                              int l32, int hl, bf16_t *smem) {
-    const int row_l = m0 + wm * 128 + l32, col_w = tn * 128 + wn * 64;
-    bf16_t *cw = reinterpret_cast<bf16_t *>(g.C);
+    const int lane = hl * 32 + l32;
     bf16_t *region = w4_ep_region(smem, wm * 2 + wn);
+    // first half: gate (blocks 0, 1) to columns 0..63 of the wave's LDS region, up (blocks 2, 3) to 64..127
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int row = row_l + i * 32;
         bf16_t *lp = region + (i * 32 + l32) * W4_EP_PITCH + hl * 4;
 #pragma unroll
-        for (int jp = 0; jp < 2; ++jp)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int o = jp * 32 + q * 8;
-                uint2 pg, pu, ps;
-                pg.x = pack2bf(acc[i][jp][4 * q], acc[i][jp][4 * q + 1]);
-                pg.y = pack2bf(acc[i][jp][4 * q + 2], acc[i][jp][4 * q + 3]);
-                pu.x = pack2bf(acc[i][jp + 2][4 * q], acc[i][jp + 2][4 * q + 1]);
-                pu.y = pack2bf(acc[i][jp + 2][4 * q + 2], acc[i][jp + 2][4 * q + 3]);
-                if (cw && row < g.M) {   // gate | up themselves: straight from the accumulator layout
-                    *reinterpret_cast<uint2 *>(cw + (int64_t)row * g.ldc + col_w + hl * 4 + o) = pg;
-                    *reinterpret_cast<uint2 *>(cw + (int64_t)row * g.ldc + g.glu_F + col_w + hl * 4 + o) = pu;
-                }
-                const float gv[4] = {bflo(pg.x), bfhi(pg.x), bflo(pg.y), bfhi(pg.y)};
-                const float uv[4] = {bflo(pu.x), bfhi(pu.x), bflo(pu.y), bfhi(pu.y)};
-                float sv[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) sv[e] = gv[e] * (1.0f / (1.0f + __expf(-gv[e]))) * uv[e];
-                ps.x = pack2bf(sv[0], sv[1]);
-                ps.y = pack2bf(sv[2], sv[3]);
-                *reinterpret_cast<uint2 *>(lp + o) = ps;
+                uint2 u;
+                u.x = pack2bf(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+                u.y = pack2bf(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                *reinterpret_cast<uint2 *>(lp + j * 32 + q * 8) = u;
             }
     }
-    w4_flush_rows<64>(g.glu_out, g.ld_glu, g.M, m0 + wm * 128, col_w, region, hl * 32 + l32);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    // second half, row-wise: a lane takes 8 consecutive columns of a row, 8 rows per pass
+    const int lr = lane >> 3, lc = (lane & 7) * 8;
+    const int col = tn * 128 + wn * 64 + lc;
+    bf16_t *cw = reinterpret_cast<bf16_t *>(g.C);
+#pragma unroll 4
+    for (int it = 0; it < 16; ++it) {
+        const int r = it * 8 + lr;
+        const int64_t row = m0 + wm * 128 + r;
+        if (row >= g.M) continue;
+        const uint4 gv = *reinterpret_cast<const uint4 *>(region + r * W4_EP_PITCH + lc);
+        const uint4 uv = *reinterpret_cast<const uint4 *>(region + r * W4_EP_PITCH + 64 + lc);
+        if (cw) {
+            *reinterpret_cast<uint4 *>(cw + row * g.ldc + col) = gv;
+            *reinterpret_cast<uint4 *>(cw + row * g.ldc + g.glu_F + col) = uv;
+        }
+        const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w}, uw[4] = {uv.x, uv.y, uv.z, uv.w};
+        uint32_t sw[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float g0 = bflo(gw[k]), g1 = bfhi(gw[k]);
+            sw[k] = pack2bf(g0 * (1.0f / (1.0f + __expf(-g0))) * bflo(uw[k]), g1 * (1.0f / (1.0f + __expf(-g1))) * bfhi(uw[k]));
+        }
+        *reinterpret_cast<uint4 *>(g.glu_out + row * g.ld_glu + col) = uint4{sw[0], sw[1], sw[2], sw[3]};
+    }
 }
 
 // SwiGLU backward store (g.glu_bwd_*): the accumulators are ds; they go to the wave's LDS region as bf16, and the
@@ -889,7 +899,7 @@ bool gemm_nt_fuses_rope(const GemmArgs &g) {
 bool gemm_nt_fuses_glu(const GemmArgs &g) {
     return g.M > 0 && g.K > 0 && g.glu_F > 0 && g.N == 2 * g.glu_F && (g.glu_F % 128) == 0 && takes_w4(g) && !g.out_fp32 &&
            !g.R && !g.bias && !g.rope_cos && !g.rope_sin && g.glu_out && !(g.ld_glu & 7) && g.ld_glu >= g.glu_F &&
-           !((uintptr_t)g.glu_out & 15) && (!g.C || (!(g.ldc & 3) && !((uintptr_t)g.C & 7))) &&
+           !((uintptr_t)g.glu_out & 15) && (!g.C || (!(g.ldc & 7) && !((uintptr_t)g.C & 15))) &&
            (int64_t)g.N * g.ldb < ((int64_t)1 << 31);
 }
 
