@@ -149,6 +149,40 @@ __device__ __forceinline__ void store_owned_rows_unrotated(bf16_t *out_row, cons
         }
 }
 
+// Results leave through LDS: stored from the accumulator layout (a lane owns a row) one store instruction would
+// touch 64 rows with 8 bytes each.  Every wave writes its 32 x HD block into a private LDS region (free after the
+// main loop's last barrier) with the two functions above and copies it out row-wise, 16 bytes per lane, whole lines.
+// Falls back to the direct stores when the destination rows are not 16-byte aligned.
+template <int HD>
+__device__ __forceinline__ bf16_t *out_region(bf16_t *smem, int wave) { return smem + wave * 32 * (HD + 8); }
+
+template <int HD>
+__device__ __forceinline__ void flush_owned_rows(bf16_t *out_row0, int64_t ld, const bf16_t *region, int lane, int n_valid) {
+    constexpr int LPR = HD / 8, RPI = 64 / LPR;
+    const int lr = lane / LPR, lc = (lane % LPR) * 8;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int it = 0; it < 32 / RPI; ++it) {
+        const int r = it * RPI + lr;
+        if (r < n_valid)
+            *reinterpret_cast<uint4 *>(out_row0 + r * ld + lc) = *reinterpret_cast<const uint4 *>(region + r * (HD + 8) + lc);
+    }
+}
+
+// out_row0: row of the wave's first query / key; cs, sn: rotary tables at that row, or NULL
+template <int HD>
+__device__ __forceinline__ void write_owned_rows(bf16_t *out_row0, int64_t ld, const f32x16 *acc, float mul, int l32, int hl,
+                                                 int n_valid, const float *cs, const float *sn, bf16_t *region) {
+    const bool wide = !(ld & 7) && !((uintptr_t)out_row0 & 15);
+    bf16_t *dst = wide ? region + l32 * (HD + 8) : out_row0 + l32 * ld;
+    if (wide || l32 < n_valid) {
+        const int tr = min(l32, n_valid - 1);  // rows past the end are never stored; keep their table reads in range
+        if (cs) store_owned_rows_unrotated<HD>(dst, acc, mul, hl, cs + tr * (HD / 2), sn + tr * (HD / 2));
+        else store_owned_rows<HD>(dst, acc, mul, hl);
+    }
+    if (wide) flush_owned_rows<HD>(out_row0, ld, region, hl * 32 + l32, n_valid);
+}
+
 // acc[hb] += X^T (columns hb*32.. of the natural tile X, reduction rows rb*32 + cch*16 ..) * frag, for all hb
 template <int HD, int LDP>
 __device__ __forceinline__ void mfma_tr_accumulate(f32x16 *acc, const bf16_t *tile, int tr_off, int rb, int cch,
@@ -339,10 +373,10 @@ __global__ __launch_bounds__(64 * NW) void flash_fwd_kernel(AttnArgs a) {
         __syncthreads();
     }
     lsum += __shfl_xor(lsum, 32, 64);
-    if (qok) {
-        store_owned_rows<HD>(a.o + ((int64_t)b * T + q) * a.ldo + (int64_t)h * HD, oacc, 1.0f / lsum, hl);
-        if (hl == 0) a.lse[((int64_t)b * a.Hq + h) * T + q] = (m * c + __builtin_amdgcn_logf(lsum)) * kLn2;
-    }
+    if (q0 < T)
+        write_owned_rows<HD>(a.o + ((int64_t)b * T + q0) * a.ldo + (int64_t)h * HD, a.ldo, oacc, 1.0f / lsum, l32, hl,
+                             min(32, T - q0), nullptr, nullptr, out_region<HD>(smem, wave));
+    if (qok && hl == 0) a.lse[((int64_t)b * a.Hq + h) * T + q] = (m * c + __builtin_amdgcn_logf(lsum)) * kLn2;
 }
 
 // ------------------------------------------------------------------ backward: dQ
@@ -449,14 +483,10 @@ __global__ __launch_bounds__(64 * NW) void flash_bwd_dq_kernel(AttnArgs a) {
         }
         __syncthreads();
     }
-    if (qok) {
-        bf16_t *dqrow = a.dq + ((int64_t)b * T + q) * a.lddq + (int64_t)h * HD;
-        if (a.rope_cos)
-            store_owned_rows_unrotated<HD>(dqrow, dqacc, a.scale, hl, a.rope_cos + (int64_t)q * (HD / 2),
-                                           a.rope_sin + (int64_t)q * (HD / 2));
-        else
-            store_owned_rows<HD>(dqrow, dqacc, a.scale, hl);
-    }
+    if (q0 < T)
+        write_owned_rows<HD>(a.dq + ((int64_t)b * T + q0) * a.lddq + (int64_t)h * HD, a.lddq, dqacc, a.scale, l32, hl,
+                             min(32, T - q0), a.rope_cos ? a.rope_cos + (int64_t)q0 * (HD / 2) : nullptr,
+                             a.rope_cos ? a.rope_sin + (int64_t)q0 * (HD / 2) : nullptr, out_region<HD>(smem, wave));
 }
 
 // ------------------------------------------------------------------ backward: dK, dV, software-pipelined
@@ -644,14 +674,13 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
         tq_j1 = tq_j1 + 1 == n_qt ? 0 : tq_j1 + 1;
     }
 #undef DKDV_SLOT
-    if (kvok) {
-        bf16_t *dkrow = a.dk + ((int64_t)b * T + kv) * a.lddk + (int64_t)hk * HD;
-        if (a.rope_cos)
-            store_owned_rows_unrotated<HD>(dkrow, dkacc, a.scale, hl, a.rope_cos + (int64_t)kv * (HD / 2),
-                                           a.rope_sin + (int64_t)kv * (HD / 2));
-        else
-            store_owned_rows<HD>(dkrow, dkacc, a.scale, hl);
-        store_owned_rows<HD>(a.dv + ((int64_t)b * T + kv) * a.lddv + (int64_t)hk * HD, dvacc, 1.0f, hl);
+    if (kv0w < T) {
+        const int n_valid = min(32, T - kv0w);
+        write_owned_rows<HD>(a.dk + ((int64_t)b * T + kv0w) * a.lddk + (int64_t)hk * HD, a.lddk, dkacc, a.scale, l32, hl,
+                             n_valid, a.rope_cos ? a.rope_cos + (int64_t)kv0w * (HD / 2) : nullptr,
+                             a.rope_cos ? a.rope_sin + (int64_t)kv0w * (HD / 2) : nullptr, out_region<HD>(smem, wave));
+        write_owned_rows<HD>(a.dv + ((int64_t)b * T + kv0w) * a.lddv + (int64_t)hk * HD, a.lddv, dvacc, 1.0f, l32, hl,
+                             n_valid, nullptr, nullptr, out_region<HD>(smem, wave));
     }
 }
 
