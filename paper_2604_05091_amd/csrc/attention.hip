@@ -524,12 +524,6 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
     const int kv0w = kvb * 128 + wave * 32, kv = kv0w + l32;
     const bool kvok = kv < T;
 
-    // zero the three stages: the pipeline's first and last slots read tiles that were never written
-    {
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        for (int i = threadIdx.x; i < 3 * STAGE / 8; i += 256) reinterpret_cast<u32x4 *>(smem)[i] = z;
-    }
-
     bf16x8 kf[KS], vf[KS];
     {
         const int kvc = kvok ? kv : T - 1;
@@ -564,35 +558,45 @@ __global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
     float stat = 0.f;
     // tiles are fetched in order; (f_head, f_tile) is the next one: query head of the group, query tile
     int f_head = 0, f_tile = 0;
-    auto fetch_next = [&]() {
+    using Stage = TileStage<64, HD, LDK, 256>;
+    auto fetch_into = [&](Stage &sq, Stage &sdo, float &st) {
         const int h = hk * G + f_head, q0t = (qt_first + f_tile) * 64;
         if (++f_tile == n_qt) {
             f_tile = 0;
             ++f_head;
         }
-        stQ.fetch_clamped(a.q + ((int64_t)b * T + q0t) * a.ldq + (int64_t)h * HD, a.ldq, T - q0t);
-        stDO.fetch_clamped(a.dout + ((int64_t)b * T + q0t) * a.lddo + (int64_t)h * HD, a.lddo, T - q0t);
+        sq.fetch_clamped(a.q + ((int64_t)b * T + q0t) * a.ldq + (int64_t)h * HD, a.ldq, T - q0t);
+        sdo.fetch_clamped(a.dout + ((int64_t)b * T + q0t) * a.lddo + (int64_t)h * HD, a.lddo, T - q0t);
         if (threadIdx.x < 128) {
             const int qq = q0t + (threadIdx.x & 63);
             const int64_t si = ((int64_t)b * a.Hq + h) * T + (qq < T ? qq : T - 1);
             // queries past T: lse = +inf makes their P (and with it dS) exactly zero
-            stat = threadIdx.x < 64 ? (qq < T ? a.lse[si] * kLog2e : INFINITY) : a.delta[si];
+            st = threadIdx.x < 64 ? (qq < T ? a.lse[si] * kLog2e : INFINITY) : a.delta[si];
         }
     };
-    auto commit = [&](int stage) {
-        bf16_t *st = smem + stage * STAGE;
-        stQ.commit_plain(st);
-        stDO.commit_plain(st + 64 * LDK);
-        if (threadIdx.x < 128) reinterpret_cast<float *>(st + STAGE_BF)[threadIdx.x] = stat;
+    auto commit_from = [&](int stage, Stage &sq, Stage &sdo, float st) {
+        bf16_t *sp = smem + stage * STAGE;
+        sq.commit_plain(sp);
+        sdo.commit_plain(sp + 64 * LDK);
+        if (threadIdx.x < 128) reinterpret_cast<float *>(sp + STAGE_BF)[threadIdx.x] = st;
     };
-    __syncthreads();  // zeros in place before the first tiles land
-    if (total > 0) {
-        fetch_next();
-        commit(0);
-    }
-    if (total > 1) {
-        fetch_next();
-        commit(1);
+    auto fetch_next = [&]() { fetch_into(stQ, stDO, stat); };
+    auto commit = [&](int stage) { commit_from(stage, stQ, stDO, stat); };
+    // prologue: the first two tiles are requested together (a second set of staging registers exists only here),
+    // then the three stages are zeroed while they are on their way: the pipeline's first and last slots read tiles
+    // that were never written
+    {
+        Stage stQ2, stDO2;
+        float stat2 = 0.f;
+        if (total > 0) fetch_into(stQ, stDO, stat);
+        if (total > 1) fetch_into(stQ2, stDO2, stat2);
+        {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            for (int i = threadIdx.x; i < 3 * STAGE / 8; i += 256) reinterpret_cast<u32x4 *>(smem)[i] = z;
+        }
+        __syncthreads();  // zeros in place before the first tiles land
+        if (total > 0) commit_from(0, stQ, stDO, stat);
+        if (total > 1) commit_from(1, stQ2, stDO2, stat2);
     }
     if (total > 2) fetch_next();
     __syncthreads();
