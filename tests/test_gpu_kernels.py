@@ -357,7 +357,9 @@ def test_cross_entropy(orc64, n, V):
 
 
 # ----------------------------------------------------------------------------- attention
-def _attention_case(orc64, B, T, Hq, Hkv, hd, seed):
+def _attention_case(orc64, B, T, Hq, Hkv, hd, seed, out_pad=0):
+    """out_pad: extra elements in the row pitch of every output (4: rows are then only 8-byte aligned and the
+    kernels store straight from the accumulator layout instead of through LDS)."""
     rng = np.random.default_rng(seed)
     nq, nkv = Hq * hd, Hkv * hd
     ld = nq + 2 * nkv
@@ -366,11 +368,14 @@ def _attention_case(orc64, B, T, Hq, Hkv, hd, seed):
     scale = 1.0 / np.sqrt(hd)
     QKV = dev_bf16(qkv)
     pq, pk, pv = QKV.data_ptr(), QKV.data_ptr() + 2 * nq, QKV.data_ptr() + 2 * (nq + nkv)
-    O = torch.zeros((B * T, nq), dtype=torch.bfloat16, device="cuda")
+    ldo, ldd = nq + out_pad, ld + out_pad
+    Op = torch.zeros((B * T, ldo), dtype=torch.bfloat16, device="cuda")
     LSE = torch.zeros((B, Hq, T), dtype=torch.float32, device="cuda")
-    ok(L.mt_k_flash_fwd(O.data_ptr(), nq, LSE.data_ptr(), pq, ld, pk, ld, pv, ld, B, T, Hq, Hkv, hd, scale, None))
+    ok(L.mt_k_flash_fwd(Op.data_ptr(), ldo, LSE.data_ptr(), pq, ld, pk, ld, pv, ld, B, T, Hq, Hkv, hd, scale, None))
     a_ref = orc64.attention_fwd(q, k, v, B, T, Hq, Hkv, hd)
-    assert rel_l2(host(O), a_ref) < BF16_TOL
+    assert rel_l2(host(Op)[:, :nq], a_ref) < BF16_TOL
+    assert not host(Op)[:, nq:].any()
+    O = Op[:, :nq].contiguous()
     # log-sum-exp of the first and last row of head 0: lse_0 = s_00, lse_last from the definition
     lse = host(LSE)
     s00 = float(q[0, :hd].astype(np.float64) @ k[0, :hd].astype(np.float64)) * scale
@@ -380,21 +385,27 @@ def _attention_case(orc64, B, T, Hq, Hkv, hd, seed):
     dq_ref, dk_ref, dv_ref = orc64.attention_bwd(dout, q, k, v, B, T, Hq, Hkv, hd)
     DO = dev_bf16(dout)
     DELTA = torch.empty((B, Hq, T), dtype=torch.float32, device="cuda")
-    DQKV = torch.zeros((B * T, ld), dtype=torch.bfloat16, device="cuda")
+    DQKV = torch.zeros((B * T, ldd), dtype=torch.bfloat16, device="cuda")
     pdq, pdk, pdv = DQKV.data_ptr(), DQKV.data_ptr() + 2 * nq, DQKV.data_ptr() + 2 * (nq + nkv)
-    ok(L.mt_k_flash_bwd(pdq, ld, pdk, ld, pdv, ld, DO.data_ptr(), nq, pq, ld, pk, ld, pv, ld, O.data_ptr(), nq,
+    ok(L.mt_k_flash_bwd(pdq, ldd, pdk, ldd, pdv, ldd, DO.data_ptr(), nq, pq, ld, pk, ld, pv, ld, O.data_ptr(), nq,
                         LSE.data_ptr(), DELTA.data_ptr(), B, T, Hq, Hkv, hd, scale, None))
     got = host(DQKV)
+    assert not got[:, ld:].any()
     # the backward reads O and P in bf16, so its error is a few bf16 roundings deep
     assert rel_l2(got[:, :nq], dq_ref) < 2e-2 and cosine(got[:, :nq], dq_ref) > 0.9995
     assert rel_l2(got[:, nq:nq + nkv], dk_ref) < 2e-2 and cosine(got[:, nq:nq + nkv], dk_ref) > 0.9995
-    assert rel_l2(got[:, nq + nkv:], dv_ref) < 1e-2 and cosine(got[:, nq + nkv:], dv_ref) > 0.9995
+    assert rel_l2(got[:, nq + nkv:ld], dv_ref) < 1e-2 and cosine(got[:, nq + nkv:ld], dv_ref) > 0.9995
 
 
 @pytest.mark.parametrize("B,T,Hq,Hkv,hd", [(2, 128, 4, 4, 64), (1, 200, 4, 2, 64), (2, 72, 2, 2, 128),
                                            (1, 392, 5, 1, 128), (1, 8, 2, 1, 64)])
 def test_flash_attention_forward_backward(orc64, B, T, Hq, Hkv, hd):
     _attention_case(orc64, B, T, Hq, Hkv, hd, seed=T + hd)
+
+
+@pytest.mark.parametrize("B,T,Hq,Hkv,hd", [(1, 200, 4, 2, 64), (2, 72, 2, 2, 128)])
+def test_flash_attention_outputs_with_8_byte_aligned_rows(orc64, B, T, Hq, Hkv, hd):
+    _attention_case(orc64, B, T, Hq, Hkv, hd, seed=T + hd + 1, out_pad=4)
 
 
 @pytest.mark.parametrize("B,T,Hq,Hkv,hd", [(2, 136, 4, 2, 64), (1, 264, 3, 1, 128)])
