@@ -322,31 +322,41 @@ __device__ __forceinline__ void w4_store(const GemmArgs &g, const f32x16 (&acc)[
     }
 }
 
-// complete, aligned tiles (what the host checks before it picks the kernel instantiated with this store)
+// complete, aligned tiles (what the host checks before it picks the kernel instantiated with this store).  Bias
+// and residual are template parameters as well: tested per element at run time they turned every one of the 64
+// loads into a branch with its own wait.  Here a row block's 16 residual loads are in flight together.
+template <bool BIAS, bool RES>
 __device__ __forceinline__ void w4_store_full_bf16(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int n0, int wm,
                                                    int wn, int l32, int hl, bf16_t *smem) {
     const int wave = wm * 2 + wn, lane = hl * 32 + l32;
     bf16_t *region = w4_ep_region(smem, wave);
     const int col_l = n0 + wn * 128 + hl * 4;
-    const bf16_t *bias = g.bias ? g.bias + col_l : nullptr;
+    uint2 bv[16];
+    if constexpr (BIAS) {
+#pragma unroll
+        for (int jq = 0; jq < 16; ++jq) bv[jq] = *reinterpret_cast<const uint2 *>(g.bias + col_l + (jq >> 2) * 32 + (jq & 3) * 8);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         bf16_t *lp = region + (i * 32 + l32) * W4_EP_PITCH + hl * 4;
         // bias and residual are added in fp32, before the one rounding to bf16
-        const bf16_t *rp = g.R ? g.R + (int64_t)(m0 + wm * 128 + i * 32 + l32) * g.ldr + col_l : nullptr;
+        uint2 rv[16];
+        if constexpr (RES) {
+            const bf16_t *rp = g.R + (int64_t)(m0 + wm * 128 + i * 32 + l32) * g.ldr + col_l;
+#pragma unroll
+            for (int jq = 0; jq < 16; ++jq) rv[jq] = *reinterpret_cast<const uint2 *>(rp + (jq >> 2) * 32 + (jq & 3) * 8);
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int o = j * 32 + q * 8;
+                const int o = j * 32 + q * 8, jq = j * 4 + q;
                 float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
-                if (bias) {
-                    const uint2 bv = *reinterpret_cast<const uint2 *>(bias + o);
-                    v0 += bflo(bv.x); v1 += bfhi(bv.x); v2 += bflo(bv.y); v3 += bfhi(bv.y);
+                if constexpr (BIAS) {
+                    v0 += bflo(bv[jq].x); v1 += bfhi(bv[jq].x); v2 += bflo(bv[jq].y); v3 += bfhi(bv[jq].y);
                 }
-                if (rp) {
-                    const uint2 rv = *reinterpret_cast<const uint2 *>(rp + o);
-                    v0 += bflo(rv.x); v1 += bfhi(rv.x); v2 += bflo(rv.y); v3 += bfhi(rv.y);
+                if constexpr (RES) {
+                    v0 += bflo(rv[jq].x); v1 += bfhi(rv[jq].x); v2 += bflo(rv[jq].y); v3 += bfhi(rv[jq].y);
                 }
                 uint2 u;
                 u.x = pack2bf(v0, v1);
@@ -379,6 +389,7 @@ __device__ __forceinline__ void w4_store_full_f32(const GemmArgs &g, const f32x1
 // the lane holds both members (j, j + 64) of every pair of its rows: blocks j4 and j4 + 2 of acc.  Columns are
 // complete (N % 128 == 0, checked on the host); rows are guarded.  Heads at or beyond rope_cols (the value
 // projection) are stored unrotated.  Bias, if any, is added before the rotation.  The rows leave through LDS.
+template <bool BIAS>
 __device__ __forceinline__ void w4_store_rope(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int n0, int wm, int wn,
                                               int l32, int hl, bf16_t *smem) {
     const int row_l = m0 + wm * 128 + l32, col_w = n0 + wn * 128;
@@ -401,7 +412,7 @@ __device__ __forceinline__ void w4_store_rope(const GemmArgs &g, const f32x16 (&
                     a[e] = acc[i][jp][4 * q + e];
                     b[e] = acc[i][jp + 2][4 * q + e];
                 }
-                if (g.bias) {
+                if constexpr (BIAS) {
                     const uint2 ba = *reinterpret_cast<const uint2 *>(g.bias + col_w + jc);
                     const uint2 bb = *reinterpret_cast<const uint2 *>(g.bias + col_w + jc + 64);
                     a[0] += bflo(ba.x); a[1] += bfhi(ba.x); a[2] += bflo(ba.y); a[3] += bfhi(ba.y);
@@ -526,7 +537,8 @@ __device__ __forceinline__ void w4_store_glu_bwd(const GemmArgs &g, const f32x16
 
 // The epilogue is a template parameter: one kernel that carries all of them keeps so much guarded store code alive
 // that the compiler moves accumulators through scratch memory on the way out (measured: 13-16 us per tile).
-enum { EPI_GENERAL = 0, EPI_FULL_BF16 = 1, EPI_FULL_F32 = 2, EPI_ROPE = 3, EPI_GLU = 4, EPI_GLU_BWD = 5 };
+enum { EPI_GENERAL = 0, EPI_FULL_BF16 = 1, EPI_FULL_F32 = 2, EPI_ROPE = 3, EPI_GLU = 4, EPI_GLU_BWD = 5, EPI_FULL_BF16_RES = 6,
+       EPI_FULL_BF16_BIAS = 7, EPI_ROPE_BIAS = 8 };
 template <int EPI>
 __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles_m, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
@@ -674,9 +686,12 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
 #undef W4_STEP
 
     if constexpr (EPI == EPI_GLU) w4_store_glu(g, acc, m0, tn, wm, wn, l32, hl, smem);
-    else if constexpr (EPI == EPI_ROPE) w4_store_rope(g, acc, m0, n0, wm, wn, l32, hl, smem);
+    else if constexpr (EPI == EPI_ROPE) w4_store_rope<false>(g, acc, m0, n0, wm, wn, l32, hl, smem);
+    else if constexpr (EPI == EPI_ROPE_BIAS) w4_store_rope<true>(g, acc, m0, n0, wm, wn, l32, hl, smem);
     else if constexpr (EPI == EPI_GLU_BWD) w4_store_glu_bwd(g, acc, m0, n0, wm, wn, l32, hl, smem);
-    else if constexpr (EPI == EPI_FULL_BF16) w4_store_full_bf16(g, acc, m0, n0, wm, wn, l32, hl, smem);
+    else if constexpr (EPI == EPI_FULL_BF16) w4_store_full_bf16<false, false>(g, acc, m0, n0, wm, wn, l32, hl, smem);
+    else if constexpr (EPI == EPI_FULL_BF16_RES) w4_store_full_bf16<false, true>(g, acc, m0, n0, wm, wn, l32, hl, smem);
+    else if constexpr (EPI == EPI_FULL_BF16_BIAS) w4_store_full_bf16<true, false>(g, acc, m0, n0, wm, wn, l32, hl, smem);
     else if constexpr (EPI == EPI_FULL_F32) w4_store_full_f32(g, acc, m0, n0, wm, wn, l32, hl);
     else w4_store(g, acc, m0, n0, wm, wn, l32, hl);
 }
@@ -699,13 +714,15 @@ hipError_t launch_w4_epi(const GemmArgs &g, hipStream_t s) {
 
 hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
     if (g.glu_F > 0) return launch_w4_epi<EPI_GLU>(g, s);
-    if (g.rope_cos) return launch_w4_epi<EPI_ROPE>(g, s);
+    if (g.rope_cos) return g.bias ? launch_w4_epi<EPI_ROPE_BIAS>(g, s) : launch_w4_epi<EPI_ROPE>(g, s);
     if (g.glu_bwd_gu) return launch_w4_epi<EPI_GLU_BWD>(g, s);
     // every tile complete and every access of the store aligned: the unguarded vector stores
     const bool full = g.M % W4_BM == 0 && g.N % W4_BN == 0 && !(g.ldc & 7) && !((uintptr_t)g.C & 15) &&
                       (!g.R || (!(g.ldr & 3) && !((uintptr_t)g.R & 7))) && !((uintptr_t)g.bias & 7);
-    if (!full) return launch_w4_epi<EPI_GENERAL>(g, s);
-    return g.out_fp32 ? launch_w4_epi<EPI_FULL_F32>(g, s) : launch_w4_epi<EPI_FULL_BF16>(g, s);
+    if (!full || (g.bias && g.R)) return launch_w4_epi<EPI_GENERAL>(g, s);
+    if (g.out_fp32) return launch_w4_epi<EPI_FULL_F32>(g, s);
+    if (g.R) return launch_w4_epi<EPI_FULL_BF16_RES>(g, s);
+    return g.bias ? launch_w4_epi<EPI_FULL_BF16_BIAS>(g, s) : launch_w4_epi<EPI_FULL_BF16>(g, s);
 }
 
 
