@@ -65,6 +65,14 @@ int32_t mt_k_gemm_nt_swiglu_bwd(const uint16_t *A, int64_t lda, const uint16_t *
  * Requires K % 64 == 0, M % 8 == 0, N % 8 == 0: MT_ERR_UNSUPPORTED otherwise (transpose and use mt_k_gemm_nt). */
 int32_t mt_k_gemm_tn(const uint16_t *At, int64_t lda, const uint16_t *Bt, int64_t ldb, float *C, int64_t ldc, int32_t M,
                      int32_t N, int32_t K, int32_t accumulate, void *stream);
+/* The same product with the reduction over K cut into split_k chunks that run as separate workgroups, for outputs
+ * whose tile count fills the last round of workgroups badly: chunk 0 writes C, chunk s > 0 a slice of ws (device,
+ * at least (split_k - 1) * M * N floats, 16-byte aligned), and a second kernel adds the slices to C in order, so the
+ * result is deterministic.  1 <= split_k <= K / 64; split_k > 1 needs N % 4 == 0, ldc % 4 == 0 and a 16-byte aligned C.
+ * mt_k_gemm_tn_pick_split returns the split the training step would choose on n_cu compute units. */
+int32_t mt_k_gemm_tn_split(const uint16_t *At, int64_t lda, const uint16_t *Bt, int64_t ldb, float *C, int64_t ldc, int32_t M,
+                           int32_t N, int32_t K, int32_t accumulate, int32_t split_k, float *ws, void *stream);
+int32_t mt_k_gemm_tn_pick_split(int64_t M, int64_t N, int64_t K, int32_t n_cu);
 /* db[cols] fp32 (written) = sum over the n rows of x [n, ld] bf16 (the gradient of such a bias); cols % 8 == 0;
  * ws: device scratch of at least mt_k_bias_grad_ws_bytes(cols) bytes.  Fixed summation order. */
 size_t mt_k_bias_grad_ws_bytes(int32_t cols);

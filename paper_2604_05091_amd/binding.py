@@ -125,6 +125,9 @@ def lib():
         "mt_k_gemm_nt_swiglu_bwd": ([p16, c_int64, p16, c_int64, p16, c_int64, p16, c_int64, c_int32, c_int32, c_int32,
                                      c_void_p], c_int32),
         "mt_k_gemm_tn": ([p16, c_int64, p16, c_int64, pf, c_int64, c_int32, c_int32, c_int32, c_int32, c_void_p], c_int32),
+        "mt_k_gemm_tn_split": ([p16, c_int64, p16, c_int64, pf, c_int64, c_int32, c_int32, c_int32, c_int32, c_int32, pf,
+                                c_void_p], c_int32),
+        "mt_k_gemm_tn_pick_split": ([c_int64, c_int64, c_int64, c_int32], c_int32),
         "mt_k_bias_grad_ws_bytes": ([c_int32], c_size_t),
         "mt_k_bias_grad": ([pf, p16, c_int64, c_int64, c_int32, c_void_p, c_void_p], c_int32),
         "mt_k_flash_fwd": ([p16, c_int64, pf, p16, c_int64, p16, c_int64, p16, c_int64, c_int32, c_int32, c_int32,

@@ -101,6 +101,12 @@ struct GemmArgs {
     // ds [M, N] (N = F, the gradient of the activation, rounded to bf16 as a stored ds would be); with the forward's
     // gate | up in glu_bwd_gu [M, 2N] the kernel stores C [M, 2N] = dgate | dup instead of ds
     const bf16_t *glu_bwd_gu = nullptr; int64_t ld_glu_bwd = 0;
+    // optional split of the reduction (gemm_tn only): the K range is cut into split_k chunks that run as separate
+    // workgroups (all tiles of chunk 0, then all tiles of chunk 1, ...), chunk 0 stores to C, chunk s > 0 to
+    // split_ws + (s - 1) M N (fp32, pitch N), and a second kernel adds them to C in that order.  For tile counts
+    // that fill the last round of workgroups badly (see gemm_tn_pick_split).
+    int32_t split_k = 1;
+    float *split_ws = nullptr;
 };
 hipError_t gemm_nt(const GemmArgs &g, hipStream_t s);
 // true when gemm_nt would apply g.rope_* in its epilogue for this problem (large grid, K % 64 == 0, head-aligned
@@ -115,6 +121,9 @@ bool gemm_nt_fuses_glu_bwd(const GemmArgs &g);
 // needs K % 64 == 0, M % 8 == 0, N % 8 == 0; returns hipErrorNotSupported otherwise (callers then transpose
 // the operands and use gemm_nt).
 hipError_t gemm_tn(const GemmArgs &g, hipStream_t s);
+// Reduction split for gemm_tn that minimises the estimated time of an M x N x K weight-gradient product on n_cu
+// compute units, 1 = none; the workspace it needs is (split - 1) * M * N floats.
+int gemm_tn_pick_split(int64_t M, int64_t N, int64_t K, int n_cu);
 
 // out[b][c][r] = in[b][r][c] for r < rows, c < cols (bf16); leading dimensions in elements.
 // Two batch levels (b0 < nb0, b1 < nb1) with independent strides on each side.

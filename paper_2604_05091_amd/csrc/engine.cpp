@@ -211,6 +211,9 @@ struct mt_handle {
     bool mlp_chunked = false;
     uint16_t *dlogits, *dlT;
     float *lse, *delta, *logits, *loss_rows, *loss_dev, *norm_ws, *bias_ws, *rope_cos, *rope_sin;
+    float *split_ws = nullptr;   // partial results of weight-gradient products whose reduction is split
+    size_t split_ws_floats = 0;
+    int n_cu = 256;
     int32_t *tok_dev, *lab_dev, *rowstart_dev, *order_dev;
     int64_t ce_chunk = 0;
     // gradient slab pool (Section 3.3 / Appendix A.3): when the fp32 gradient blocks cannot all be pinned,
@@ -349,6 +352,12 @@ mt_status weight_grad(mt_handle *h, const uint16_t *dY, int64_t ldy, const uint1
         g.A = dY; g.lda = ldy; g.B = X; g.ldb = ldx; g.C = dW; g.ldc = in; g.R = nullptr; g.ldr = 0;
         g.M = (int32_t)out; g.N = (int32_t)in; g.K = (int32_t)rows;
         g.out_fp32 = 1; g.accumulate = accumulate;
+        // tile counts that fill the last round of workgroups badly: split the reduction (deterministic, fixed order)
+        int sp = gemm_tn_pick_split(out, in, rows, h->n_cu);
+        while (sp > 1 && (size_t)(sp - 1) * (size_t)out * (size_t)in > h->split_ws_floats) --sp;
+        if ((in & 3) || ((uintptr_t)dW & 15)) sp = 1;
+        g.split_k = sp;
+        g.split_ws = h->split_ws;
         const double bytes = 2.0 * ((double)out * rows + (double)in * rows) + (double)out * in * (accumulate ? 8.0 : 4.0);
         Timed t(h, CLS_GEMM, 2.0 * (double)out * (double)in * (double)rows, bytes);
         KCHK(gemm_tn(g, s));
@@ -958,7 +967,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     struct ActPlan { size_t xn, yn, qkv, att, h1, gu, sact, lse; };
     struct Plan {
         size_t W[2], G[2], anchors, blk_h, dsact, dgu, dyn, dh1, datt, dqkv,
-            dxn, gA, gB, tA, tB, wT, wT2, dlogits, dlT, delta, logits, loss_rows, loss_dev, norm_ws, bias_ws, rope_cos, rope_sin,
+            dxn, gA, gB, tA, tB, wT, wT2, dlogits, dlT, delta, logits, loss_rows, loss_dev, norm_ws, bias_ws, split_ws, rope_cos, rope_sin,
             tok, lab, rowstart, order;
     } P;
     const int K = std::min<int>(cfg->ckpt_interval, D.L);
@@ -999,6 +1008,23 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     P.loss_rows = plan(n * e4); P.loss_dev = plan(256);
     P.norm_ws = plan(rmsnorm_bwd_ws_floats(D.d) * e4);
     P.bias_ws = plan(D.bias ? bias_grad_ws_floats((int32_t)D.Nqkv) * e4 : 0);
+    // workspace for split reductions of the weight-gradient products, sized for the full token count
+    {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            h->n_cu = v;
+        else
+            (void)hipGetLastError();
+        const int64_t rows = (int64_t)cfg->max_batch * cfg->max_seq;
+        const int64_t shp[5][2] = {{D.Nqkv, D.d}, {D.d, D.Nq}, {2 * (int64_t)D.F, D.d}, {D.d, D.F}, {D.V, D.d}};
+        size_t need = 0;
+        for (auto &sh : shp) {
+            const int sp = gemm_tn_pick_split(sh[0], sh[1], sh[0] == D.V ? std::min<int64_t>(rows, chunk) : rows, h->n_cu);
+            need = std::max(need, (size_t)(sp - 1) * (size_t)sh[0] * (size_t)sh[1]);
+        }
+        h->split_ws_floats = need;
+    }
+    P.split_ws = plan(h->split_ws_floats * e4);
     P.rope_cos = plan((size_t)cfg->max_seq * (D.hd / 2) * e4);
     P.rope_sin = plan((size_t)cfg->max_seq * (D.hd / 2) * e4);
     P.tok = plan(n * 4); P.lab = plan(n * 4); P.rowstart = plan(((size_t)D.V + 1) * 4); P.order = plan(n * 4);
@@ -1059,6 +1085,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
     h->logits = (float *)(A + P.logits); h->loss_rows = (float *)(A + P.loss_rows);
     h->loss_dev = (float *)(A + P.loss_dev); h->norm_ws = (float *)(A + P.norm_ws);
     h->bias_ws = (float *)(A + P.bias_ws);
+    h->split_ws = h->split_ws_floats ? (float *)(A + P.split_ws) : nullptr;
     h->rope_cos = (float *)(A + P.rope_cos); h->rope_sin = (float *)(A + P.rope_sin);
     h->tok_dev = (int32_t *)(A + P.tok); h->lab_dev = (int32_t *)(A + P.lab);
     h->rowstart_dev = (int32_t *)(A + P.rowstart); h->order_dev = (int32_t *)(A + P.order);

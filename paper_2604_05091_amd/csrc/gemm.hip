@@ -740,11 +740,22 @@ template <int EPI>
 __global__ __launch_bounds__(W4_NT) void gemm_tn_w4_kernel(GemmArgs g, int tiles_m, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     constexpr int BM = W4_BM, BN = W4_BN;
-    const int nb = tiles_m * tiles_n;
+    const int n_tiles = tiles_m * tiles_n, nb = n_tiles * g.split_k;
     int pid = blockIdx.x;
     {
         const int q = nb / kXcd, r = nb % kXcd, x = pid % kXcd;
         pid = x * q + (x < r ? x : r) + pid / kXcd;
+    }
+    // split reduction: units are ordered chunk-major, so the workgroups running together still form tile patches
+    // that walk the same K range; chunk 0 owns C, the others a slice of the workspace
+    const int chunk = pid / n_tiles;
+    pid -= chunk * n_tiles;
+    const int nk_all = g.K / BK;
+    const int kb = (int)((int64_t)chunk * nk_all / g.split_k), ke = (int)((int64_t)(chunk + 1) * nk_all / g.split_k);
+    if (chunk > 0) {
+        g.C = g.split_ws + (int64_t)(chunk - 1) * g.M * g.N;
+        g.ldc = g.N;
+        g.accumulate = 0;
     }
     const int group = kGroupM * tiles_n;
     const int first_m = (pid / group) * kGroupM;
@@ -761,8 +772,8 @@ __global__ __launch_bounds__(W4_NT) void gemm_tn_w4_kernel(GemmArgs g, int tiles
     // loader: thread owns the 16-byte chunk (tid & 31) (8 consecutive m or n) of the k rows (tid >> 5) + 8 j.
     // Chunks past the matrix edge re-read the last chunk; they only feed outputs that are never stored.
     const int lk = tid >> 5, lc = (tid & 31) * 8;
-    const bf16_t *abase = g.A + min(m0 + lc, g.M - 8);
-    const bf16_t *bbase = g.B + min(n0 + lc, g.N - 8);
+    const bf16_t *abase = g.A + min(m0 + lc, g.M - 8) + (int64_t)kb * BK * g.lda;
+    const bf16_t *bbase = g.B + min(n0 + lc, g.N - 8) + (int64_t)kb * BK * g.ldb;
     u32x4 st[16];
     bf16x8 fr[2][8];
     f32x16 acc[4][4];
@@ -842,7 +853,7 @@ __global__ __launch_bounds__(W4_NT) void gemm_tn_w4_kernel(GemmArgs g, int tiles
         cur = nxt;                                                                                      \
     }
 
-    const int nk = g.K / BK;
+    const int nk = ke - kb;
 #pragma unroll
     for (int c = 0; c < 16; ++c) TN_LOAD(c, 0);
 #pragma unroll
@@ -870,6 +881,17 @@ __global__ __launch_bounds__(W4_NT) void gemm_tn_w4_kernel(GemmArgs g, int tiles
     else w4_store(g, acc, m0, n0, wm, wn, l32, hl);
 }
 
+// C (pitch ldc) += ws[0] + ws[1] + ... (n_ws slices of M x N floats, pitch N), added in that order
+__global__ __launch_bounds__(256) void split_reduce_kernel(float *C, int64_t ldc, const float *ws, int n_ws, int M, int N) {
+    const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4, total = (int64_t)M * N;
+    if (idx >= total) return;
+    const int64_t row = idx / N;
+    const int col = (int)(idx % N);
+    f32x4 v = *reinterpret_cast<const f32x4 *>(C + row * ldc + col);
+    for (int k = 0; k < n_ws; ++k) v += *reinterpret_cast<const f32x4 *>(ws + (int64_t)k * total + idx);
+    *reinterpret_cast<f32x4 *>(C + row * ldc + col) = v;
+}
+
 template <int EPI>
 hipError_t launch_tn_epi(const GemmArgs &g, hipStream_t s) {
     constexpr size_t lds = (size_t)2 * TN_STAGE_BYTES;
@@ -881,7 +903,13 @@ hipError_t launch_tn_epi(const GemmArgs &g, hipStream_t s) {
         attr_set = true;
     }
     const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = (g.N + W4_BN - 1) / W4_BN;
-    hipLaunchKernelGGL(gemm_tn_w4_kernel<EPI>, dim3((unsigned)(tiles_m * tiles_n)), dim3(W4_NT), lds, s, g, tiles_m, tiles_n);
+    hipLaunchKernelGGL(gemm_tn_w4_kernel<EPI>, dim3((unsigned)(tiles_m * tiles_n * g.split_k)), dim3(W4_NT), lds, s, g, tiles_m,
+                       tiles_n);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || g.split_k == 1) return e;
+    const int64_t quads = ((int64_t)g.M * g.N + 3) / 4;
+    hipLaunchKernelGGL(split_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, reinterpret_cast<float *>(g.C),
+                       g.ldc, g.split_ws, g.split_k - 1, g.M, g.N);
     return hipGetLastError();
 }
 
@@ -951,6 +979,26 @@ hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
     return launch<128, 128, 2, 2>(g, s);
 }
 
+int gemm_tn_pick_split(int64_t M, int64_t N, int64_t K, int n_cu) {
+    if (M <= 0 || N <= 0 || K < BK || n_cu <= 0) return 1;
+    const int64_t tiles = ((M + W4_BM - 1) / W4_BM) * ((N + W4_BN - 1) / W4_BN);
+    const int64_t nk = K / BK;
+    // one 64-deep k-step of a 256 x 256 tile takes about 1.65 us; the reduction moves (split + 1) M N floats at
+    // about 3.5 TB/s; a round of workgroups costs the same whether it is full or not
+    const double t_step = 1.65e-6, bw = 3.5e12;
+    int best = 1;
+    double best_t = 1e30;
+    for (int sp = 1; sp <= 6 && nk / sp >= 32; ++sp) {
+        const double rounds = (double)((tiles * sp + n_cu - 1) / n_cu);
+        const double t = rounds * (double)nk / sp * t_step + (sp > 1 ? (sp + 1) * 4.0 * (double)M * (double)N / bw : 0.0);
+        if (t < best_t * (sp > 1 ? 0.98 : 1.0)) {   // a split has to win by 2 % to be taken
+            best_t = t;
+            best = sp;
+        }
+    }
+    return best;
+}
+
 hipError_t gemm_tn(const GemmArgs &g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
     if ((g.lda & 7) || (g.ldb & 7) || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
@@ -958,6 +1006,10 @@ hipError_t gemm_tn(const GemmArgs &g, hipStream_t s) {
         g.glu_out || g.glu_bwd_gu)
         return hipErrorInvalidValue;
     if ((g.K % BK) || (g.M & 7) || (g.N & 7)) return hipErrorNotSupported;
+    if (g.split_k < 1 || g.split_k > g.K / BK) return hipErrorInvalidValue;
+    // the reduction of a split reads and writes C four floats at a time
+    if (g.split_k > 1 && (!g.split_ws || ((uintptr_t)g.split_ws & 15) || (g.ldc & 3) || (g.N & 3) || ((uintptr_t)g.C & 15)))
+        return hipErrorInvalidValue;
     return launch_tn(g, s);
 }
 

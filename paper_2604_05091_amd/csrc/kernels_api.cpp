@@ -89,6 +89,19 @@ int32_t mt_k_gemm_tn(const uint16_t *At, int64_t lda, const uint16_t *Bt, int64_
     return to_status(e);
 }
 
+int32_t mt_k_gemm_tn_split(const uint16_t *At, int64_t lda, const uint16_t *Bt, int64_t ldb, float *C, int64_t ldc, int32_t M,
+                           int32_t N, int32_t K, int32_t accumulate, int32_t split_k, float *ws, void *stream) {
+    if (!At || !Bt || !C || split_k < 1 || (split_k > 1 && !ws)) return MT_ERR_INVALID_ARG;
+    GemmArgs g;
+    g.A = At; g.lda = lda; g.B = Bt; g.ldb = ldb; g.C = C; g.ldc = ldc; g.R = nullptr; g.ldr = 0;
+    g.M = M; g.N = N; g.K = K; g.out_fp32 = 1; g.accumulate = accumulate != 0;
+    g.split_k = split_k; g.split_ws = ws;
+    const hipError_t e = gemm_tn(g, S(stream));
+    if (e == hipErrorNotSupported) return MT_ERR_UNSUPPORTED;
+    return to_status(e);
+}
+int32_t mt_k_gemm_tn_pick_split(int64_t M, int64_t N, int64_t K, int32_t n_cu) { return gemm_tn_pick_split(M, N, K, n_cu); }
+
 size_t mt_k_bias_grad_ws_bytes(int32_t cols) { return bias_grad_ws_floats(cols) * sizeof(float); }
 int32_t mt_k_bias_grad(float *db, const uint16_t *x, int64_t ld, int64_t n, int32_t cols, void *ws, void *stream) {
     if (!db || !x || !ws || !al16(x)) return MT_ERR_INVALID_ARG;

@@ -119,6 +119,40 @@ def test_gemm_token_major_weight_gradient(orc64, n, out, inn):
     assert L.mt_k_gemm_tn(DY.data_ptr(), ldy, X.data_ptr(), ldx, DW.data_ptr(), inn, out, inn, n - 8, 0, None) == -2
 
 
+@pytest.mark.parametrize("n,out,inn,split", [(2048, 520, 1032, 2), (4096, 264, 256, 5), (1024, 1280, 776, 3)])
+def test_gemm_weight_gradient_with_split_reduction(orc64, n, out, inn, split):
+    """The weight-gradient product with its reduction over the tokens cut into chunks that run as separate
+    workgroups: equal to the oracle, with and without accumulation, bit-identical from run to run; ragged tiles."""
+    rng = np.random.default_rng(n + out + inn)
+    dy, x = bf16_round(rng.standard_normal((n, out))), bf16_round(rng.standard_normal((n, inn)))
+    ref = orc64.linear_bwd_w(dy, x)
+    DY, X = dev_bf16(dy), dev_bf16(x)
+    WS = torch.full(((split - 1) * out * inn,), 9.0, dtype=torch.float32, device="cuda")
+    DW = torch.full((out, inn), 7.0, dtype=torch.float32, device="cuda")
+    ok(L.mt_k_gemm_tn_split(DY.data_ptr(), out, X.data_ptr(), inn, DW.data_ptr(), inn, out, inn, n, 0, split, WS.data_ptr(), None))
+    first = DW.clone()
+    assert rel_l2(host(DW), ref) < 5e-6
+    ok(L.mt_k_gemm_tn_split(DY.data_ptr(), out, X.data_ptr(), inn, DW.data_ptr(), inn, out, inn, n, 1, split, WS.data_ptr(), None))
+    assert rel_l2(host(DW), 2 * ref) < 5e-6
+    DW2 = torch.zeros((out, inn), dtype=torch.float32, device="cuda")
+    ok(L.mt_k_gemm_tn_split(DY.data_ptr(), out, X.data_ptr(), inn, DW2.data_ptr(), inn, out, inn, n, 0, split, WS.data_ptr(), None))
+    assert torch.equal(first, DW2)
+    # more chunks than 64-deep steps, or no workspace: argument errors
+    assert L.mt_k_gemm_tn_split(DY.data_ptr(), out, X.data_ptr(), inn, DW.data_ptr(), inn, out, inn, n, 0, n // 64 + 1,
+                                WS.data_ptr(), None) != 0
+    assert L.mt_k_gemm_tn_split(DY.data_ptr(), out, X.data_ptr(), inn, DW.data_ptr(), inn, out, inn, n, 0, 2, None, None) != 0
+
+
+def test_split_choice_for_the_benchmark_shapes():
+    """The split the step picks: none where the tiles fill whole rounds of 256 workgroups (7B q|k|v and output
+    projections), one where the last round would be mostly empty (14B shapes)."""
+    pick = L.mt_k_gemm_tn_pick_split
+    assert pick(12288, 4096, 65536, 256) == 1 and pick(4096, 4096, 65536, 256) == 1
+    assert pick(22016, 4096, 65536, 256) == 2
+    assert pick(7168, 5120, 65536, 256) > 1 and pick(5120, 13824, 65536, 256) > 1
+    assert pick(4096, 4096, 1024, 256) == 1       # short reductions are never split
+
+
 def test_gemm_weight_gradient_form_long_reduction(orc64):
     """dW[out,in] = sum_t dy[t,out] x[t,in]: both operands transposed first, fp32 result."""
     rng = np.random.default_rng(2)
