@@ -26,6 +26,18 @@ def test_one_block_at_real_width_matches_oracle(orc64, name, T):
     check_against_oracle(orc64, shape, 1, T, params, tok, lab, loss, grads)
 
 
+def test_many_tokens_with_a_ragged_last_row_tile_match_oracle(orc64):
+    """13 x 1000 tokens: the large-grid kernels with a partial last row tile (guarded rows in the fused rotary,
+    SwiGLU and SwiGLU-backward stores, the general store elsewhere) and a token count that the token-major
+    weight-gradient kernel refuses (not a multiple of 64), so the transposed-copy route runs."""
+    shape = mt_inputs.ModelShape(1, 256, 4, 2, 128, 512, 512)
+    B, T = 13, 1000
+    params = mt_inputs.make_params(shape, seed=7, std=0.05)
+    tok, lab = mt_inputs.make_batch(shape.vocab, B, T, seed=8)
+    loss, grads, _ = gpu_step(shape, B, T, params, tok, lab)
+    check_against_oracle(orc64, shape, B, T, params, tok, lab, loss, grads)
+
+
 @pytest.mark.parametrize("qkv_bias", [False, True])
 def test_many_tokens_take_the_large_grid_kernels_and_match_oracle(orc64, qkv_bias):
     """A narrow model (heads of 128) on 12 x 1024 tokens: every projection then runs in the large-grid GEMM
