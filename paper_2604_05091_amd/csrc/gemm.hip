@@ -322,7 +322,8 @@ __device__ __forceinline__ void w4_store(const GemmArgs &g, const f32x16 (&acc)[
     }
 }
 
-// complete, aligned tiles (what the host checks before it picks the kernel instantiated with this store).  Bias
+// complete, aligned column tiles (what the host checks before it picks the kernel instantiated with this store;
+// a ragged last row tile is handled by row guards).  Bias
 // and residual are template parameters as well: tested per element at run time they turned every one of the 64
 // loads into a branch with its own wait.  Here a row block's 16 residual loads are in flight together.
 template <bool BIAS, bool RES>
@@ -342,7 +343,8 @@ __device__ __forceinline__ void w4_store_full_bf16(const GemmArgs &g, const f32x
         // bias and residual are added in fp32, before the one rounding to bf16
         uint2 rv[16];
         if constexpr (RES) {
-            const bf16_t *rp = g.R + (int64_t)(m0 + wm * 128 + i * 32 + l32) * g.ldr + col_l;
+            // rows past M (a ragged last row tile) re-read the last row; the second half never stores them
+            const bf16_t *rp = g.R + (int64_t)min(m0 + wm * 128 + i * 32 + l32, g.M - 1) * g.ldr + col_l;
 #pragma unroll
             for (int jq = 0; jq < 16; ++jq) rv[jq] = *reinterpret_cast<const uint2 *>(rp + (jq >> 2) * 32 + (jq & 3) * 8);
         }
@@ -372,6 +374,7 @@ __device__ __forceinline__ void w4_store_full_f32(const GemmArgs &g, const f32x1
     const int row_l = m0 + wm * 128 + l32, col_l = n0 + wn * 128 + hl * 4;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+        if (row_l + i * 32 >= g.M) continue;   // ragged last row tile
         float *cp = reinterpret_cast<float *>(g.C) + (int64_t)(row_l + i * 32) * g.ldc + col_l;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -716,8 +719,8 @@ hipError_t launch_w4(const GemmArgs &g, hipStream_t s) {
     if (g.glu_F > 0) return launch_w4_epi<EPI_GLU>(g, s);
     if (g.rope_cos) return g.bias ? launch_w4_epi<EPI_ROPE_BIAS>(g, s) : launch_w4_epi<EPI_ROPE>(g, s);
     if (g.glu_bwd_gu) return launch_w4_epi<EPI_GLU_BWD>(g, s);
-    // every tile complete and every access of the store aligned: the unguarded vector stores
-    const bool full = g.M % W4_BM == 0 && g.N % W4_BN == 0 && !(g.ldc & 7) && !((uintptr_t)g.C & 15) &&
+    // every column tile complete and every access of the store aligned: the vector stores (rows are guarded)
+    const bool full = g.N % W4_BN == 0 && !(g.ldc & 7) && !((uintptr_t)g.C & 15) &&
                       (!g.R || (!(g.ldr & 3) && !((uintptr_t)g.R & 7))) && !((uintptr_t)g.bias & 7);
     if (!full || (g.bias && g.R)) return launch_w4_epi<EPI_GENERAL>(g, s);
     if (g.out_fp32) return launch_w4_epi<EPI_FULL_F32>(g, s);
@@ -914,7 +917,7 @@ hipError_t launch_tn_epi(const GemmArgs &g, hipStream_t s) {
 }
 
 hipError_t launch_tn(const GemmArgs &g, hipStream_t s) {
-    const bool full = g.M % W4_BM == 0 && g.N % W4_BN == 0 && !(g.ldc & 3) && !((uintptr_t)g.C & 15);
+    const bool full = g.N % W4_BN == 0 && !(g.ldc & 3) && !((uintptr_t)g.C & 15);
     return full ? launch_tn_epi<EPI_FULL_F32>(g, s) : launch_tn_epi<EPI_GENERAL>(g, s);
 }
 
