@@ -489,202 +489,190 @@ __global__ __launch_bounds__(64 * NW) void flash_bwd_dq_kernel(AttnArgs a) {
                              a.rope_cos ? a.rope_sin + (int64_t)q0 * (HD / 2) : nullptr, out_region<HD>(smem, wave));
 }
 
-// ------------------------------------------------------------------ backward: dK, dV, software-pipelined
-// grid: key blocks of 128 (heaviest first = block 0) x (batch, KV head); a lane owns one key and keeps its K
-// and V fragments in registers; the query heads of the group and their query tiles >= the key block are
-// walked as one sequence.  The work is cut into units u = (query tile, 32-query half) and every wave runs a three-stage pipeline over them so that the matrix cores and the
-// vector ALU work at the same time although only one wave fits on a SIMD:
-//     slot t :   A(t+1)  S = Q K^T, dP = dO V^T          16 MFMAs  -> accumulator set (t+1)&1
-//                B(t)    P = exp2(S c - lse), dS = P (dP - delta), packed to bf16     VALU
-//                C(t-1)  dV^T += dO^T P, dK^T += Q^T dS   16 MFMAs  <- packed set (t-1)&1
-// The three parts of a slot are independent, so the scheduler can issue B's arithmetic between the
-// MFMAs.  Three LDS stages hold the tiles of units t-1 .. t+1; tile j+2 is written during slot 2j+1 into
-// the stage that tile j-1 left at the end of slot 2j.  Slots run from t = -1 to t = U with the same body:
-// LDS and the registers start as zeros, so the parts that fall outside 0 .. U-1 add exact zeros (C) or
-// compute values nobody reads (A, B).  Units a wave has no visible query for are simply fully masked.
-__device__ __forceinline__ void wg_barrier_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-constexpr int kPipePad = 40;
+// ------------------------------------------------------------------ backward: dK, dV
+// grid: key blocks of 128 (heaviest first = block 0) x (batch, KV head); the query heads of the group and their
+// 64-query tiles >= the key block are walked as one sequence through a double-buffered LDS stage, one barrier
+// per tile.  8 waves: wave w owns the 32 keys of group w & 3 (a lane owns one key) and, of every tile, the
+// 32-query half w >> 2; the two waves of a key group sit on the same SIMD, keep separate dK / dV accumulators
+// and add them through LDS at the end.  Per tile a wave computes S^T = K Q^T and dP^T = V dO^T (16 MFMAs),
+// P = exp2(S c - lse), dS = P (dP - delta) on the vector ALU, then dV^T += dO^T P and dK^T += Q^T dS (16 MFMAs);
+// the other wave's MFMAs cover the exponentials.  The lane's K fragments live in registers, V fragments are
+// re-read from LDS for every tile: with both in registers only one wave would fit on a SIMD (measured 15 %
+// slower at 128k tokens, with a three-stage software pipeline inside the wave to make up for it).
+// LDS: K, V [128][HD + 8] | two stages of { Q, dO [64][HD + 40], lse * log2e [64], delta [64] }.
+// Row pitch HD + 40 elements: consecutive rows are 20 banks apart, which keeps the 16-byte row reads
+// conflict-free (odd multiple of 4 banks) and lets the four rows of a transposing read overlap in only
+// 12 of 64 banks (with HD + 8 they pile up on the same 28 banks).
+constexpr int kDkdvPad = 40;
 template <int HD>
-__global__ __launch_bounds__(256) void flash_bwd_dkdv_kernel(AttnArgs a) {
-    // row pitch HD + 40 elements: consecutive rows are 20 banks apart, which keeps the 16-byte row reads
-    // conflict-free (odd multiple of 4 banks) and lets the four rows of a transposing read overlap in only
-    // 12 of 64 banks (with HD + 8 they pile up on the same 28 banks)
-    constexpr int LDK = HD + kPipePad, KS = HD / 16, HB = HD / 32;
-    constexpr int STAGE_BF = 2 * 64 * LDK, STAGE = STAGE_BF + 256;  // Q, dO (bf16) | lse*log2e[64], delta[64] (fp32)
+__global__ __launch_bounds__(512) void flash_bwd_dkdv_kernel(AttnArgs a) {
+    constexpr int LDK = HD + kDkdvPad, LDKV = HD + 8, HB = HD / 32;
+    constexpr int KV_BF = 128 * LDKV;
+    constexpr int STAGE_BF = 2 * 64 * LDK, STAGE = STAGE_BF + 256;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    bf16_t *Kt = smem, *Vt = smem + KV_BF, *stages = smem + 2 * KV_BF;
 
     const int T = a.T, G = a.Hq / a.Hkv;
     int set, kvb;
     if (!decode_block((T + 127) / 128, a.B * a.Hkv, &set, &kvb)) return;
-    kvb = snake8(kvb, (T + 127) / 128);  // key block 0 sees the most queries
+    kvb = snake8(kvb, (T + 127) / 128);
     const int b = set / a.Hkv, hk = set % a.Hkv;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int kg = wave & 3, par = wave >> 2;
     const int tr_off = tr_lane_offset(lane, LDK);
-    const int kv0w = kvb * 128 + wave * 32, kv = kv0w + l32;
-    const bool kvok = kv < T;
+    const int kv0w = kvb * 128 + kg * 32, kv = kv0w + l32;
 
-    bf16x8 kf[KS], vf[KS];
-    {
-        const int kvc = kvok ? kv : T - 1;
-        const bf16_t *kp = a.k + ((int64_t)b * T + kvc) * a.ldk + (int64_t)hk * HD + hl * 8;
-        const bf16_t *vp = a.v + ((int64_t)b * T + kvc) * a.ldv + (int64_t)hk * HD + hl * 8;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            kf[ks] = load_frag_global(kp + ks * 16);
-            vf[ks] = load_frag_global(vp + ks * 16);
-        }
-    }
     f32x16 dvacc[HB], dkacc[HB];
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
         dvacc[hb] = zero16();
         dkacc[hb] = zero16();
     }
-    f32x16 sS[2] = {zero16(), zero16()}, sP[2] = {zero16(), zero16()};  // S and dP of the unit in flight / in use
-    bf16x8 fP[2][2], fS[2][2];                                          // packed P and dS, [set][16-query half]
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            fP[i][j] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
-            fS[i][j] = fP[i][j];
-        }
     const float c = a.scale * kLog2e;
     const int qt_first = (kvb * 128) / 64, n_qt = (T + 63) / 64 - qt_first;
     const int total = G * n_qt;
 
-    TileStage<64, HD, LDK, 256> stQ, stDO;
+    using Stage = TileStage<64, HD, LDK, 512>;
+    Stage stQ, stDO;
     float stat = 0.f;
-    // tiles are fetched in order; (f_head, f_tile) is the next one: query head of the group, query tile
     int f_head = 0, f_tile = 0;
-    using Stage = TileStage<64, HD, LDK, 256>;
-    auto fetch_into = [&](Stage &sq, Stage &sdo, float &st) {
+    auto fetch_next = [&]() {
         const int h = hk * G + f_head, q0t = (qt_first + f_tile) * 64;
         if (++f_tile == n_qt) {
             f_tile = 0;
             ++f_head;
         }
-        sq.fetch_clamped(a.q + ((int64_t)b * T + q0t) * a.ldq + (int64_t)h * HD, a.ldq, T - q0t);
-        sdo.fetch_clamped(a.dout + ((int64_t)b * T + q0t) * a.lddo + (int64_t)h * HD, a.lddo, T - q0t);
+        stQ.fetch_clamped(a.q + ((int64_t)b * T + q0t) * a.ldq + (int64_t)h * HD, a.ldq, T - q0t);
+        stDO.fetch_clamped(a.dout + ((int64_t)b * T + q0t) * a.lddo + (int64_t)h * HD, a.lddo, T - q0t);
         if (threadIdx.x < 128) {
             const int qq = q0t + (threadIdx.x & 63);
             const int64_t si = ((int64_t)b * a.Hq + h) * T + (qq < T ? qq : T - 1);
             // queries past T: lse = +inf makes their P (and with it dS) exactly zero
-            st = threadIdx.x < 64 ? (qq < T ? a.lse[si] * kLog2e : INFINITY) : a.delta[si];
+            stat = threadIdx.x < 64 ? (qq < T ? a.lse[si] * kLog2e : INFINITY) : a.delta[si];
         }
     };
-    auto commit_from = [&](int stage, Stage &sq, Stage &sdo, float st) {
-        bf16_t *sp = smem + stage * STAGE;
-        sq.commit_plain(sp);
-        sdo.commit_plain(sp + 64 * LDK);
-        if (threadIdx.x < 128) reinterpret_cast<float *>(sp + STAGE_BF)[threadIdx.x] = st;
+    auto commit = [&](int stage) {
+        bf16_t *sp = stages + stage * STAGE;
+        stQ.commit_plain(sp);
+        stDO.commit_plain(sp + 64 * LDK);
+        if (threadIdx.x < 128) reinterpret_cast<float *>(sp + STAGE_BF)[threadIdx.x] = stat;
     };
-    auto fetch_next = [&]() { fetch_into(stQ, stDO, stat); };
-    auto commit = [&](int stage) { commit_from(stage, stQ, stDO, stat); };
-    // prologue: the first two tiles are requested together (a second set of staging registers exists only here),
-    // then the three stages are zeroed while they are on their way: the pipeline's first and last slots read tiles
-    // that were never written
     {
-        Stage stQ2, stDO2;
-        float stat2 = 0.f;
-        if (total > 0) fetch_into(stQ, stDO, stat);
-        if (total > 1) fetch_into(stQ2, stDO2, stat2);
-        {
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            for (int i = threadIdx.x; i < 3 * STAGE / 8; i += 256) reinterpret_cast<u32x4 *>(smem)[i] = z;
-        }
-        __syncthreads();  // zeros in place before the first tiles land
-        if (total > 0) commit_from(0, stQ, stDO, stat);
-        if (total > 1) commit_from(1, stQ2, stDO2, stat2);
+        TileStage<128, HD, LDKV, 512> stK, stV;
+        const int rows = T - kvb * 128;
+        stK.fetch(a.k + ((int64_t)b * T + kvb * 128) * a.ldk + (int64_t)hk * HD, a.ldk, rows, HD);
+        stV.fetch(a.v + ((int64_t)b * T + kvb * 128) * a.ldv + (int64_t)hk * HD, a.ldv, rows, HD);
+        fetch_next();
+        stK.commit(Kt);
+        stV.commit(Vt);
+        commit(0);
     }
-    if (total > 2) fetch_next();
     __syncthreads();
 
-    // one slot; PAR = t & 1 (compile time); SA / SB / SC = LDS stages of the tiles of units t+1, t, t-1;
-    // QSB = first query of the tile of unit t
-#define DKDV_SLOT(PAR, SA, SB, SC, QSB)                                                                 \
-    {                                                                                                   \
-        constexpr int rbA = 1 - (PAR), rbB = (PAR), rbC = 1 - (PAR);                                    \
-        const bf16_t *QA = smem + (SA) * STAGE, *dOA = QA + 64 * LDK;                                   \
-        const bf16_t *QB = smem + (SB) * STAGE;                                                         \
-        const bf16_t *QC = smem + (SC) * STAGE, *dOC = QC + 64 * LDK;                                   \
-        const float *lses = reinterpret_cast<const float *>(QB + STAGE_BF), *dlts = lses + 64;          \
-        /* ---- B(t): needs S, dP of set PAR */                                                         \
-        {                                                                                               \
-            /* causal mask: key kv sees query q0u + qi + e only if kv <= it, i.e. the element with in-unit  \
-               offset o = r4*8 + e is masked when o < lim (lim <= 0 for units past the diagonal) */            \
-            const int lim = kv - ((QSB) + rbB * 32 + hl * 4);                                           \
-            f32x16 pacc, dsacc;                                                                         \
-            _Pragma("unroll") for (int r4 = 0; r4 < 4; ++r4) {                                          \
-                const int qi = rbB * 32 + r4 * 8 + hl * 4;                                              \
-                const float4 l4 = *reinterpret_cast<const float4 *>(lses + qi);                         \
-                const float4 d4 = *reinterpret_cast<const float4 *>(dlts + qi);                         \
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};        \
-                _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                         \
-                    const int r = r4 * 4 + e;                                                           \
-                    float p = __builtin_amdgcn_exp2f(sS[PAR][r] * c - lv[e]);                           \
-                    p = (r4 * 8 + e < lim) ? 0.f : p;                                                   \
-                    pacc[r] = p;                                                                        \
-                    dsacc[r] = p * (sP[PAR][r] - dv4[e]);                                               \
-                }                                                                                       \
-            }                                                                                           \
-            fP[PAR][0] = pack_frag(pacc, 0);                                                            \
-            fP[PAR][1] = pack_frag(pacc, 1);                                                            \
-            fS[PAR][0] = pack_frag(dsacc, 0);                                                           \
-            fS[PAR][1] = pack_frag(dsacc, 1);                                                           \
-        }                                                                                               \
-        /* ---- A(t+1): S, dP of the next unit into set 1 - PAR */                                      \
-        {                                                                                               \
-            const bf16_t *qr = QA + (rbA * 32 + l32) * LDK + hl * 8;                                    \
-            const bf16_t *dor = dOA + (rbA * 32 + l32) * LDK + hl * 8;                                  \
-            f32x16 s_ = zero16(), p_ = zero16();                                                        \
-            _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                         \
-                const bf16x8 qq8 = *reinterpret_cast<const bf16x8 *>(qr + ks * 16);                     \
-                const bf16x8 dd8 = *reinterpret_cast<const bf16x8 *>(dor + ks * 16);                    \
-                s_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq8, kf[ks], s_, 0, 0, 0);                 \
-                p_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dd8, vf[ks], p_, 0, 0, 0);                 \
-            }                                                                                           \
-            sS[1 - (PAR)] = s_;                                                                         \
-            sP[1 - (PAR)] = p_;                                                                         \
-        }                                                                                               \
-        /* ---- C(t-1): dV, dK from the packed set 1 - PAR */                                           \
-        _Pragma("unroll") for (int cch = 0; cch < 2; ++cch) {                                           \
-            mfma_tr_accumulate<HD, LDK>(dvacc, dOC, tr_off, rbC, cch, fP[1 - (PAR)][cch]);              \
-            mfma_tr_accumulate<HD, LDK>(dkacc, QC, tr_off, rbC, cch, fS[1 - (PAR)][cch]);               \
-        }                                                                                               \
-        /* B's results are consumed in the next slot only: without this the compiler sinks B's arithmetic   \
-           below the tile commit that follows the odd slot, out of reach of this slot's MFMAs */            \
-        asm volatile("" : "+v"(fP[PAR][0]), "+v"(fP[PAR][1]), "+v"(fS[PAR][0]), "+v"(fS[PAR][1]));      \
+    const bf16_t *kr = Kt + (kg * 32 + l32) * LDKV + hl * 8;
+    const bf16_t *vr = Vt + (kg * 32 + l32) * LDKV + hl * 8;
+    bf16x8 kf[HD / 16];
+#pragma unroll
+    for (int i = 0; i < HD / 16; ++i) kf[i] = *reinterpret_cast<const bf16x8 *>(kr + i * 16);
+    int tq = 0;  // query tile inside the head
+    for (int j = 0; j < total; ++j) {
+        const bf16_t *Qs = stages + (j & 1) * STAGE, *dOs = Qs + 64 * LDK;
+        const float *lses = reinterpret_cast<const float *>(Qs + STAGE_BF), *dlts = lses + 64;
+        const int q0u = (qt_first + tq) * 64 + par * 32;
+        const bool more = j + 1 < total;
+        if (more) fetch_next();
+        if (q0u + 31 >= kv0w) {  // wave-uniform: some query of the half sees some key of the group
+            f32x16 s_ = zero16(), p_ = zero16();
+            const bf16_t *qr = Qs + (par * 32 + l32) * LDK + hl * 8;
+            const bf16_t *dor = dOs + (par * 32 + l32) * LDK + hl * 8;
+#pragma unroll
+            for (int half = 0; half < HD / 64; ++half) {
+                bf16x8 qq[4], kk[4], dd[4], vv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    qq[i] = *reinterpret_cast<const bf16x8 *>(qr + (half * 4 + i) * 16);
+                    kk[i] = kf[half * 4 + i];
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    dd[i] = *reinterpret_cast<const bf16x8 *>(dor + (half * 4 + i) * 16);
+                    vv[i] = *reinterpret_cast<const bf16x8 *>(vr + (half * 4 + i) * 16);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq[i], kk[i], s_, 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) p_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dd[i], vv[i], p_, 0, 0, 0);
+            }
+            // P = exp2(S c - lse), dS = P (dP - delta); element r of the lane belongs to query
+            // q0u + (r >> 2) * 8 + hl * 4 + (r & 3), visible to the lane's key only if kv <= query
+            const int lim = kv - (q0u + hl * 4);
+            const bool diag = q0u < kv0w + 31;
+            f32x16 dsacc;
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int qi = par * 32 + r4 * 8 + hl * 4;
+                const float4 l4 = *reinterpret_cast<const float4 *>(lses + qi);
+                const float4 d4 = *reinterpret_cast<const float4 *>(dlts + qi);
+                const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int r = r4 * 4 + e;
+                    float p = __builtin_amdgcn_exp2f(s_[r] * c - lv[e]);
+                    if (diag) p = (r4 * 8 + e < lim) ? 0.f : p;
+                    s_[r] = p;
+                    dsacc[r] = p * (p_[r] - dv4[e]);
+                }
+            }
+            // dV^T += dO^T P, dK^T += Q^T dS
+#pragma unroll
+            for (int cch = 0; cch < 2; ++cch) {
+                mfma_tr_accumulate<HD, LDK>(dvacc, dOs, tr_off, par, cch, pack_frag(s_, cch));
+                mfma_tr_accumulate<HD, LDK>(dkacc, Qs, tr_off, par, cch, pack_frag(dsacc, cch));
+            }
+        }
+        if (more) commit((j + 1) & 1);
+        __syncthreads();
+        tq = tq + 1 == n_qt ? 0 : tq + 1;
     }
-    // B's dependence on the set written by the previous slot's A, and C's on the previous slot's B, are the
-    // only links between slots; within a slot the scheduler is free to interleave the three parts.
-    int st_j = 2, st_j1 = 0;   // LDS stages of tiles j and j+1 (tile -1 reads the still-zero stage 2)
-    int tq_j = 0, tq_j1 = 0;   // their query-tile numbers inside the head
-    for (int j = -1; j < total; ++j) {
-        const int st_j2 = st_j1 == 2 ? 0 : st_j1 + 1;
-        // odd slot t = 2j+1: A(2j+2) tile j+1 half 0, B(2j+1) tile j half 1, C(2j) tile j half 0
-        DKDV_SLOT(1, st_j1, st_j, st_j, (qt_first + tq_j) * 64)
-        // tile j+2 goes to the stage tile j-1 left at the end of the previous slot; then tile j+3 is requested
-        if (j >= 0 && j + 2 < total) commit(st_j2);
-        if (j >= 0 && j + 3 < total) fetch_next();
-        wg_barrier_lds();
-        // even slot t = 2j+2: A(2j+3) tile j+1 half 1, B(2j+2) tile j+1 half 0, C(2j+1) tile j half 1
-        DKDV_SLOT(0, st_j1, st_j1, st_j, (qt_first + tq_j1) * 64)
-        wg_barrier_lds();
-        st_j = st_j1;
-        st_j1 = st_j2;
-        tq_j = tq_j1;
-        tq_j1 = tq_j1 + 1 == n_qt ? 0 : tq_j1 + 1;
+
+    // the two waves of a key group exchange halves: the first keeps dK, the second dV
+    {
+        float4 *red = reinterpret_cast<float4 *>(smem);  // [wave][4 * HB][lane], 16 bytes per lane
+        constexpr int NV = 4 * HB;
+        auto publish = [&](const f32x16 *acc) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int o = (i & 3) * 4;
+                red[(wave * NV + i) * 64 + lane] = make_float4(acc[i >> 2][o], acc[i >> 2][o + 1], acc[i >> 2][o + 2], acc[i >> 2][o + 3]);
+            }
+        };
+        auto absorb = [&](f32x16 *acc) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const float4 t = red[((wave ^ 4) * NV + i) * 64 + lane];
+                const int o = (i & 3) * 4;
+                acc[i >> 2][o] += t.x;
+                acc[i >> 2][o + 1] += t.y;
+                acc[i >> 2][o + 2] += t.z;
+                acc[i >> 2][o + 3] += t.w;
+            }
+        };
+        if (par) publish(dkacc);
+        else publish(dvacc);
+        __syncthreads();
+        if (par) absorb(dvacc);
+        else absorb(dkacc);
+        __syncthreads();
     }
-#undef DKDV_SLOT
     if (kv0w < T) {
         const int n_valid = min(32, T - kv0w);
-        write_owned_rows<HD>(a.dk + ((int64_t)b * T + kv0w) * a.lddk + (int64_t)hk * HD, a.lddk, dkacc, a.scale, l32, hl,
-                             n_valid, a.rope_cos ? a.rope_cos + (int64_t)kv0w * (HD / 2) : nullptr,
-                             a.rope_cos ? a.rope_sin + (int64_t)kv0w * (HD / 2) : nullptr, out_region<HD>(smem, wave));
-        write_owned_rows<HD>(a.dv + ((int64_t)b * T + kv0w) * a.lddv + (int64_t)hk * HD, a.lddv, dvacc, 1.0f, l32, hl,
-                             n_valid, nullptr, nullptr, out_region<HD>(smem, wave));
+        if (par == 0)
+            write_owned_rows<HD>(a.dk + ((int64_t)b * T + kv0w) * a.lddk + (int64_t)hk * HD, a.lddk, dkacc, a.scale, l32,
+                                 hl, n_valid, a.rope_cos ? a.rope_cos + (int64_t)kv0w * (HD / 2) : nullptr,
+                                 a.rope_cos ? a.rope_sin + (int64_t)kv0w * (HD / 2) : nullptr, out_region<HD>(smem, wave));
+        else
+            write_owned_rows<HD>(a.dv + ((int64_t)b * T + kv0w) * a.lddv + (int64_t)hk * HD, a.lddv, dvacc, 1.0f, l32, hl,
+                                 n_valid, nullptr, nullptr, out_region<HD>(smem, wave));
     }
 }
 
@@ -767,18 +755,19 @@ hipError_t flash_bwd_dkdv(const AttnArgs &a, hipStream_t s) {
         ((uintptr_t)a.dv & 7))
         return hipErrorInvalidValue;
     const dim3 grid(grid_blocks((a.T + 127) / 128, a.B * a.Hkv));
+    // K, V [128][hd + 8] | two stages of Q, dO [64][hd + pad] + 64 lse + 64 delta
     if (a.hd == 128) {
-        constexpr size_t lds = 3 * ((2 * 64 * (128 + kPipePad)) * sizeof(bf16_t) + 512);
+        constexpr size_t lds = (2 * 128 * (128 + 8) + 2 * (2 * 64 * (128 + kDkdvPad))) * sizeof(bf16_t) + 2 * 512;
         static bool done = false;
         hipError_t e = ensure_lds(&flash_bwd_dkdv_kernel<128>, lds, &done);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(flash_bwd_dkdv_kernel<128>, grid, dim3(256), lds, s, a);
+        hipLaunchKernelGGL(flash_bwd_dkdv_kernel<128>, grid, dim3(512), lds, s, a);
     } else {
-        constexpr size_t lds = 3 * ((2 * 64 * (64 + kPipePad)) * sizeof(bf16_t) + 512);
+        constexpr size_t lds = (2 * 128 * (64 + 8) + 2 * (2 * 64 * (64 + kDkdvPad))) * sizeof(bf16_t) + 2 * 512;
         static bool done = false;
         hipError_t e = ensure_lds(&flash_bwd_dkdv_kernel<64>, lds, &done);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(flash_bwd_dkdv_kernel<64>, grid, dim3(256), lds, s, a);
+        hipLaunchKernelGGL(flash_bwd_dkdv_kernel<64>, grid, dim3(512), lds, s, a);
     }
     return hipGetLastError();
 }
