@@ -535,6 +535,7 @@ __global__ __launch_bounds__(512) void flash_bwd_dkdv_kernel(AttnArgs a) {
     using Stage = TileStage<64, HD, LDK, 512>;
     Stage stQ, stDO;
     float stat = 0.f;
+    bool stat_pad = false;
     int f_head = 0, f_tile = 0;
     auto fetch_next = [&]() {
         const int h = hk * G + f_head, q0t = (qt_first + f_tile) * 64;
@@ -545,17 +546,22 @@ __global__ __launch_bounds__(512) void flash_bwd_dkdv_kernel(AttnArgs a) {
         stQ.fetch_clamped(a.q + ((int64_t)b * T + q0t) * a.ldq + (int64_t)h * HD, a.ldq, T - q0t);
         stDO.fetch_clamped(a.dout + ((int64_t)b * T + q0t) * a.lddo + (int64_t)h * HD, a.lddo, T - q0t);
         if (threadIdx.x < 128) {
+            // one plain load, nothing computed from it here: arithmetic on the value would make these two waves
+            // wait for it (and for the tile loads just issued) before they start on the current tile
             const int qq = q0t + (threadIdx.x & 63);
             const int64_t si = ((int64_t)b * a.Hq + h) * T + (qq < T ? qq : T - 1);
-            // queries past T: lse = +inf makes their P (and with it dS) exactly zero
-            stat = threadIdx.x < 64 ? (qq < T ? a.lse[si] * kLog2e : INFINITY) : a.delta[si];
+            stat = *(threadIdx.x < 64 ? a.lse + si : a.delta + si);
+            stat_pad = qq >= T;
         }
     };
     auto commit = [&](int stage) {
         bf16_t *sp = stages + stage * STAGE;
         stQ.commit_plain(sp);
         stDO.commit_plain(sp + 64 * LDK);
-        if (threadIdx.x < 128) reinterpret_cast<float *>(sp + STAGE_BF)[threadIdx.x] = stat;
+        // queries past T: lse = +inf makes their P (and with it dS) exactly zero
+        if (threadIdx.x < 128)
+            reinterpret_cast<float *>(sp + STAGE_BF)[threadIdx.x] =
+                threadIdx.x < 64 ? (stat_pad ? INFINITY : stat * kLog2e) : stat;
     };
     {
         TileStage<128, HD, LDKV, 512> stK, stV;
