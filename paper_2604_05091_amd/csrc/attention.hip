@@ -490,37 +490,37 @@ __global__ __launch_bounds__(64 * NW) void flash_bwd_dq_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------ backward: dK, dV
-// grid: key blocks of 128 (heaviest first = block 0) x (batch, KV head); the query heads of the group and their
+// grid: key blocks of 256 (heaviest first = block 0) x (batch, KV head); the query heads of the group and their
 // 64-query tiles >= the key block are walked as one sequence through a double-buffered LDS stage, one barrier
-// per tile.  8 waves: wave w owns the 32 keys of group w & 3 (a lane owns one key) and, of every tile, the
-// 32-query half w >> 2; the two waves of a key group sit on the same SIMD, keep separate dK / dV accumulators
-// and add them through LDS at the end.  Per tile a wave computes S^T = K Q^T and dP^T = V dO^T (16 MFMAs),
-// P = exp2(S c - lse), dS = P (dP - delta) on the vector ALU, then dV^T += dO^T P and dK^T += Q^T dS (16 MFMAs);
-// the other wave's MFMAs cover the exponentials.  The lane's K fragments live in registers, V fragments are
-// re-read from LDS for every tile: with both in registers only one wave would fit on a SIMD (measured 15 %
-// slower at 128k tokens, with a three-stage software pipeline inside the wave to make up for it).
-// LDS: K, V [128][HD + 8] | two stages of { Q, dO [64][HD + 40], lse * log2e [64], delta [64] }.
+// per tile.  8 waves, two per SIMD: wave w owns keys w*32 .. w*32+31 of the block (a lane owns one key) and works
+// through both 32-query halves of every tile: S^T = K Q^T and dP^T = V dO^T (16 MFMAs), P = exp2(S c - lse),
+// dS = P (dP - delta) on the vector ALU, then dV^T += dO^T P and dK^T += Q^T dS (16 MFMAs); the other wave's MFMAs
+// cover the exponentials.  The lane's K fragments live in registers, its V fragments are re-read from LDS for
+// every half: with both in registers only one wave fits on a SIMD (that version, with a three-stage software
+// pipeline inside the wave to make up for it, measured 25 % slower at 128k tokens).  A block of 256 keys rather
+// than 128 halves the Q / dO bytes fetched and written to LDS per MFMA: LDS takes writes at ~70 bytes per clock,
+// and with 128-key blocks the tile commits alone were 15 % of the kernel's time.
+// LDS: V [256][HD + 8] | two stages of { Q, dO [64][HD + 40], lse * log2e [64], delta [64] }.
 // Row pitch HD + 40 elements: consecutive rows are 20 banks apart, which keeps the 16-byte row reads
 // conflict-free (odd multiple of 4 banks) and lets the four rows of a transposing read overlap in only
 // 12 of 64 banks (with HD + 8 they pile up on the same 28 banks).
 constexpr int kDkdvPad = 40;
 template <int HD>
 __global__ __launch_bounds__(512) void flash_bwd_dkdv_kernel(AttnArgs a) {
-    constexpr int LDK = HD + kDkdvPad, LDKV = HD + 8, HB = HD / 32;
-    constexpr int KV_BF = 128 * LDKV;
+    constexpr int LDK = HD + kDkdvPad, LDKV = HD + 8, HB = HD / 32, KB = 256;
+    constexpr int V_BF = KB * LDKV;
     constexpr int STAGE_BF = 2 * 64 * LDK, STAGE = STAGE_BF + 256;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-    bf16_t *Kt = smem, *Vt = smem + KV_BF, *stages = smem + 2 * KV_BF;
+    bf16_t *Vt = smem, *stages = smem + V_BF;
 
-    const int T = a.T, G = a.Hq / a.Hkv;
+    const int T = a.T, G = a.Hq / a.Hkv, nkb = (T + KB - 1) / KB;
     int set, kvb;
-    if (!decode_block((T + 127) / 128, a.B * a.Hkv, &set, &kvb)) return;
-    kvb = snake8(kvb, (T + 127) / 128);
+    if (!decode_block(nkb, a.B * a.Hkv, &set, &kvb)) return;
+    kvb = snake8(kvb, nkb);
     const int b = set / a.Hkv, hk = set % a.Hkv;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hl = lane >> 5;
-    const int kg = wave & 3, par = wave >> 2;
     const int tr_off = tr_lane_offset(lane, LDK);
-    const int kv0w = kvb * 128 + kg * 32, kv = kv0w + l32;
+    const int kv0w = kvb * KB + wave * 32, kv = kv0w + l32;
 
     f32x16 dvacc[HB], dkacc[HB];
 #pragma unroll
@@ -529,7 +529,7 @@ __global__ __launch_bounds__(512) void flash_bwd_dkdv_kernel(AttnArgs a) {
         dkacc[hb] = zero16();
     }
     const float c = a.scale * kLog2e;
-    const int qt_first = (kvb * 128) / 64, n_qt = (T + 63) / 64 - qt_first;
+    const int qt_first = (kvb * KB) / 64, n_qt = (T + 63) / 64 - qt_first;
     const int total = G * n_qt;
 
     using Stage = TileStage<64, HD, LDK, 512>;
@@ -563,49 +563,47 @@ __global__ __launch_bounds__(512) void flash_bwd_dkdv_kernel(AttnArgs a) {
             reinterpret_cast<float *>(sp + STAGE_BF)[threadIdx.x] =
                 threadIdx.x < 64 ? (stat_pad ? INFINITY : stat * kLog2e) : stat;
     };
+    bf16x8 kf[HD / 16];
     {
-        TileStage<128, HD, LDKV, 512> stK, stV;
-        const int rows = T - kvb * 128;
-        stK.fetch(a.k + ((int64_t)b * T + kvb * 128) * a.ldk + (int64_t)hk * HD, a.ldk, rows, HD);
-        stV.fetch(a.v + ((int64_t)b * T + kvb * 128) * a.ldv + (int64_t)hk * HD, a.ldv, rows, HD);
+        TileStage<KB, HD, LDKV, 512> stV;
+        stV.fetch(a.v + ((int64_t)b * T + kvb * KB) * a.ldv + (int64_t)hk * HD, a.ldv, T - kvb * KB, HD);
         fetch_next();
-        stK.commit(Kt);
+        const bf16_t *kp = a.k + ((int64_t)b * T + min(kv, T - 1)) * a.ldk + (int64_t)hk * HD + hl * 8;
+#pragma unroll
+        for (int i = 0; i < HD / 16; ++i) kf[i] = load_frag_global(kp + i * 16);
         stV.commit(Vt);
         commit(0);
     }
     __syncthreads();
 
-    const bf16_t *kr = Kt + (kg * 32 + l32) * LDKV + hl * 8;
-    const bf16_t *vr = Vt + (kg * 32 + l32) * LDKV + hl * 8;
-    bf16x8 kf[HD / 16];
-#pragma unroll
-    for (int i = 0; i < HD / 16; ++i) kf[i] = *reinterpret_cast<const bf16x8 *>(kr + i * 16);
+    const bf16_t *vr = Vt + (wave * 32 + l32) * LDKV + hl * 8;
     int tq = 0;  // query tile inside the head
     for (int j = 0; j < total; ++j) {
         const bf16_t *Qs = stages + (j & 1) * STAGE, *dOs = Qs + 64 * LDK;
         const float *lses = reinterpret_cast<const float *>(Qs + STAGE_BF), *dlts = lses + 64;
-        const int q0u = (qt_first + tq) * 64 + par * 32;
+        const int q0t = (qt_first + tq) * 64;
         const bool more = j + 1 < total;
         if (more) fetch_next();
-        if (q0u + 31 >= kv0w) {  // wave-uniform: some query of the half sees some key of the group
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const int q0u = q0t + rb * 32;
+            if (q0u + 31 < kv0w) continue;  // wave-uniform: no query of the half sees a key of the wave
             f32x16 s_ = zero16(), p_ = zero16();
-            const bf16_t *qr = Qs + (par * 32 + l32) * LDK + hl * 8;
-            const bf16_t *dor = dOs + (par * 32 + l32) * LDK + hl * 8;
+            const bf16_t *qr = Qs + (rb * 32 + l32) * LDK + hl * 8;
+            const bf16_t *dor = dOs + (rb * 32 + l32) * LDK + hl * 8;
 #pragma unroll
             for (int half = 0; half < HD / 64; ++half) {
-                bf16x8 qq[4], kk[4], dd[4], vv[4];
+                bf16x8 qq[4], dd[4], vv[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    qq[i] = *reinterpret_cast<const bf16x8 *>(qr + (half * 4 + i) * 16);
-                    kk[i] = kf[half * 4 + i];
-                }
+                for (int i = 0; i < 4; ++i) qq[i] = *reinterpret_cast<const bf16x8 *>(qr + (half * 4 + i) * 16);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     dd[i] = *reinterpret_cast<const bf16x8 *>(dor + (half * 4 + i) * 16);
                     vv[i] = *reinterpret_cast<const bf16x8 *>(vr + (half * 4 + i) * 16);
                 }
 #pragma unroll
-                for (int i = 0; i < 4; ++i) s_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq[i], kk[i], s_, 0, 0, 0);
+                for (int i = 0; i < 4; ++i)
+                    s_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qq[i], kf[half * 4 + i], s_, 0, 0, 0);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) p_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dd[i], vv[i], p_, 0, 0, 0);
             }
@@ -616,7 +614,7 @@ __global__ __launch_bounds__(512) void flash_bwd_dkdv_kernel(AttnArgs a) {
             f32x16 dsacc;
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
-                const int qi = par * 32 + r4 * 8 + hl * 4;
+                const int qi = rb * 32 + r4 * 8 + hl * 4;
                 const float4 l4 = *reinterpret_cast<const float4 *>(lses + qi);
                 const float4 d4 = *reinterpret_cast<const float4 *>(dlts + qi);
                 const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
@@ -632,53 +630,21 @@ __global__ __launch_bounds__(512) void flash_bwd_dkdv_kernel(AttnArgs a) {
             // dV^T += dO^T P, dK^T += Q^T dS
 #pragma unroll
             for (int cch = 0; cch < 2; ++cch) {
-                mfma_tr_accumulate<HD, LDK>(dvacc, dOs, tr_off, par, cch, pack_frag(s_, cch));
-                mfma_tr_accumulate<HD, LDK>(dkacc, Qs, tr_off, par, cch, pack_frag(dsacc, cch));
+                mfma_tr_accumulate<HD, LDK>(dvacc, dOs, tr_off, rb, cch, pack_frag(s_, cch));
+                mfma_tr_accumulate<HD, LDK>(dkacc, Qs, tr_off, rb, cch, pack_frag(dsacc, cch));
             }
         }
         if (more) commit((j + 1) & 1);
         __syncthreads();
         tq = tq + 1 == n_qt ? 0 : tq + 1;
     }
-
-    // the two waves of a key group exchange halves: the first keeps dK, the second dV
-    {
-        float4 *red = reinterpret_cast<float4 *>(smem);  // [wave][4 * HB][lane], 16 bytes per lane
-        constexpr int NV = 4 * HB;
-        auto publish = [&](const f32x16 *acc) {
-#pragma unroll
-            for (int i = 0; i < NV; ++i) {
-                const int o = (i & 3) * 4;
-                red[(wave * NV + i) * 64 + lane] = make_float4(acc[i >> 2][o], acc[i >> 2][o + 1], acc[i >> 2][o + 2], acc[i >> 2][o + 3]);
-            }
-        };
-        auto absorb = [&](f32x16 *acc) {
-#pragma unroll
-            for (int i = 0; i < NV; ++i) {
-                const float4 t = red[((wave ^ 4) * NV + i) * 64 + lane];
-                const int o = (i & 3) * 4;
-                acc[i >> 2][o] += t.x;
-                acc[i >> 2][o + 1] += t.y;
-                acc[i >> 2][o + 2] += t.z;
-                acc[i >> 2][o + 3] += t.w;
-            }
-        };
-        if (par) publish(dkacc);
-        else publish(dvacc);
-        __syncthreads();
-        if (par) absorb(dvacc);
-        else absorb(dkacc);
-        __syncthreads();
-    }
     if (kv0w < T) {
         const int n_valid = min(32, T - kv0w);
-        if (par == 0)
-            write_owned_rows<HD>(a.dk + ((int64_t)b * T + kv0w) * a.lddk + (int64_t)hk * HD, a.lddk, dkacc, a.scale, l32,
-                                 hl, n_valid, a.rope_cos ? a.rope_cos + (int64_t)kv0w * (HD / 2) : nullptr,
-                                 a.rope_cos ? a.rope_sin + (int64_t)kv0w * (HD / 2) : nullptr, out_region<HD>(smem, wave));
-        else
-            write_owned_rows<HD>(a.dv + ((int64_t)b * T + kv0w) * a.lddv + (int64_t)hk * HD, a.lddv, dvacc, 1.0f, l32, hl,
-                                 n_valid, nullptr, nullptr, out_region<HD>(smem, wave));
+        write_owned_rows<HD>(a.dk + ((int64_t)b * T + kv0w) * a.lddk + (int64_t)hk * HD, a.lddk, dkacc, a.scale, l32, hl,
+                             n_valid, a.rope_cos ? a.rope_cos + (int64_t)kv0w * (HD / 2) : nullptr,
+                             a.rope_cos ? a.rope_sin + (int64_t)kv0w * (HD / 2) : nullptr, out_region<HD>(smem, wave));
+        write_owned_rows<HD>(a.dv + ((int64_t)b * T + kv0w) * a.lddv + (int64_t)hk * HD, a.lddv, dvacc, 1.0f, l32, hl,
+                             n_valid, nullptr, nullptr, out_region<HD>(smem, wave));
     }
 }
 
@@ -760,16 +726,16 @@ hipError_t flash_bwd_dkdv(const AttnArgs &a, hipStream_t s) {
     if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.dout) || ((uintptr_t)a.dk & 7) ||
         ((uintptr_t)a.dv & 7))
         return hipErrorInvalidValue;
-    const dim3 grid(grid_blocks((a.T + 127) / 128, a.B * a.Hkv));
-    // K, V [128][hd + 8] | two stages of Q, dO [64][hd + pad] + 64 lse + 64 delta
+    const dim3 grid(grid_blocks((a.T + 255) / 256, a.B * a.Hkv));
+    // V [256][hd + 8] | two stages of Q, dO [64][hd + pad] + 64 lse + 64 delta
     if (a.hd == 128) {
-        constexpr size_t lds = (2 * 128 * (128 + 8) + 2 * (2 * 64 * (128 + kDkdvPad))) * sizeof(bf16_t) + 2 * 512;
+        constexpr size_t lds = (256 * (128 + 8) + 2 * (2 * 64 * (128 + kDkdvPad))) * sizeof(bf16_t) + 2 * 512;
         static bool done = false;
         hipError_t e = ensure_lds(&flash_bwd_dkdv_kernel<128>, lds, &done);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(flash_bwd_dkdv_kernel<128>, grid, dim3(512), lds, s, a);
     } else {
-        constexpr size_t lds = (2 * 128 * (64 + 8) + 2 * (2 * 64 * (64 + kDkdvPad))) * sizeof(bf16_t) + 2 * 512;
+        constexpr size_t lds = (256 * (64 + 8) + 2 * (2 * 64 * (64 + kDkdvPad))) * sizeof(bf16_t) + 2 * 512;
         static bool done = false;
         hipError_t e = ensure_lds(&flash_bwd_dkdv_kernel<64>, lds, &done);
         if (e != hipSuccess) return e;
