@@ -432,7 +432,8 @@ def _attention_case(orc64, B, T, Hq, Hkv, hd, seed, out_pad=0):
 
 
 @pytest.mark.parametrize("B,T,Hq,Hkv,hd", [(2, 128, 4, 4, 64), (1, 200, 4, 2, 64), (2, 72, 2, 2, 128),
-                                           (1, 392, 5, 1, 128), (1, 8, 2, 1, 64)])
+                                           (1, 392, 5, 1, 128), (1, 8, 2, 1, 64), (1, 648, 4, 2, 128),
+                                           (2, 520, 2, 2, 64)])
 def test_flash_attention_forward_backward(orc64, B, T, Hq, Hkv, hd):
     _attention_case(orc64, B, T, Hq, Hkv, hd, seed=T + hd)
 
