@@ -530,7 +530,7 @@ mt_status head_forward_backward(mt_handle *h, const uint16_t *W, float *G, const
     hipStream_t s = h->s_comp;
     const uint16_t *wlm = W, *gf = W + (size_t)D.V * D.d;
     float *dWlm = G, *dgf = G + (size_t)D.V * D.d;
-    uint16_t *zn = h->xn, *dzn = h->dxn;
+    uint16_t *zn = h->dh1, *dzn = h->dxn;  // backward temporaries: the activation sets hold the last block's internals
     KCHK(rmsnorm_fwd(zn, x, gf, n, D.d, h->cfg.rms_eps, s));
     KCHK(transpose2d(s, wlm, h->wT, D.V, D.d, D.d, D.V));   // [d, V]
     for (int64_t c0 = 0; c0 < n; c0 += h->ce_chunk) {
@@ -1323,14 +1323,19 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     // ---- load schedule: E, 1..L, H, then per block of K layers (last block first) the layers in forward
     // order up to the block's last one (RecomputeBlock) and back down in reverse order (LocalBackward).
     // The block's last layer is recomputed and differentiated in one slot, so a block of m layers costs
-    // 2m-1 loads; with K = 1 this is the sequence E, 1..L, H, L..1.
+    // 2m-1 loads (the last block: m); with K = 1 this is the sequence E, 1..L, H, L..1.
     struct BwdSlot { int layer; bool recompute, backward; };
     std::vector<BwdSlot> bslots;
     const int K = h->K;
+    // The last block is the exception: the streaming forward has just left its internals in the activation sets
+    // (it runs those layers the way a recomputation would), so its backward starts at once.
+    const int last_lo = ((D.L - 1) / K) * K + 1;
     for (int b = (D.L - 1) / K; b >= 0; --b) {
         const int lo = b * K + 1, hi = std::min((b + 1) * K, D.L);
-        for (int l = lo; l < hi; ++l) bslots.push_back({l, true, false});
-        bslots.push_back({hi, true, true});
+        const bool live = lo == last_lo;
+        if (!live)
+            for (int l = lo; l < hi; ++l) bslots.push_back({l, true, false});
+        bslots.push_back({hi, !live, true});
         for (int l = hi - 1; l >= lo; --l) bslots.push_back({l, false, true});
     }
     const int nloads = D.L + 2 + (int)bslots.size();
@@ -1509,7 +1514,9 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
             if (s == 0) {
                 KCHK(embed_gather(h->boundary(0), W, h->tok_dev, n, D.d, sc));
             } else {
-                STEP(layer_forward(h, bind_layer(W, h->lo), h->boundary(s - 1), h->boundary(s), batch, seq, false));
+                const bool live = s >= last_lo;  // layers of the last block keep what their backward reads
+                if (live) h->select_acts(s - last_lo);
+                STEP(layer_forward(h, bind_layer(W, h->lo), h->boundary(s - 1), h->boundary(s), batch, seq, live));
             }
         }
         STEP(end_unit(s));
