@@ -11,7 +11,8 @@
  *            weights into one of two device buffers, compute, keep only h_0..h_L in HBM.
  *   Phase 2  loss anchoring:     final norm + LM head + mean cross-entropy, head gradients.
  *   Phase 3  block-wise backward: for i = L..1 StreamIn theta_i again, recompute block i
- *            from h_{i-1}, LocalBackward, Offload the fp32 gradients to the host while the
+ *            from h_{i-1} (except the last checkpoint block, whose internals the forward has
+ *            just left in the work buffers), LocalBackward, Offload the fp32 gradients to the host while the
  *            next block's weights stream in (Section 3.2: three streams, double buffering,
  *            Weights-Ready / Backward-Done / Buffer-Free events).
  *   last     AdamUpdate on the host CPU (Section 3.1, optimizer update phase).
