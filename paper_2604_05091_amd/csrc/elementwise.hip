@@ -183,12 +183,23 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(bf16_t *dx, float *par
     for (int j = threadIdx.x; j < d; j += 256) partial[(int64_t)blockIdx.x * d + j] = red[j];
 }
 
+// out[j] (+)= sum over rows of partial[r][j].  A block owns 32 columns; its 8 row groups each add every 8th row in
+// order and the 8 group sums are added in order, so the result does not depend on the launch.
 __global__ __launch_bounds__(256) void colsum_kernel(float *out, const float *partial, int nrows, int d, int accumulate) {
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= d) return;
+    __shared__ float red[8][32];
+    const int cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    const int j = blockIdx.x * 32 + cl;
     float s = 0.f;
-    for (int r = 0; r < nrows; ++r) s += partial[(int64_t)r * d + j];
-    out[j] = accumulate ? out[j] + s : s;
+    if (j < d)
+        for (int r = rg; r < nrows; r += 8) s += partial[(int64_t)r * d + j];
+    red[rg][cl] = s;
+    __syncthreads();
+    if (rg == 0 && j < d) {
+        float t = red[0][cl];
+#pragma unroll
+        for (int g = 1; g < 8; ++g) t += red[g][cl];
+        out[j] = accumulate ? out[j] + t : t;
+    }
 }
 
 // ------------------------------------------------------------------ bias gradient (column sums of a bf16 matrix)
@@ -456,7 +467,7 @@ hipError_t rmsnorm_bwd(bf16_t *dx_out, float *dgain, const bf16_t *dy, const bf1
                            n, d, eps);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(d, 256)), dim3(256), 0, s, dgain, partial, (int)grid, d,
+    hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(d, 32)), dim3(256), 0, s, dgain, partial, (int)grid, d,
                        accumulate_dgain);
     return hipGetLastError();
 }
@@ -470,7 +481,7 @@ hipError_t bias_grad(float *db, const bf16_t *x, int64_t ld, int64_t n, int32_t 
                        ld, n, cols, rpb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(cols, 256)), dim3(256), 0, s, db, ws, kBiasGradRowBlocks, cols, 0);
+    hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(cols, 32)), dim3(256), 0, s, db, ws, kBiasGradRowBlocks, cols, 0);
     return hipGetLastError();
 }
 
