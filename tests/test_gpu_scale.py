@@ -52,9 +52,35 @@ def test_many_tokens_take_the_large_grid_kernels_and_match_oracle(orc64, qkv_bia
     check_against_oracle(orc64, shape, B, T, params, tok, lab, loss, grads)
 
 
+
+def _check_dk_dv_of_late_keys(qkv, dout, DQKV, r0, T, nq, h, hd, scale, back):
+    """dK and dV rows of keys close to the end of a sequence (T - 1 - d for d in back) from the definition: only the
+    queries from the key to the end see it.  S = Q K^T scale (causal), P = softmax, dP = dO V^T,
+    dS = P (dP - rowsum(dO O)), dV = P^T dO, dK = scale dS^T Q, in fp64 on the bf16 inputs."""
+    q0 = T - 1 - max(back)
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    K = f64(qkv[r0:r0 + T, nq + h * hd: nq + (h + 1) * hd])
+    V = f64(qkv[r0:r0 + T, 2 * nq + h * hd: 2 * nq + (h + 1) * hd])
+    Q = f64(qkv[r0 + q0:r0 + T, h * hd:(h + 1) * hd])
+    dO = f64(dout[r0 + q0:r0 + T, h * hd:(h + 1) * hd])
+    S = Q @ K.T * scale
+    S[np.arange(T)[None, :] > (q0 + np.arange(T - q0))[:, None]] = -np.inf
+    P = np.exp(S - S.max(axis=1, keepdims=True))
+    P /= P.sum(axis=1, keepdims=True)
+    dS = P * (dO @ V.T - np.sum(dO * (P @ V), axis=1)[:, None])
+    for d in back:
+        k = T - 1 - d
+        dv_ref, dk_ref = P[:, k] @ dO, scale * (dS[:, k] @ Q)
+        dv = DQKV[r0 + k, 2 * nq + h * hd: 2 * nq + (h + 1) * hd].float().cpu().numpy()
+        dk = DQKV[r0 + k, nq + h * hd: nq + (h + 1) * hd].float().cpu().numpy()
+        assert rel_l2(dv, dv_ref) < 3e-2 and cosine(dv, dv_ref) > 0.999, (h, k, rel_l2(dv, dv_ref))
+        assert rel_l2(dk, dk_ref) < 3e-2 and cosine(dk, dk_ref) > 0.999, (h, k, rel_l2(dk, dk_ref))
+
+
 def test_attention_rows_at_128k_context(orc64):
     """Forward output and dq of sampled query rows at T = 131072 (one sequence, 7B head layout reduced to
-    2 query heads sharing nothing): each row needs only its own keys, so the oracle can do it row by row."""
+    2 query heads sharing nothing): each row needs only its own keys, so the oracle can do it row by row; dK and dV
+    of keys near the end of the sequence from the definition."""
     L = mt.lib()
     T, Hq, Hkv, hd = 131072, 2, 2, 128
     nq = Hq * hd
@@ -86,6 +112,8 @@ def test_attention_rows_at_128k_context(orc64):
                 assert np.max(np.abs(dq)) < 1e-5 and np.all(dq_ref == 0)
             else:
                 assert rel_l2(dq, dq_ref) < 3e-2 and cosine(dq, dq_ref) > 0.999, (h, t, rel_l2(dq, dq_ref))
+    # dK, dV of keys in the last key block (owned by different waves of the dK/dV workgroup)
+    _check_dk_dv_of_late_keys(qkv, dout, DQKV, 0, T, nq, 1, hd, scale, (0, 37, 140, 255))
 
 
 # ----------------------------------------------------------------------------- full-size launches, sampled outputs
@@ -163,3 +191,5 @@ def test_attention_at_benchmark_shape_sampled_rows(orc64):
     dv = DQKV[r0 + t, 2 * nq + h * hd: 2 * nq + (h + 1) * hd].float().cpu().numpy()
     dk = DQKV[r0 + t, nq + h * hd: nq + (h + 1) * hd].float().cpu().numpy()
     assert rel_l2(dv, dv_ref) < 3e-2 and rel_l2(dk, dk_ref) < 3e-2, (rel_l2(dv, dv_ref), rel_l2(dk, dk_ref))
+    # and keys further back, which several queries see, from the definition
+    _check_dk_dv_of_late_keys(qkv, dout, DQKV, 4 * T, T, nq, 11, hd, scale, (0, 33, 100, 250, 300))
