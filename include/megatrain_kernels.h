@@ -93,6 +93,17 @@ size_t mt_k_rmsnorm_bwd_ws_bytes(int32_t d);
 int32_t mt_k_rmsnorm_bwd(uint16_t *dx, float *dgain, const uint16_t *dy, const uint16_t *x, const uint16_t *gain,
                          const uint16_t *dres, void *ws, int64_t n, int32_t d, float eps, void *stream);
 
+/* mt_k_rmsnorm_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments without ws, same results bit for bit.  The per-block
+ * partial gain gradients go to a device array that is part of the library image (512 * 8192 floats = 16 MiB on
+ * every device the library runs on, held until the process ends); its address is looked up once per device at the
+ * first call there.  The call allocates nothing.  d <= MT_K_RMSNORM_BWD_NOALLOC_MAX_D, otherwise MT_ERR_UNSUPPORTED
+ * and nothing is launched.  All calls on one device share the array: calls that overlap on one device (different
+ * streams or threads) race; calls on one stream are ordered and safe.  Nothing in it needs to start at zero. */
+#define MT_K_RMSNORM_BWD_NOALLOC_MAX_D 8192
+int32_t mt_k_rmsnorm_bwd_noalloc(uint16_t *dx, float *dgain, const uint16_t *dy, const uint16_t *x, const uint16_t *gain,
+                                 const uint16_t *dres, int64_t n, int32_t d, float eps, void *stream);
+
 /* Fill cos/sin tables [T, hd/2] fp32 on the HOST: angle = t * base^(-2j/hd), computed in double. */
 int32_t mt_k_rope_table(float *host_cos, float *host_sin, int32_t T, int32_t hd, double base);
 /* Rotate in place the first n_heads heads (hd wide, hd % 16 == 0) of every row of x [n, ld];

@@ -106,6 +106,7 @@ def lib():
         "mt_k_rmsnorm_fwd": ([p16, p16, p16, c_int64, c_int32, c_float, c_void_p], c_int32),
         "mt_k_rmsnorm_bwd_ws_bytes": ([c_int32], c_size_t),
         "mt_k_rmsnorm_bwd": ([p16, pf, p16, p16, p16, p16, c_void_p, c_int64, c_int32, c_float, c_void_p], c_int32),
+        "mt_k_rmsnorm_bwd_noalloc": ([p16, pf, p16, p16, p16, p16, c_int64, c_int32, c_float, c_void_p], c_int32),
         "mt_k_rope_table": ([pf, pf, c_int32, c_int32, c_double], c_int32),
         "mt_k_rope": ([p16, c_int64, c_int64, c_int32, c_int32, c_int32, pf, pf, c_int32, c_void_p], c_int32),
         "mt_k_swiglu_fwd": ([p16, p16, c_int64, c_int32, c_void_p], c_int32),

@@ -144,6 +144,11 @@ hipError_t rmsnorm_bwd(bf16_t *dx_out, float *dgain, const bf16_t *dy, const bf1
                        const bf16_t *dres, float *partial, int64_t n, int32_t d, float eps, hipStream_t s,
                        int accumulate_dgain = 0);
 
+// The same with the workspace in a file-scope device array of the library (d <= 8192): no allocation, but calls that
+// overlap on one device share that array and race.
+hipError_t rmsnorm_bwd_static(bf16_t *dx_out, float *dgain, const bf16_t *dy, const bf16_t *x, const bf16_t *gain,
+                              const bf16_t *dres, int64_t n, int32_t d, float eps, hipStream_t s);
+
 // In-place rotation of the first n_heads heads of each row of x [n, ld]; cos/sin tables [T, hd/2] fp32;
 // position of row r is r % T; sign +1 forward, -1 inverse.
 hipError_t rope_inplace(bf16_t *x, int64_t ld, int64_t n, int32_t T, int32_t n_heads, int32_t hd, const float *cs,

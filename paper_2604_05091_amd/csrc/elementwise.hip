@@ -4,6 +4,8 @@
 // All of them move 16 bytes per lane per access (8 bf16 or 4 fp32), do their
 // arithmetic in fp32 and reduce inside a 64-lane wave with cross-lane shuffles.
 // None uses atomics, so every result is bit-reproducible from run to run.
+#include <atomic>
+
 #include "common.h"
 
 namespace mt {
@@ -470,6 +472,32 @@ hipError_t rmsnorm_bwd(bf16_t *dx_out, float *dgain, const bf16_t *dy, const bf1
     hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(d, 32)), dim3(256), 0, s, dgain, partial, (int)grid, d,
                        accumulate_dgain);
     return hipGetLastError();
+}
+
+// ---- RMSNorm backward for callers that may not allocate: the partial-gain-gradient workspace is a file-scope
+// device array instead of a caller buffer.  Its name is only a host-side handle; the device address is looked up
+// once per device (each device holds its own copy) and passed to the kernels like any other workspace.
+constexpr int kStaticNormMaxD = 8192;
+static __device__ __align__(256) float scratch[(size_t)kNormBwdBlocks * kStaticNormMaxD];  // 16 MiB per device
+constexpr int kMaxDevices = 64;
+
+hipError_t rmsnorm_bwd_static(bf16_t *dx_out, float *dgain, const bf16_t *dy, const bf16_t *x, const bf16_t *gain,
+                              const bf16_t *dres, int64_t n, int32_t d, float eps, hipStream_t s) {
+    static std::atomic<float *> scratch_of_device[kMaxDevices];
+    if (d <= 0 || d > kStaticNormMaxD) return hipErrorInvalidValue;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    float *ptr = scratch_of_device[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        scratch_of_device[dev].store(ptr, std::memory_order_release);  // same value from every thread
+    }
+    // every partial row that the column sum reads is written by the first kernel of this call: nothing to clear
+    return rmsnorm_bwd(dx_out, dgain, dy, x, gain, dres, ptr, n, d, eps, s, 0);
 }
 
 size_t bias_grad_ws_floats(int32_t cols) { return (size_t)kBiasGradRowBlocks * (size_t)cols; }

@@ -133,6 +133,15 @@ int32_t mt_k_rmsnorm_bwd(uint16_t *dx, float *dgain, const uint16_t *dy, const u
     return to_status(rmsnorm_bwd(dx, dgain, dy, x, gain, dres, (float *)ws, n, d, eps, S(stream)));
 }
 
+int32_t mt_k_rmsnorm_bwd_noalloc(uint16_t *dx, float *dgain, const uint16_t *dy, const uint16_t *x, const uint16_t *gain,
+                                 const uint16_t *dres, int64_t n, int32_t d, float eps, void *stream) {
+    if (!dx || !dgain || !dy || !x || !gain) return MT_ERR_INVALID_ARG;
+    if (!al16(dx) || !al16(dy) || !al16(x) || !al16(gain) || !al16(dres)) return MT_ERR_INVALID_ARG;
+    if (n <= 0 || d <= 0 || (d & 7)) return MT_ERR_INVALID_ARG;
+    if (d > MT_K_RMSNORM_BWD_NOALLOC_MAX_D) return MT_ERR_UNSUPPORTED;  // beyond the static workspace
+    return to_status(rmsnorm_bwd_static(dx, dgain, dy, x, gain, dres, n, d, eps, S(stream)));
+}
+
 int32_t mt_k_rope_table(float *host_cos, float *host_sin, int32_t T, int32_t hd, double base) {
     if (!host_cos || !host_sin || T <= 0 || hd <= 0 || (hd & 1) || !(base > 0)) return MT_ERR_INVALID_ARG;
     rope_table(host_cos, host_sin, T, hd, base);
