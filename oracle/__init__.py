@@ -72,6 +72,8 @@ class Oracle:
         L.orc_attention_bwd.argtypes = [vp] * 7 + [i64] * 5
         L.orc_attention_row.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64]
         L.orc_attention_row.restype = None
+        L.orc_attention_key_row.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64]
+        L.orc_attention_key_row.restype = None
         L.orc_swiglu_fwd.argtypes = [vp, vp, vp, i64]
         L.orc_swiglu_bwd.argtypes = [vp, vp, vp, vp, vp, i64]
         L.orc_cross_entropy.argtypes = [vp, vp, vp, vp, i64, i64]
@@ -153,6 +155,16 @@ class Oracle:
         self.lib.orc_attention_row(a.ctypes.data, dq.ctypes.data, q.ctypes.data, da.ctypes.data, k.ctypes.data,
                                    v.ctypes.data, k.shape[0], k.shape[1])
         return a, dq
+
+    def attention_key_row(self, q, da, k, v, u):
+        """One key row of one head of one sequence: q, da, k, v [T, hd]; returns (dk_u, dv_u), the gradients key u
+        and its value receive from the queries u .. T-1."""
+        q, da, k, v = self.arr(q), self.arr(da), self.arr(k), self.arr(v)
+        assert q.shape == da.shape == k.shape == v.shape and 0 <= u < q.shape[0]
+        dk, dv = np.empty(q.shape[1], self.dtype), np.empty(q.shape[1], self.dtype)
+        self.lib.orc_attention_key_row(dk.ctypes.data, dv.ctypes.data, q.ctypes.data, da.ctypes.data, k.ctypes.data,
+                                       v.ctypes.data, q.shape[0], q.shape[1], u)
+        return dk, dv
 
     def swiglu_fwd(self, gate, up):
         gate, up = self.arr(gate), self.arr(up)

@@ -310,6 +310,60 @@ void orc_attention_row(real *a, real *dq, const real *q, const real *da, const r
     free(p);
 }
 
+/* One key row of the same attention (one head of one sequence): the gradients that key u and its value receive
+ * from every query that sees it, t = u .. T-1.  q, da, k, v are [T, hd] contiguous (rows before u of q and da are
+ * not read).  For each such query: p_t = softmax over keys 0..t, a_t = sum_w p_tw v_w,
+ * dS_tu = p_tu (da_t.v_u - da_t.a_t);  dv_u = sum_t p_tu da_t,  dk_u = sum_t dS_tu q_t / sqrt(hd).
+ * Costs (T-u) full softmax rows, so it reaches keys near the end of very long sequences. */
+void orc_attention_key_row(real *dk, real *dv, const real *q, const real *da, const real *k, const real *v, int64_t T,
+                           int64_t hd, int64_t u) {
+    const real scale = (real)(1.0 / sqrt((double)hd));
+    const int64_t nq = T - u;
+    real *pu = (real *)malloc(sizeof(real) * (size_t)nq);  /* p_tu of query t = u + i */
+    real *ds = (real *)malloc(sizeof(real) * (size_t)nq);  /* dS_tu / sqrt(hd) */
+    /* the queries are independent of each other */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < nq; ++i) {
+        const int64_t t = u + i;
+        const real *qt = q + t * hd, *dat = da + t * hd;
+        real *p = (real *)malloc(sizeof(real) * (size_t)(t + 1));
+        real *a = (real *)malloc(sizeof(real) * (size_t)hd);
+        real mx = -INFINITY, den = 0;
+        for (int64_t w = 0; w <= t; ++w) {
+            real s = 0;
+            for (int64_t j = 0; j < hd; ++j) s += qt[j] * k[w * hd + j];
+            p[w] = s * scale;
+            if (p[w] > mx) mx = p[w];
+        }
+        for (int64_t w = 0; w <= t; ++w) {
+            p[w] = (real)exp((double)(p[w] - mx));
+            den += p[w];
+        }
+        for (int64_t j = 0; j < hd; ++j) a[j] = 0;
+        for (int64_t w = 0; w <= t; ++w) {
+            p[w] /= den;
+            for (int64_t j = 0; j < hd; ++j) a[j] += p[w] * v[w * hd + j];
+        }
+        real dp_u = 0, delta = 0;
+        for (int64_t j = 0; j < hd; ++j) {
+            dp_u += dat[j] * v[u * hd + j];
+            delta += dat[j] * a[j];
+        }
+        pu[i] = p[u];
+        ds[i] = p[u] * (dp_u - delta) * scale;
+        free(a);
+        free(p);
+    }
+    for (int64_t j = 0; j < hd; ++j) dk[j] = dv[j] = 0;
+    for (int64_t i = 0; i < nq; ++i)
+        for (int64_t j = 0; j < hd; ++j) {
+            dv[j] += pu[i] * da[(u + i) * hd + j];
+            dk[j] += ds[i] * q[(u + i) * hd + j];
+        }
+    free(ds);
+    free(pu);
+}
+
 /* ------------------------------------------------------------------ SwiGLU
  * s = gate * sigmoid(gate) * up */
 void orc_swiglu_fwd(real *s, const real *gate, const real *up, int64_t n) {
@@ -517,22 +571,6 @@ static void block_backward(real *dx, const real *dy, const real *x, const real *
 
     free(ds); free(dgt); free(dup); free(dyn); free(tmp); free(dh1);
     free(da); free(dq); free(dk); free(dv); free(dxn);
-}
-
-/* Exposed for per-kernel parity tests: one block forward (returns y and fills the
- * caller's cache arrays) and one block backward from a given cache. */
-void orc_block_forward(real *y, const real *x, const real *const *w, real *const *cache10, const orc_cfg *cf,
-                       int64_t B, int64_t T) {
-    block_cache c = {cache10[0], cache10[1], cache10[2], cache10[3], cache10[4],
-                     cache10[5], cache10[6], cache10[7], cache10[8], cache10[9]};
-    block_forward(y, x, w, &c, cf, B, T);
-}
-
-void orc_block_backward(real *dx, const real *dy, const real *x, const real *const *w, real *const *gw,
-                        real *const *cache10, const orc_cfg *cf, int64_t B, int64_t T) {
-    block_cache c = {cache10[0], cache10[1], cache10[2], cache10[3], cache10[4],
-                     cache10[5], cache10[6], cache10[7], cache10[8], cache10[9]};
-    block_backward(dx, dy, x, w, gw, &c, cf, B, T);
 }
 
 /* ------------------------------------------------------------------ the training step

@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import paper_2604_05091_amd as mt
-from gpu_util import bf16_round, cosine, dev_bf16, dev_f32, dev_i32, host, ok, rel_l2
+from gpu_util import assert_rows_close, bf16_round, cosine, dev_bf16, dev_f32, dev_i32, host, ok, rel_l2
 
 pytestmark = pytest.mark.gpu
 L = None
@@ -25,6 +25,11 @@ def _lib():
 
 
 BF16_TOL = 6e-3   # rel. L2 of a tensor whose elements carry one bf16 rounding (2^-9 = 2e-3 each) plus fp32 sums
+# Per-row bounds (gpu_util.rows_close), as a fraction of the row's largest reference element: one bf16 rounding of
+# that element is 2^-9; 2^-7 leaves room for fp32 summation order.  Two roundings deep (an input of the last step
+# was itself rounded): 2^-6.  Attention backward (P, dS and O each pass through bf16): 2^-5 plus 2^-9 of the
+# tensor's largest element for rows that are nearly zero by cancellation.
+ROW1, ROW2, ROW_ATT_BWD, ROW_FLOOR = 2.0 ** -7, 2.0 ** -6, 2.0 ** -5, 2.0 ** -9
 
 
 # ----------------------------------------------------------------------------- GEMM
@@ -53,6 +58,7 @@ def test_gemm_nt_residual_strides_fp32_accumulate(orc64):
     ok(L.mt_k_gemm_nt(A.data_ptr(), lda, B.data_ptr(), ldb, C.data_ptr(), ldc, R.data_ptr(), N, M, N, K, 0, 0, None))
     got = host(C)
     assert rel_l2(got[:, :N], ref + r) < BF16_TOL
+    assert_rows_close(got[:, :N], ref + r, ROW1, what="gemm + residual")
     assert np.all(got[:, N:] == 0)              # nothing written outside the N columns
     # fp32 output, then accumulate a second product on top
     C32 = torch.zeros((M, N), dtype=torch.float32, device="cuda")
@@ -76,12 +82,15 @@ def test_gemm_large_grid_kernel_all_epilogues(orc64, M, N, K):
     ok(L.mt_k_gemm_nt(A.data_ptr(), lda, B.data_ptr(), ldb, C.data_ptr(), ldc, R.data_ptr(), ldr, M, N, K, 0, 0, None))
     got = host(C)
     assert rel_l2(got[:, :N], ref + r_full[:, :N]) < BF16_TOL
+    assert_rows_close(got[:, :N], ref + r_full[:, :N], ROW1, what="large-grid gemm + residual")
     assert np.all(got[:, N:] == 0)
     C32 = torch.full((M, N), 3.0, dtype=torch.float32, device="cuda")
     ok(L.mt_k_gemm_nt(A.data_ptr(), lda, B.data_ptr(), ldb, C32.data_ptr(), N, None, 0, M, N, K, 1, 0, None))
     assert rel_l2(host(C32), ref) < 2e-6
+    assert_rows_close(host(C32), ref, 1e-5, what="large-grid gemm fp32")
     ok(L.mt_k_gemm_nt(A.data_ptr(), lda, B.data_ptr(), ldb, C32.data_ptr(), N, None, 0, M, N, K, 1, 1, None))
     assert rel_l2(host(C32), 2 * ref) < 2e-6
+    assert_rows_close(host(C32), 2 * ref, 1e-5, what="large-grid gemm fp32 accumulate")
 
 
 @pytest.mark.parametrize("M,N,K", [(300, 200, 136), (4100, 3080, 128)])
@@ -95,6 +104,7 @@ def test_gemm_bias_epilogue_and_bias_gradient(orc64, M, N, K):
     C = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
     ok(L.mt_k_gemm_nt_bias(A.data_ptr(), K, B.data_ptr(), K, C.data_ptr(), N, BI.data_ptr(), M, N, K, None))
     assert rel_l2(host(C), ref) < BF16_TOL
+    assert_rows_close(host(C), ref, ROW1, what="gemm + bias")
     ws = torch.empty(L.mt_k_bias_grad_ws_bytes(N) // 4, dtype=torch.float32, device="cuda")
     DB = torch.full((N,), 5.0, dtype=torch.float32, device="cuda")
     ok(L.mt_k_bias_grad(DB.data_ptr(), C.data_ptr(), N, M, N, ws.data_ptr(), None))
@@ -114,8 +124,10 @@ def test_gemm_token_major_weight_gradient(orc64, n, out, inn):
     DW = torch.full((out, inn), 7.0, dtype=torch.float32, device="cuda")
     ok(L.mt_k_gemm_tn(DY.data_ptr(), ldy, X.data_ptr(), ldx, DW.data_ptr(), inn, out, inn, n, 0, None))
     assert rel_l2(host(DW), ref) < 5e-6
+    assert_rows_close(host(DW), ref, 2e-5, what="token-major weight gradient")
     ok(L.mt_k_gemm_tn(DY.data_ptr(), ldy, X.data_ptr(), ldx, DW.data_ptr(), inn, out, inn, n, 1, None))
     assert rel_l2(host(DW), 2 * ref) < 5e-6
+    assert_rows_close(host(DW), 2 * ref, 2e-5, what="token-major weight gradient, accumulate")
     assert L.mt_k_gemm_tn(DY.data_ptr(), ldy, X.data_ptr(), ldx, DW.data_ptr(), inn, out, inn, n - 8, 0, None) == -2
 
 
@@ -132,6 +144,7 @@ def test_gemm_weight_gradient_with_split_reduction(orc64, n, out, inn, split):
     ok(L.mt_k_gemm_tn_split(DY.data_ptr(), out, X.data_ptr(), inn, DW.data_ptr(), inn, out, inn, n, 0, split, WS.data_ptr(), None))
     first = DW.clone()
     assert rel_l2(host(DW), ref) < 5e-6
+    assert_rows_close(host(DW), ref, 2e-5, what="split weight gradient")
     ok(L.mt_k_gemm_tn_split(DY.data_ptr(), out, X.data_ptr(), inn, DW.data_ptr(), inn, out, inn, n, 1, split, WS.data_ptr(), None))
     assert rel_l2(host(DW), 2 * ref) < 5e-6
     DW2 = torch.zeros((out, inn), dtype=torch.float32, device="cuda")
@@ -201,6 +214,7 @@ def test_rmsnorm_forward_backward(orc64, n, d):
     Y = torch.empty_like(X)
     ok(L.mt_k_rmsnorm_fwd(Y.data_ptr(), X.data_ptr(), G.data_ptr(), n, d, 1e-5, None))
     assert rel_l2(host(Y), orc64.rmsnorm_fwd(x, g, 1e-5)) < BF16_TOL
+    assert_rows_close(host(Y), orc64.rmsnorm_fwd(x, g, 1e-5), ROW1, what="rmsnorm forward")
     dx_ref, dg_ref = orc64.rmsnorm_bwd(dy, x, g, 1e-5)
     ws = torch.empty(L.mt_k_rmsnorm_bwd_ws_bytes(d) // 4, dtype=torch.float32, device="cuda")
     DX = torch.empty_like(X)
@@ -208,10 +222,13 @@ def test_rmsnorm_forward_backward(orc64, n, d):
     ok(L.mt_k_rmsnorm_bwd(DX.data_ptr(), DG.data_ptr(), DY.data_ptr(), X.data_ptr(), G.data_ptr(), DR.data_ptr(),
                           ws.data_ptr(), n, d, 1e-5, None))
     assert rel_l2(host(DX), dx_ref + dres) < BF16_TOL
+    assert_rows_close(host(DX), dx_ref + dres, ROW1, what="rmsnorm backward + residual")
     assert rel_l2(host(DG), dg_ref) < 1e-5
+    assert_rows_close(host(DG), dg_ref, 1e-5, what="rmsnorm gain gradient")
     ok(L.mt_k_rmsnorm_bwd(DX.data_ptr(), DG.data_ptr(), DY.data_ptr(), X.data_ptr(), G.data_ptr(), None,
                           ws.data_ptr(), n, d, 1e-5, None))
     assert rel_l2(host(DX), dx_ref) < BF16_TOL
+    assert_rows_close(host(DX), dx_ref, ROW1, what="rmsnorm backward")
 
 
 def test_rmsnorm_backward_many_rows_gain_reduction(orc64):
@@ -225,6 +242,8 @@ def test_rmsnorm_backward_many_rows_gain_reduction(orc64):
     ok(L.mt_k_rmsnorm_bwd(DX.data_ptr(), DG.data_ptr(), DY.data_ptr(), X.data_ptr(), G.data_ptr(), None,
                           ws.data_ptr(), n, d, 1e-5, None))
     assert rel_l2(host(DG), dg_ref) < 1e-5 and rel_l2(host(DX), dx_ref) < BF16_TOL
+    assert_rows_close(host(DX), dx_ref, ROW1, what="rmsnorm backward, 5000 rows")
+    assert_rows_close(host(DG), dg_ref, 2e-5, what="rmsnorm gain gradient, 5000 rows")
 
 
 # ----------------------------------------------------------------------------- RoPE
@@ -241,6 +260,7 @@ def test_rope_forward_and_inverse(orc64, hd, base):
     got = host(X)
     ref = orc64.rope(x[:, :H * hd], B, T, H, hd, base, +1)
     assert rel_l2(got[:, :H * hd], ref) < BF16_TOL
+    assert_rows_close(got[:, :H * hd], ref, ROW1, width=hd, what="rope")
     assert np.array_equal(got[:, H * hd:], x[:, H * hd:])       # columns after the heads untouched
     ok(L.mt_k_rope(X.data_ptr(), ld, B * T, T, H, hd, CS.data_ptr(), SN.data_ptr(), -1, None))
     assert rel_l2(host(X)[:, :H * hd], x[:, :H * hd]) < 2 * BF16_TOL
@@ -273,6 +293,7 @@ def test_gemm_with_rotary_embedding_in_the_store(orc64, M, N, K, T, rope_cols, w
     got = host(C)
     assert rel_l2(got, ref) < BF16_TOL
     assert rel_l2(got[:, rope_cols:], lin[:, rope_cols:]) < BF16_TOL
+    assert_rows_close(got, ref, ROW1, width=hd, what="gemm with rotary store")
     # a grid too small for the kernel that rotates, or heads that do not line up: refused, nothing silently skipped
     assert L.mt_k_gemm_nt_rope(A.data_ptr(), K, B.data_ptr(), K, C.data_ptr(), N, None, CS.data_ptr(), SN.data_ptr(), T,
                                rope_cols, 256, N, K, None) == -2
@@ -296,6 +317,7 @@ def test_gemm_with_swiglu_in_the_store(orc64, M, F, K, keep_gu):
     ok(L.mt_k_gemm_nt_swiglu(A.data_ptr(), K, W.data_ptr(), K, GU.data_ptr() if keep_gu else None, 2 * F, S.data_ptr(), F,
                              M, F, K, None))
     assert rel_l2(host(S), s_ref) < 2 * BF16_TOL
+    assert_rows_close(host(S), s_ref, ROW2, what="gemm with SwiGLU store")
     GU2 = torch.zeros((M, 2 * F), dtype=torch.bfloat16, device="cuda")
     S2 = torch.zeros((M, F), dtype=torch.bfloat16, device="cuda")
     ok(L.mt_k_gemm_nt(A.data_ptr(), K, W.data_ptr(), K, GU2.data_ptr(), 2 * F, None, 0, M, 2 * F, K, 0, 0, None))
@@ -304,6 +326,7 @@ def test_gemm_with_swiglu_in_the_store(orc64, M, F, K, keep_gu):
     if keep_gu:
         assert torch.equal(GU, GU2)
         assert rel_l2(host(GU), gu_ref) < BF16_TOL
+        assert_rows_close(host(GU), gu_ref, ROW1, what="gate|up next to the SwiGLU store")
     assert L.mt_k_gemm_nt_swiglu(A.data_ptr(), K, W.data_ptr(), K, None, 0, S.data_ptr(), F, 256, F, K, None) == -2
     assert L.mt_k_gemm_nt_swiglu(A.data_ptr(), K, W.data_ptr(), K, None, 0, S.data_ptr(), F - 64, M, F - 64, K, None) == -2
 
@@ -322,6 +345,8 @@ def test_gemm_with_swiglu_backward_in_the_store(orc64, M, F, K):
     ok(L.mt_k_gemm_nt_swiglu_bwd(A.data_ptr(), K, W.data_ptr(), K, DGU.data_ptr(), 2 * F, GU.data_ptr(), 2 * F, M, F, K, None))
     got = host(DGU)
     assert rel_l2(got[:, :F], dg_ref) < 2 * BF16_TOL and rel_l2(got[:, F:], du_ref) < 2 * BF16_TOL
+    assert_rows_close(got[:, :F], dg_ref, ROW2, what="SwiGLU-backward store, dgate")
+    assert_rows_close(got[:, F:], du_ref, ROW2, what="SwiGLU-backward store, dup")
     DS = torch.zeros((M, F), dtype=torch.bfloat16, device="cuda")
     DGU2 = torch.zeros((M, 2 * F), dtype=torch.bfloat16, device="cuda")
     ok(L.mt_k_gemm_nt(A.data_ptr(), K, W.data_ptr(), K, DS.data_ptr(), F, None, 0, M, F, K, 0, 0, None))
@@ -340,11 +365,14 @@ def test_swiglu_forward_backward(orc64):
     S = torch.empty((n, F), dtype=torch.bfloat16, device="cuda")
     ok(L.mt_k_swiglu_fwd(S.data_ptr(), GU.data_ptr(), n, F, None))
     assert rel_l2(host(S), orc64.swiglu_fwd(gu[:, :F], gu[:, F:])) < BF16_TOL
+    assert_rows_close(host(S), orc64.swiglu_fwd(gu[:, :F], gu[:, F:]), ROW1, what="swiglu forward")
     DGU = torch.empty_like(GU)
     ok(L.mt_k_swiglu_bwd(DGU.data_ptr(), DS.data_ptr(), GU.data_ptr(), n, F, None))
     dg, du = orc64.swiglu_bwd(ds, gu[:, :F], gu[:, F:])
     got = host(DGU)
     assert rel_l2(got[:, :F], dg) < BF16_TOL and rel_l2(got[:, F:], du) < BF16_TOL
+    assert_rows_close(got[:, :F], dg, ROW1, what="swiglu backward, dgate")
+    assert_rows_close(got[:, F:], du, ROW1, what="swiglu backward, dup")
 
 
 # ----------------------------------------------------------------------------- embedding
@@ -387,6 +415,17 @@ def test_cross_entropy(orc64, n, V):
     assert abs(host(out)[0] - loss_ref) < 1e-5 * abs(loss_ref)
     got = host(DZ)
     assert rel_l2(got, dl_ref) < BF16_TOL
+    # every element: the fp32 value (softmax - onehot) / n rounded once to bf16
+    assert (np.abs(got - dl_ref) <= 2.0 ** -8 * np.abs(dl_ref) + 1e-12).all()
+    # every row's loss term
+    lr = host(LR)
+    for r in range(n):
+        if y[r] >= 0:
+            zz = z[r].astype(np.float64)
+            want = np.log(np.exp(zz - zz.max()).sum()) + zz.max() - zz[y[r]]
+            assert abs(lr[r] - want) <= 1e-5 * max(1.0, abs(want)), r
+        else:
+            assert lr[r] == 0
     assert np.all(got[1] == 0)
 
 
@@ -408,6 +447,7 @@ def _attention_case(orc64, B, T, Hq, Hkv, hd, seed, out_pad=0):
     ok(L.mt_k_flash_fwd(Op.data_ptr(), ldo, LSE.data_ptr(), pq, ld, pk, ld, pv, ld, B, T, Hq, Hkv, hd, scale, None))
     a_ref = orc64.attention_fwd(q, k, v, B, T, Hq, Hkv, hd)
     assert rel_l2(host(Op)[:, :nq], a_ref) < BF16_TOL
+    assert_rows_close(host(Op)[:, :nq], a_ref, ROW2, width=hd, what="attention forward (per token and head)")
     assert not host(Op)[:, nq:].any()
     O = Op[:, :nq].contiguous()
     # log-sum-exp of the first and last row of head 0: lse_0 = s_00, lse_last from the definition
@@ -429,6 +469,9 @@ def _attention_case(orc64, B, T, Hq, Hkv, hd, seed, out_pad=0):
     assert rel_l2(got[:, :nq], dq_ref) < 2e-2 and cosine(got[:, :nq], dq_ref) > 0.9995
     assert rel_l2(got[:, nq:nq + nkv], dk_ref) < 2e-2 and cosine(got[:, nq:nq + nkv], dk_ref) > 0.9995
     assert rel_l2(got[:, nq + nkv:ld], dv_ref) < 1e-2 and cosine(got[:, nq + nkv:ld], dv_ref) > 0.9995
+    assert_rows_close(got[:, :nq], dq_ref, ROW_ATT_BWD, ROW_FLOOR, width=hd, what="attention dq (per token and head)")
+    assert_rows_close(got[:, nq:nq + nkv], dk_ref, ROW_ATT_BWD, ROW_FLOOR, width=hd, what="attention dk")
+    assert_rows_close(got[:, nq + nkv:ld], dv_ref, ROW_ATT_BWD, ROW_FLOOR, width=hd, what="attention dv")
 
 
 @pytest.mark.parametrize("B,T,Hq,Hkv,hd", [(2, 128, 4, 4, 64), (1, 200, 4, 2, 64), (2, 72, 2, 2, 128),
@@ -474,6 +517,9 @@ def test_flash_attention_backward_with_rotary_backward_in_the_store(orc64, B, T,
     assert rel_l2(got[:, :nq], dq_ref) < 2e-2 and cosine(got[:, :nq], dq_ref) > 0.9995
     assert rel_l2(got[:, nq:nq + nkv], dk_ref) < 2e-2 and cosine(got[:, nq:nq + nkv], dk_ref) > 0.9995
     assert rel_l2(got[:, nq + nkv:], dv_ref) < 1e-2 and cosine(got[:, nq + nkv:], dv_ref) > 0.9995
+    assert_rows_close(got[:, :nq], dq_ref, ROW_ATT_BWD, ROW_FLOOR, width=hd, what="attention dq with rotary backward")
+    assert_rows_close(got[:, nq:nq + nkv], dk_ref, ROW_ATT_BWD, ROW_FLOOR, width=hd, what="attention dk with rotary backward")
+    assert_rows_close(got[:, nq + nkv:], dv_ref, ROW_ATT_BWD, ROW_FLOOR, width=hd, what="attention dv")
     # one table without the other is an argument error
     assert L.mt_k_flash_bwd_rope(pdq, ld, pdk, ld, pdv, ld, DO.data_ptr(), nq, pq, ld, pk, ld, pv, ld, O.data_ptr(), nq,
                                  LSE.data_ptr(), DELTA.data_ptr(), CS.data_ptr(), None, B, T, Hq, Hkv, hd, scale,

@@ -249,6 +249,36 @@ def test_single_row_attention_matches_torch_sdpa_and_autograd(orc64):
         assert np.allclose(dq, tq.grad[0, 0, t].numpy(), rtol=1e-10, atol=1e-13)
 
 
+def test_single_key_row_matches_full_backward_and_torch_autograd(orc64):
+    """orc_attention_key_row (dK, dV of one key from the queries that see it) against the full backward routine
+    and against torch autograd through scaled_dot_product_attention; first, middle and last keys."""
+    rng = np.random.default_rng(23)
+    T, hd = 41, 16
+    q, k, v, da = (rng.standard_normal((T, hd)) for _ in range(4))
+    _, dk_full, dv_full = orc64.attention_bwd(da, q, k, v, 1, T, 1, 1, hd)
+    tk = torch.tensor(k[None, None], requires_grad=True)
+    tv = torch.tensor(v[None, None], requires_grad=True)
+    ta = F.scaled_dot_product_attention(torch.tensor(q[None, None]), tk, tv, is_causal=True)
+    ta.backward(torch.tensor(da[None, None]))
+    for u in (0, 1, 19, T - 2, T - 1):
+        dk, dv = orc64.attention_key_row(q, da, k, v, u)
+        assert np.allclose(dk, dk_full[u], rtol=1e-10, atol=1e-13) and np.allclose(dv, dv_full[u], rtol=1e-10, atol=1e-13)
+        assert np.allclose(dk, tk.grad[0, 0, u].numpy(), rtol=1e-10, atol=1e-13)
+        assert np.allclose(dv, tv.grad[0, 0, u].numpy(), rtol=1e-10, atol=1e-13)
+    # the last key is seen by the last query alone: dv = p da, with p from the single-row routine's softmax
+    a_last, _ = orc64.attention_row(q[T - 1], da[T - 1], k, v)
+    s = k @ q[T - 1] / np.sqrt(hd)
+    p_last = np.exp(s[-1] - s.max()) / np.exp(s - s.max()).sum()
+    dk, dv = orc64.attention_key_row(q, da, k, v, T - 1)
+    assert np.allclose(dv, p_last * da[T - 1], rtol=1e-12)
+    assert np.allclose(dk, p_last * (da[T - 1] @ v[-1] - da[T - 1] @ a_last) / np.sqrt(hd) * q[T - 1], rtol=1e-10)
+    # rows of q and da before the key are not read
+    q2, da2 = q.copy(), da.copy()
+    q2[:19], da2[:19] = np.nan, np.nan
+    dk2, dv2 = orc64.attention_key_row(q2, da2, k, v, 19)
+    assert np.array_equal(dk2, orc64.attention_key_row(q, da, k, v, 19)[0]) and np.isfinite(dv2).all()
+
+
 def test_gqa_equals_mha_with_replicated_kv_weights(orc64):
     gqa = ModelShape(1, 16, 4, 2, 8, 24, 20)
     mha = ModelShape(1, 16, 4, 4, 8, 24, 20)
