@@ -2,13 +2,16 @@
 """Benchmark of the streamed training step on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config auto|tiny|1.3B|7B|14B|7B-128k]
+                    [--second-config auto|none|NAME] [--overlap-check] [--copy-calibration]
 
 A "step" is one pass of the whole hot path over one synthetic batch: mt_train_step
 (weight streaming, forward, loss, per-block recompute + backward, gradient offload)
 and the host Adam update of every parameter (which also refreshes the streamed bf16 copy).  By default
 this is one call, mt_train_step_adam, which runs each unit's update on host threads as soon as its
 gradients have landed; --separate-adam times mt_train_step followed by mt_adam_step instead.  Inputs are
-resident in host memory, as the method prescribes, when the timed region starts.
+resident in host memory, as the method prescribes, when the timed region starts; every step gets a fresh seeded
+batch.  The default run (no --config) measures the 7B workload and then, under the key "second_workload", 1 + 3
+steps of the 14B workload, the second configuration the metric is quoted on.
 
 Prints ONE JSON line.  `value` is model TFLOP/s by the paper's accounting (6ND + 12LHT^2,
 recompute not counted).  `roofline` is for the dominant kernel class (the MFMA GEMM unless
@@ -84,56 +87,62 @@ def cpu_baseline(name: str) -> dict:
                       f"{dt:.2f} s, loss {loss:.4f}"}
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", default="auto")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--flags", type=int, default=0, help="extra MT_FLAG_* bits (diagnostics)")
-    ap.add_argument("--mlp-chunk", type=int, default=0, help="chunked MLP: tokens per chunk (0 = off)")
-    ap.add_argument("--ckpt-interval", type=int, default=1,
-                    help="checkpoint interval K of Algorithm 1 (the headline number is quoted at K = 1)")
-    ap.add_argument("--no-kernel-timing", action="store_true",
-                    help="diagnostic: no HIP event pairs around the GEMM / attention launches (the roofline object is then empty)")
-    ap.add_argument("--separate-adam", action="store_true",
-                    help="call mt_train_step then mt_adam_step instead of the overlapped mt_train_step_adam")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
-        return 2
+def gemm_source_hash() -> str:
+    import hashlib
+    return hashlib.sha256(open(os.path.join(ROOT, "paper_2604_05091_amd", "csrc", "gemm.hip"), "rb").read()).hexdigest()[:16]
 
+
+def measured_traffic(name: str, dom: int):
+    """HBM-side bytes per launch of the dominant kernel from the rocprofv3 --pmc summary under profiles/ (FETCH_SIZE,
+    WRITE_SIZE, scaled by a copy of known size).  The summary names the hash of the GEMM source it was measured on;
+    when the source has changed since, the figure no longer belongs to the kernel that was timed and null is reported."""
+    tpath = os.path.join(ROOT, "profiles", "gemm_kernels_7B_hbm_traffic.md")
+    if dom != 0 or not os.path.exists(tpath):
+        return None, "no counter summary for this kernel class and workload"
+    import re
+    text = open(tpath).read()
+    m = re.search(r"traffic_bytes_per_launch\[%s\] = ([0-9.eE+]+)" % re.escape(name), text)
+    if not m:
+        return None, "no counter summary for this workload"
+    hm = re.search(r"gemm_source_sha256_16 = ([0-9a-f]+)", text)
+    if not hm or hm.group(1) != gemm_source_hash():
+        return None, "profiles/gemm_kernels_7B_hbm_traffic.md was measured on an older csrc/gemm.hip"
+    return float(m.group(1)), "profiles/gemm_kernels_7B_hbm_traffic.md (same csrc/gemm.hip)"
+
+
+def run_workload(name: str, steps: int, warmup: int, args, flags: int = 0, adam: bool = True, quiet: bool = False) -> dict:
+    """Create a handle for the workload, run warmup + steps on fresh seeded batches, return the measurements."""
+    import gc
     import numpy as np
     import mt_inputs
     import paper_2604_05091_amd as mt
-    # The library owns its device memory and streams; torch is deliberately not imported here, so the
-    # HIP runtime in use is the system one that the library was linked against.
-    mt.lib()  # fail loudly if the extension is not built
-    if mt.device_count() < 1:
-        print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
-        return 3
-
-    name = pick_config(args.config)
     shape, B, T = {**mt_inputs.CONFIGS, **mt_inputs.LONG_CONTEXT}[name]
     n_params = mt_inputs.n_params(shape)
     t_setup = time.time()
     params = mt_inputs.make_params(shape, seed=0)
-    tok, lab = mt_inputs.make_batch(shape.vocab, B, T, seed=1)
+    # a fresh batch for every step (stream_id = step number), generated before the timed region: the timed steps
+    # never see a batch the model has already been updated on
+    batches = [mt_inputs.make_batch(shape.vocab, B, T, seed=1, stream_id=i) for i in range(warmup + steps)]
     cfg = mt.ModelCfg.make(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
                            shape.vocab, B, T, rope_base=shape.rope_base, rms_eps=shape.rms_eps,
-                           flags=(0 if args.no_kernel_timing else mt.FLAG_KERNEL_TIMING) | args.flags, ckpt_interval=args.ckpt_interval,
-                           mlp_chunk=args.mlp_chunk)
+                           flags=(0 if args.no_kernel_timing else mt.FLAG_KERNEL_TIMING) | args.flags | flags,
+                           ckpt_interval=args.ckpt_interval, mlp_chunk=args.mlp_chunk)
     link = mt.link_probe(256 << 20, 4)     # copy-bandwidth probe of this session: the host-link roofline
     h = mt.TrainHandle(cfg, params)
     t_setup = time.time() - t_setup
-    print(f"[bench] {name}: {n_params/1e9:.3f} B params, batch {B} x seq {T}, setup {t_setup:.1f} s, "
-          f"link probe {link}", file=sys.stderr, flush=True)
+    if not quiet:
+        print(f"[bench] {name}: {n_params/1e9:.3f} B params, batch {B} x seq {T}, setup {t_setup:.1f} s, "
+              f"link probe {link}", file=sys.stderr, flush=True)
 
     lr, step_no = 1e-4, 0
     losses = []
+
     def one_step(n):
-        if args.separate_adam:
+        tok, lab = batches[n - 1]
+        if not adam:
+            loss = h.train_step(tok, lab)
+            st = h.stats()
+        elif args.separate_adam:
             loss = h.train_step(tok, lab)
             st = h.stats()
             h.adam_step(lr, step=n)
@@ -143,23 +152,25 @@ def main() -> int:
             st = h.stats()
         return loss, st
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step_no += 1
         losses.append(one_step(step_no)[0])
-        print(f"[bench] warmup step {step_no} loss {losses[-1]:.4f}", file=sys.stderr, flush=True)
+        if not quiet:
+            print(f"[bench] warmup step {step_no} loss {losses[-1]:.4f}", file=sys.stderr, flush=True)
     mt.device_synchronize()
     per_step = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step_no += 1
         loss, st = one_step(step_no)
         losses.append(loss)
         per_step.append(st)
-        print(f"[bench] step {step_no} loss {losses[-1]:.4f} train {st['step_ms']:.0f} ms adam {st['adam_ms']:.0f} ms",
-              file=sys.stderr, flush=True)
+        if not quiet:
+            print(f"[bench] step {step_no} loss {losses[-1]:.4f} train {st['step_ms']:.0f} ms adam {st['adam_ms']:.0f} ms",
+                  file=sys.stderr, flush=True)
     mt.device_synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
+    ms_per_step = elapsed * 1e3 / steps
 
     flops = mt.model_flops(n_params, shape.n_layers, shape.hidden, B, T)
     mean = lambda k: float(np.mean([s[k] for s in per_step]))
@@ -170,23 +181,15 @@ def main() -> int:
     names = ["gemm_nt_w4_kernel<*> + gemm_tn_w4_kernel<*> (bf16 MFMA GEMM)", "flash_fwd_kernel", "flash_bwd_dkdv_kernel + flash_bwd_dq_kernel"]
     dom = int(np.argmax(cls_ms))
     achieved = cls_fl[dom] / (cls_ms[dom] * 1e-3) / 1e12 if cls_ms[dom] > 0 else 0.0
-    # HBM-side bytes per launch of the dominant kernel, measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE,
-    # calibrated against a copy kernel); the summary under profiles/ carries the figure for the GEMM class of
-    # the 7B workload in a line "traffic_bytes_per_launch[7B] = N".
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "gemm_kernels_7B_hbm_traffic.md")
-    if dom == 0 and os.path.exists(tpath):
-        import re
-        m = re.search(r"traffic_bytes_per_launch\[%s\] = ([0-9.eE+]+)" % re.escape(name), open(tpath).read())
-        traffic = float(m.group(1)) if m else None
+    traffic, traffic_note = measured_traffic(name, dom)
     roofline = {"bound": "mfma", "kernel": names[dom], "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
-                "launches_per_step": int(cls_n[dom] / args.steps),
+                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "traffic_source": traffic_note,
+                "launches_per_step": int(cls_n[dom] / steps),
                 "avg_launch_ms": float(cls_ms[dom] / max(cls_n[dom], 1)),
                 "algorithmic_bytes_per_launch": float(cls_by[dom] / max(cls_n[dom], 1)),
                 "algorithmic_flops_per_launch": float(cls_fl[dom] / max(cls_n[dom], 1)),
-                "share_of_compute_busy": float(cls_ms[dom] / args.steps / max(mean("compute_busy_ms"), 1e-9)),
-                "classes": {names[i]: {"ms_per_step": float(cls_ms[i] / args.steps),
+                "share_of_compute_busy": float(cls_ms[dom] / steps / max(mean("compute_busy_ms"), 1e-9)),
+                "classes": {names[i]: {"ms_per_step": float(cls_ms[i] / steps),
                                        "tflops": float(cls_fl[i] / max(cls_ms[i] * 1e-3, 1e-12) / 1e12)}
                             for i in range(3)}}
     h2d_busy, d2h_busy = mean("h2d_busy_ms"), mean("d2h_busy_ms")
@@ -200,19 +203,17 @@ def main() -> int:
         "link_hidden_frac": (mean("h2d_hidden_ms") + mean("d2h_hidden_ms")) / max(h2d_busy + d2h_busy, 1e-9),
     }
     out = {
-        "metric": "sustained model TFLOPS per step (6ND + 12LHT^2; train step + host Adam)",
-        "adam": "separate call" if args.separate_adam else "overlapped per unit (mt_train_step_adam)",
         "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "config": {"workload": f"{name}: {shape.n_layers} layers, hidden {shape.hidden}, {shape.n_q_heads}/"
                                f"{shape.n_kv_heads} heads x {shape.head_dim}, ffn {shape.ffn}, vocab {shape.vocab}, "
                                f"batch {B} x seq {T}", "n_params": n_params, "tokens_per_step": B * T,
                    "host_state": "fp32 master/grad/Adam on host, bf16 streamed weights",
+                   "batches": "a fresh seeded batch every step",
                    "ckpt_interval": args.ckpt_interval, "mlp_chunk": args.mlp_chunk},
         "roofline": roofline,
         "train_step_ms": mean("step_ms"), "adam_step_ms": mean("adam_ms"),
-        "train_only_tflops": (flops / (mean("step_ms") * 1e-3) / 1e12) if args.separate_adam else None,
+        "train_only_tflops": (flops / (mean("step_ms") * 1e-3) / 1e12) if (args.separate_adam or not adam) else None,
         "compute_busy_ms": mean("compute_busy_ms"),
         "link": link_stats,
         "device_arena_gb": per_step[-1]["device_arena_bytes"] / 1e9,
@@ -220,7 +221,109 @@ def main() -> int:
         "loss_first": losses[0], "loss_last": losses[-1],
     }
     h.close()
-    del params
+    del h, params, batches
+    gc.collect()
+    return out
+
+
+def overlap_check(name: str, args) -> dict:
+    """The train step alone (no optimizer) in four schedules: pipelined, every copy and unit followed by a device
+    synchronisation, kernels only, copies only.  1 - (T_pipelined - T_compute_only) / T_copy_only is the share of the
+    link time that the pipeline hides, measured without any event arithmetic."""
+    import paper_2604_05091_amd as mt
+    res = {}
+    for key, fl in (("pipelined", 0), ("serial", mt.FLAG_SERIAL), ("compute_only", mt.FLAG_COMPUTE_ONLY),
+                    ("copy_only", mt.FLAG_COPY_ONLY)):
+        r = run_workload(name, 2, 1, args, flags=fl, adam=False, quiet=True)
+        res[key + "_ms"] = r["train_step_ms"]
+        if key == "pipelined":
+            res["pipelined_event_hidden_frac"] = r["link"]["link_hidden_frac"]
+            res["pipelined_compute_busy_ms"] = r["compute_busy_ms"]
+        print(f"[bench] overlap check, {key}: train step {r['train_step_ms']:.0f} ms", file=sys.stderr, flush=True)
+    res["hidden_frac_by_difference"] = 1.0 - max(0.0, res["pipelined_ms"] - res["compute_only_ms"]) / max(res["copy_only_ms"], 1e-9)
+    res["serial_slowdown"] = res["serial_ms"] / res["pipelined_ms"]
+    return res
+
+
+def copy_calibration() -> int:
+    """A plain device-to-device copy of known size (1 GiB read, 1 GiB written, three times) for scaling the
+    FETCH_SIZE / WRITE_SIZE counters of `rocprofv3 --pmc`; torch only holds the two buffers."""
+    import torch
+    n = 1 << 30
+    src = torch.full((n,), 1, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "dispatches": 3}))
+    return 0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="auto")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--second-config", default="auto",
+                    help="auto: after the default 7B run, also 1 + 3 steps of the 14B workload (the metric's second "
+                         "configuration) when the host has room for its state; none; or a workload name")
+    ap.add_argument("--flags", type=int, default=0, help="extra MT_FLAG_* bits (diagnostics)")
+    ap.add_argument("--mlp-chunk", type=int, default=0, help="chunked MLP: tokens per chunk (0 = off)")
+    ap.add_argument("--ckpt-interval", type=int, default=1,
+                    help="checkpoint interval K of Algorithm 1 (the headline number is quoted at K = 1)")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="diagnostic: no HIP event pairs around the GEMM / attention launches (the roofline object is then empty)")
+    ap.add_argument("--separate-adam", action="store_true",
+                    help="call mt_train_step then mt_adam_step instead of the overlapped mt_train_step_adam")
+    ap.add_argument("--overlap-check", action="store_true",
+                    help="also time the train step pipelined / serial / kernels only / copies only (four more handles)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a 1 GiB device copy, three times (counter calibration under rocprofv3 --pmc)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        return 2
+    if args.copy_calibration:
+        return copy_calibration()
+
+    import mt_inputs
+    import paper_2604_05091_amd as mt
+    # The library owns its device memory and streams; torch is deliberately not imported here, so the
+    # HIP runtime in use is the system one that the library was linked against.
+    mt.lib()  # fail loudly if the extension is not built
+    if mt.device_count() < 1:
+        print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
+        return 3
+
+    name = pick_config(args.config)
+    res = run_workload(name, args.steps, args.warmup, args)
+    out = {
+        "metric": "sustained model TFLOPS per step (6ND + 12LHT^2; train step + host Adam)",
+        "adam": "separate call" if args.separate_adam else "overlapped per unit (mt_train_step_adam)",
+        "value": res.pop("value"), "unit": res.pop("unit"),
+        "n_gpus": 1, "steps": res.pop("steps"), "warmup": res.pop("warmup"), "ms_per_step": res.pop("ms_per_step"),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+    }
+    out.update(res)
+    if args.overlap_check:
+        out["overlap_check"] = overlap_check(name, args)
+    second = args.second_config
+    if second == "auto":
+        second = "none"
+        if args.config == "auto" and name == "7B":
+            need = host_bytes_needed(mt_inputs.n_params(mt_inputs.CONFIGS["14B"][0])) / 1e9
+            if mem_available_gb() > need + 16:
+                second = "14B"
+            else:
+                out["second_workload"] = {"skipped": f"14B needs {need:.0f} GB of host memory, {mem_available_gb():.0f} GB available"}
+    if second != "none":
+        r2 = run_workload(second, 3, 1, args)
+        out["second_workload"] = {k: r2[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "config", "roofline",
+                                                      "adam_step_ms", "compute_busy_ms", "link", "device_arena_gb",
+                                                      "host_pinned_gb", "loss_first", "loss_last")}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(name)
     print(json.dumps(out))

@@ -195,13 +195,21 @@ mt_status mt_adam_step(mt_handle *h, float lr, float beta1, float beta2, float e
 /* mt_train_step and mt_adam_step in one call, with the optimizer overlapped: the Adam update of each
  * unit (same arithmetic as mt_adam_step, same arguments) runs on host threads as soon as that unit's
  * gradient block has landed, while the GPU continues with the remaining blocks (Algorithm 1,
- * "CPU-side optimizer update (asynchronous)"; Section 3.3).  Returns after both the step and every
+ * optimizer phase; Section 3.3).  Returns after both the step and every
  * update have finished.  On MT_OK the gradient tensors hold this step's gradients and the parameters,
- * moments and bf16 copy are updated.  With MT_FLAG_COMPUTE_ONLY / MT_FLAG_COPY_ONLY no update is applied. */
+ * moments and bf16 copy are updated.  With MT_FLAG_COMPUTE_ONLY / MT_FLAG_COPY_ONLY no update is applied.
+ * Failure: argument, shape and token-range errors are found before anything runs and leave every state untouched.
+ * An error after that (MT_ERR_HIP) can leave the update applied to the units whose gradients had already landed
+ * (the head and the later blocks) and not to the others; nothing is rolled back.  The handle then refuses
+ * mt_train_step_adam and mt_adam_step with MT_ERR_STATE, so that a retry cannot apply the same step twice to some
+ * units, until the caller has restored the parameters (its own arrays) and the moments (through mt_get_tensor)
+ * from a copy of its own and called mt_refresh_shadow, which acknowledges the state.  mt_train_step alone stays
+ * usable. */
 mt_status mt_train_step_adam(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
                              float *loss, float lr, float beta1, float beta2, float eps, float wd, int64_t step);
 
-/* Rebuild the bf16 copy from the caller's fp32 parameters (after the caller edited them). */
+/* Rebuild the bf16 copy from the caller's fp32 parameters (after the caller edited them).  Also acknowledges a
+ * partially applied optimizer step (see mt_train_step_adam). */
 mt_status mt_refresh_shadow(mt_handle *h);
 
 #define MT_KIND_GRAD 0

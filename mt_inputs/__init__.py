@@ -90,8 +90,7 @@ def tensor_table(s: ModelShape):
     """Canonical tensor order: (name, rows, cols) for the 9L+3 (12L+3 with qkv_bias; one fewer with tie_embeddings)
     parameter tensors.
 
-    Matrices are row-major [out_features, in_features]; vectors have cols == 1... no:
-    vectors are reported as (rows=n, cols=1).
+    Matrices are row-major [out_features, in_features]; a vector of n elements is reported as (rows=n, cols=1).
     """
     nq, nkv = s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim
     t = [("embed", s.vocab, s.hidden)]

@@ -246,6 +246,9 @@ struct mt_handle {
 
     mt_stats stats;
     bool have_grads = false;
+    // an overlapped step (mt_train_step_adam) failed after its host worker had started: some units may carry this
+    // step's Adam update and others not.  Optimizer calls are refused until mt_refresh_shadow acknowledges it.
+    bool opt_partial = false;
     size_t pinned_bytes = 0, pageable_bytes = 0;
 };
 
@@ -636,8 +639,8 @@ void adam_range(mt_handle *h, int unit, size_t off, size_t count, const AdamHype
     }
 }
 
-// Host optimizer running beside the GPU (Algorithm 1, "CPU-side optimizer update (asynchronous)";
-// Section 3.3: a background CPU thread applies the update as gradient blocks land).  The step pushes
+// Host optimizer running beside the GPU (Algorithm 1, optimizer phase; Section 3.3: a background CPU thread
+// applies the update as gradient blocks land).  The step pushes
 // (copy-done event, unit u, element range) right after enqueueing a device-to-host copy of gradients; the worker
 // waits for that event and updates the tensors of the unit inside the range.  A unit's weights are never streamed again in the same
 // step once its gradients exist, so updating its master copy and bf16 copy in place is safe.
@@ -1222,6 +1225,7 @@ mt_status mt_create(const mt_model_cfg *cfg, float *const *host_param_ptrs, mt_h
 mt_status mt_refresh_shadow(mt_handle *h) {
     if (!h) return fail(MT_ERR_INVALID_ARG, "handle is NULL");
     build_shadow(h);
+    h->opt_partial = false;
     return MT_OK;
 }
 
@@ -1239,6 +1243,8 @@ mt_status mt_train_step_accumulate(mt_handle *h, const int32_t *tokens, const in
 mt_status mt_train_step_adam(mt_handle *h, const int32_t *tokens, const int32_t *labels, int32_t batch, int32_t seq,
                              float *loss, float lr, float beta1, float beta2, float eps, float wd, int64_t step) {
     if (step < 1) return fail(MT_ERR_INVALID_ARG, "step must be >= 1");
+    if (h && h->opt_partial)
+        return fail(MT_ERR_STATE, "an earlier mt_train_step_adam failed part-way: restore the parameters and moments, then call mt_refresh_shadow");
     const AdamHyper hp = {lr, beta1, beta2, eps, wd, step};
     return train_step_core(h, tokens, labels, batch, seq, loss, &hp, false);
 }
@@ -1421,6 +1427,7 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
         if (es != MT_OK) return es;
     }
     if (apply_opt || use_slabs) worker.reset(new HostWorker(h, apply_opt ? opt : nullptr));
+    if (apply_opt) h->opt_partial = true;  // until every unit's update is known to have been applied
     // Gradient block r lives in Gbuf[r & 1] as the image of unit u.  It normally goes to the host as one piece;
     // with tied embeddings the head's image (table gradient | final norm gradient) goes to two units, and the
     // embedding's scatter-add is added to the table gradient that the head left there.
@@ -1537,8 +1544,10 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
         const int s = D.L + 2 + (int)i, l = bslots[i].layer, r = 1 + (D.L - l);
         const int lo = ((l - 1) / K) * K + 1;
         if (s + 1 < nloads) STEP(issue_load(s + 1));
-        STEP(begin_unit(s));
+        // the wait for the gradient buffer comes before the unit's start event, so that a stall on the copy that
+        // still drains that buffer is not booked as compute-busy time (it would count that copy as hidden)
         if (bslots[i].backward) STEP(wait_gbuf(r));
+        STEP(begin_unit(s));
         if (!no_kern) {
             const LayerW w = bind_layer(h->Wbuf[s & 1], h->lo);
             h->select_acts(l - lo);
@@ -1557,8 +1566,8 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     // ---- embedding backward (no weights needed), gradient block L+1
     {
         const int r = D.L + 1;
-        HIPCHK(hipEventRecord(h->comp_start[nloads], sc));
         STEP(wait_gbuf(r));
+        HIPCHK(hipEventRecord(h->comp_start[nloads], sc));
         if (!no_kern) KCHK(embed_scatter(h->Gbuf[r & 1], gcur, h->rowstart_dev, h->order_dev, D.V, D.d, sc));
         STEP(issue_offload(r, 0));
     }
@@ -1574,6 +1583,7 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
         if (apply_opt) h->stats.adam_ms = busy;
         if (worker->failed()) return fail(MT_ERR_HIP, "the host worker thread could not wait for a gradient copy");
     }
+    h->opt_partial = false;
 
     // ---- statistics from event timestamps
     mt_stats &S = h->stats;
@@ -1656,6 +1666,8 @@ mt_status mt_adam_step(mt_handle *h, float lr, float beta1, float beta2, float e
     if (!h) return fail(MT_ERR_INVALID_ARG, "handle is NULL");
     if (step < 1) return fail(MT_ERR_INVALID_ARG, "step must be >= 1");
     if (!h->have_grads) return fail(MT_ERR_STATE, "mt_adam_step before any successful mt_train_step");
+    if (h->opt_partial)
+        return fail(MT_ERR_STATE, "an earlier mt_train_step_adam failed part-way: restore the parameters and moments, then call mt_refresh_shadow");
     const double t0 = now_ms();
     for (int i = 0; i < h->n_tensors; ++i) {
         const TensorRef &t = h->tref[i];
