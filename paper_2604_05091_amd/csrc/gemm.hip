@@ -702,215 +702,15 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4_kernel(GemmArgs g, int tiles
 }
 
 // ---------------------------------------------------------------------------------------------
-// The same 256 x 256 tile and 128 x 128 wave quadrants with the global loads written straight into LDS
-// (global_load_lds_dwordx4: lane i of a wave delivers its 16 bytes to a wave-uniform LDS base + 16 i, from any global
-// address), so a k-step needs no staging registers and no LDS store instructions.  K is walked in half-steps of 32
-// through a ring of four LDS stages (A 256 x 32 | B 256 x 32 bf16, 32 KB each):
-//   half-step h:  MFMAs of k-slice 0 of stage h  ||  LDS reads of slice 1
-//                 wait until the loads of stage h + 1 have landed (two younger groups stay in flight); barrier
-//                 MFMAs of slice 1  ||  LDS reads of slice 0 of stage h + 1  ||  loads of stage h + 4 into the ring
-//                 slot of stage h, which every wave has finished reading when it passes the barrier
-// so a load has three half-steps (about 3000 MFMA clocks) to land, and the one barrier per half-step sits between two
-// MFMA groups whose operands are already in registers.  A wave-load fills 1 KB of contiguous LDS = 16 rows of 64
-// bytes, so rows cannot be padded; the 16-byte chunk c of row r is stored at chunk position c ^ ((r >> 2) & 3) instead
-// (the lane that fills position p simply fetches chunk p ^ ((r >> 2) & 3)), which spreads the fragment reads of 16
-// consecutive rows over all 64 banks.  The four stages are separate arrays: the compiler orders an LDS read after
-// every earlier load-to-LDS that may alias it, and only distinct arrays are known not to.  Each array is as large as a
-// wave's store staging block, which reuses it after the loop.
-constexpr int WD_HALF = 256 * 32 * 2, WD_STAGE = 2 * WD_HALF, WD_ARRAY = 128 * W4_EP_PITCH * 2;
-static_assert(WD_ARRAY >= WD_STAGE, "a ring stage must fit into a staging block");
-
-template <int EPI>
-__global__ __launch_bounds__(W4_NT) void gemm_nt_w4d_kernel(GemmArgs g, int tiles_m, int tiles_n) {
-    __shared__ __attribute__((aligned(1024))) char st0[WD_ARRAY];
-    __shared__ __attribute__((aligned(1024))) char st1[WD_ARRAY];
-    __shared__ __attribute__((aligned(1024))) char st2[WD_ARRAY];
-    __shared__ __attribute__((aligned(1024))) char st3[WD_ARRAY];
-    typedef const __attribute__((address_space(1))) void *gptr;
-    typedef __attribute__((address_space(3))) void *lptr;
-    const int nb = tiles_m * tiles_n;
-    int pid = blockIdx.x;
-    {
-        const int q = nb / kXcd, r = nb % kXcd, x = pid % kXcd;
-        pid = x * q + (x < r ? x : r) + pid / kXcd;
-    }
-    const int group = kGroupM * tiles_n;
-    const int first_m = (pid / group) * kGroupM;
-    const int gsz = min(tiles_m - first_m, kGroupM);
-    const int tm = first_m + (pid % group) % gsz;
-    const int tn = (pid % group) / gsz;
-    const int m0 = tm * W4_BM, n0 = tn * W4_BN;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
-    const int l32 = lane & 31, hl = lane >> 5;
-
-    // loader: wave w fills rows 64 w .. 64 w + 63 of the A half and of the B half of a stage, 16 rows per load;
-    // lane l delivers to chunk position l & 3 of row l >> 2 and fetches the chunk that belongs there
-    constexpr bool glu = EPI == EPI_GLU;
-    const bf16_t *abase = g.A + (int64_t)m0 * g.lda;
-    const bf16_t *bbase = g.B + (glu ? 0 : (int64_t)n0 * g.ldb);
-    uint32_t off[8];
-    {
-        const int chunk = (lane & 3) ^ ((lane >> 4) & 3);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int r = wave * 64 + j * 16 + (lane >> 2);
-            off[j] = (uint32_t)(min(r, g.M - 1 - m0) * (int)g.lda + chunk * 8) * 2u;   // bytes
-            // SwiGLU pairing: tile rows in blocks of 64 = gate c.., up c.., gate c+64.., up c+64.. (c = 128 tn)
-            const int brow = glu ? ((r >> 6) & 1) * g.glu_F + tn * 128 + ((r >> 7) & 1) * 64 + (r & 63) : min(r, g.N - 1 - n0);
-            off[4 + j] = (uint32_t)(brow * (int)g.ldb + chunk * 8) * 2u;
-        }
-    }
-    const uint32_t fill_off = (uint32_t)(wave * 64 * 64);
-    // fragment reads: k-chunk 2 ks + hl of row l32 + 32 i sits at chunk position (2 ks + hl) ^ ((l32 >> 2) & 3)
-    uint32_t rda[2], rdb[2];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        const uint32_t pos = (uint32_t)(((2 * ks + hl) ^ ((l32 >> 2) & 3)) * 16);
-        rda[ks] = (uint32_t)((wm * 128 + l32) * 64) + pos;
-        rdb[ks] = (uint32_t)(WD_HALF + (wn * 128 + l32) * 64) + pos;
-    }
-    bf16x8 fr[2][8];   // [set][A block 0..3 | B block 0..3]
-    f32x16 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    // One load-to-LDS, written out as assembly: the compiler orders every later LDS read after all earlier builtin
-    // load-to-LDS instructions it cannot tell apart (a full vmcnt(0) once per ring turn here), which would undo the
-    // three half-steps of slack; ordering is done by hand instead (WD_WAIT).  M0 carries the wave-uniform LDS address,
-    // lane i lands at M0 + 16 i; the global address is the uniform base plus the lane's 32-bit byte offset.
-#define WD_LOAD1(STG, J, H)                                                                             \
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"                       \
-                 :                                                                                      \
-                 : "v"(off[J]), "s"(((J) < 4 ? abase : bbase) + (H) * 32),                              \
-                   "s"((uint32_t)(uintptr_t)(lptr)(STG) + ((J) < 4 ? 0u : (uint32_t)WD_HALF) + fill_off + ((J) & 3) * 1024u) \
-                 : "memory", "m0")
-#define WD_FILL(STG, H)                                                                                 \
-    {                                                                                                   \
-        WD_LOAD1(STG, 0, H); WD_LOAD1(STG, 1, H); WD_LOAD1(STG, 2, H); WD_LOAD1(STG, 3, H);             \
-        WD_LOAD1(STG, 4, H); WD_LOAD1(STG, 5, H); WD_LOAD1(STG, 6, H); WD_LOAD1(STG, 7, H);             \
-    }
-#define WD_READ(SET, STG, KS)                                                                           \
-    {                                                                                                   \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
-            fr[SET][i] = *reinterpret_cast<const bf16x8 *>((STG) + rda[KS] + i * 2048);                 \
-            fr[SET][4 + i] = *reinterpret_cast<const bf16x8 *>((STG) + rdb[KS] + i * 2048);             \
-        }                                                                                               \
-    }
-#define WD_MMA1(SET, I, J) acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[SET][4 + (J)], fr[SET][I], acc[I][J], 0, 0, 0)
-#define WD_MMA_ROWS(SET, I0, I1)                                                                        \
-    {                                                                                                   \
-        _Pragma("unroll") for (int i = I0; i < I1; ++i)                                                 \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) WD_MMA1(SET, i, j);                           \
-    }
-#define WD_WAIT(N) asm volatile("s_waitcnt vmcnt(" #N ") lgkmcnt(0)\n\ts_barrier" ::: "memory")
-    // load J of the group, then one MFMA, pinned in this order
-#define WD_LOAD_MMA(STG, J, H, SET, I, JJ)                                                              \
-    {                                                                                                   \
-        WD_LOAD1(STG, J, H);                                                                            \
-        WD_MMA1(SET, I, JJ);                                                                            \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-    }
-    // steady state: half-step H out of CUR, the next one in NXT already requested, stage H + 4 requested into CUR
-#define WD_STEP(CUR, NXT, H)                                                                            \
-    {                                                                                                   \
-        WD_READ(1, CUR, 1);                                                                             \
-        WD_MMA_ROWS(0, 0, 4);                                                                           \
-        _Pragma("unroll") for (int c = 0; c < 8; ++c) {                                                 \
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                          \
-        }                                                                                               \
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                              \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        WD_WAIT(16);                                                                                    \
-        WD_READ(0, NXT, 0);                                                                             \
-        WD_MMA_ROWS(1, 0, 2);                                                                           \
-        _Pragma("unroll") for (int c = 0; c < 8; ++c) {                                                 \
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                          \
-        }                                                                                               \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        WD_LOAD_MMA(CUR, 0, (H) + 4, 1, 2, 0); WD_LOAD_MMA(CUR, 1, (H) + 4, 1, 2, 1);                   \
-        WD_LOAD_MMA(CUR, 2, (H) + 4, 1, 2, 2); WD_LOAD_MMA(CUR, 3, (H) + 4, 1, 2, 3);                   \
-        WD_LOAD_MMA(CUR, 4, (H) + 4, 1, 3, 0); WD_LOAD_MMA(CUR, 5, (H) + 4, 1, 3, 1);                   \
-        WD_LOAD_MMA(CUR, 6, (H) + 4, 1, 3, 2); WD_LOAD_MMA(CUR, 7, (H) + 4, 1, 3, 3);                   \
-    }
-    // the last half-steps: nothing (or less) left to request, so fewer load groups are in flight at the barrier
-#define WD_TAIL(CUR, NXT, H)                                                                            \
-    if ((H) < nh) {                                                                                     \
-        WD_READ(1, CUR, 1);                                                                             \
-        WD_MMA_ROWS(0, 0, 4);                                                                           \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        const int younger_ = nh - 2 - (H);                                                              \
-        if (younger_ >= 2) WD_WAIT(16);                                                                 \
-        else if (younger_ == 1) WD_WAIT(8);                                                             \
-        else WD_WAIT(0);                                                                                \
-        if ((H) + 1 < nh) WD_READ(0, NXT, 0);                                                           \
-        if ((H) + 4 < nh) WD_FILL(CUR, (H) + 4);                                                        \
-        WD_MMA_ROWS(1, 0, 4);                                                                           \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-    }
-
-    const int nh = g.K / 32;   // even and >= 2 (K % 64 == 0)
-    WD_FILL(st0, 0);
-    WD_FILL(st1, 1);
-    if (nh > 2) {
-        WD_FILL(st2, 2);
-        WD_FILL(st3, 3);
-        WD_WAIT(24);
-    } else {
-        WD_WAIT(8);
-    }
-    WD_READ(0, st0, 0);
-    int h = 0;
-    for (; h + 8 <= nh; h += 4) {
-        WD_STEP(st0, st1, h);
-        WD_STEP(st1, st2, h + 1);
-        WD_STEP(st2, st3, h + 2);
-        WD_STEP(st3, st0, h + 3);
-    }
-    WD_TAIL(st0, st1, h);
-    WD_TAIL(st1, st2, h + 1);
-    WD_TAIL(st2, st3, h + 2);
-    WD_TAIL(st3, st0, h + 3);
-    WD_TAIL(st0, st1, h + 4);
-    WD_TAIL(st1, st2, h + 5);
-    WD_TAIL(st2, st3, h + 6);
-    WD_TAIL(st3, st0, h + 7);
-#undef WD_LOAD1
-#undef WD_FILL
-#undef WD_READ
-#undef WD_MMA1
-#undef WD_MMA_ROWS
-#undef WD_WAIT
-#undef WD_LOAD_MMA
-#undef WD_STEP
-#undef WD_TAIL
-    // every wave has passed the last half-step's barrier, i.e. has read its last fragments: the arrays are free
-    bf16_t *region = reinterpret_cast<bf16_t *>(wave == 0 ? st0 : wave == 1 ? st1 : wave == 2 ? st2 : st3);
-    w4_epilogue<EPI>(g, acc, m0, n0, tn, wm, wn, l32, hl, region);
-}
-
-template <int EPI>
-hipError_t launch_w4d_epi(const GemmArgs &g, hipStream_t s) {
-    const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = EPI == EPI_GLU ? g.glu_F / 128 : (g.N + W4_BN - 1) / W4_BN;
-    hipLaunchKernelGGL(gemm_nt_w4d_kernel<EPI>, dim3((unsigned)(tiles_m * tiles_n)), dim3(W4_NT), 0, s, g, tiles_m, tiles_n);
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------------------------
 // Load-to-LDS variant with full k-steps of 64: a wave-load fills 8 rows of 128 bytes (whole cache lines per request),
 // two LDS slots of 64 KB (A 256 x 64 | B 256 x 64 bf16), chunk c of row r stored at position c ^ ((r >> 1) & 7).
-//   step t:  k-slices 0..2: MFMAs, the LDS reads one slice ahead
+//   step t:  k-slice 0: MFMAs  ||  LDS reads of slice 1  ||  the B-row loads of step t + 1
+//            k-slices 1, 2: MFMAs, the LDS reads one slice ahead
 //            wait for the loads of step t + 1 (all that are in flight) and for the wave's last reads of the slot; barrier
-//            k-slice 3: MFMAs  ||  LDS reads of slice 0 of step t + 1  ||  the 16 loads of step t + 2 into the slot just freed
-// A load has between three and four k-slices (1500-2000 MFMA clocks) to land.
+//            k-slice 3: MFMAs  ||  LDS reads of slice 0 of step t + 1  ||  the A-row loads of step t + 2 into the slot just freed
+// A load has two to four k-slices (1000-2000 MFMA clocks) to land; loads go out one per two MFMAs (64 clocks): the path
+// into LDS takes a wave's 1 KB every 16 clocks and four waves share it.  No staging registers, no LDS store
+// instructions, half the LDS instruction traffic of the register-staged kernel; measured 5-8 % faster at the 7B shapes.
 constexpr int WE_HALF = 256 * 64 * 2, WE_SLOT = 2 * WE_HALF, WE_ARRAY = 2 * 128 * W4_EP_PITCH * 2;
 static_assert(WE_ARRAY >= WE_SLOT, "a slot must fit into two staging blocks");
 
@@ -973,13 +773,14 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4e_kernel(GemmArgs g, int tile
     // One load-to-LDS, written out as assembly: the compiler orders every later LDS read after all earlier builtin
     // load-to-LDS instructions it cannot tell apart (a full vmcnt(0) in front of reads of the other slot), which undoes
     // the overlap; ordering is done by hand instead (WE_WAIT).  M0 carries the wave-uniform LDS address, lane i lands
-    // at M0 + 16 i; the global address is the uniform base plus the lane's 32-bit byte offset.
+    // at M0 + 16 i; the global address is the uniform base plus the lane's 32-bit byte offset.  (M0 is a reserved
+    // register: the compiler keeps no value in it and sets it itself before any instruction of its own that reads it.)
 #define WE_LOAD1(SLOT, J, T)                                                                            \
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"                       \
                  :                                                                                      \
                  : "v"(off[J]), "s"(((J) < 8 ? abase : bbase) + (T) * 64),                              \
                    "s"((uint32_t)(uintptr_t)(lptr)(SLOT) + ((J) < 8 ? 0u : (uint32_t)WE_HALF) + fill_off + ((J) & 7) * 1024u) \
-                 : "memory", "m0")
+                 : "memory")
 #define WE_FILL(SLOT, T)                                                                                \
     {                                                                                                   \
         WE_LOAD1(SLOT, 0, T); WE_LOAD1(SLOT, 1, T); WE_LOAD1(SLOT, 2, T); WE_LOAD1(SLOT, 3, T);         \
@@ -1014,53 +815,48 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4e_kernel(GemmArgs g, int tile
         __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                              \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
-#if defined(WE_EXP_NOVM)
-#define WE_WAIT(N) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
-#elif defined(WE_EXP_NOBAR)
-#define WE_WAIT(N) asm volatile("s_waitcnt vmcnt(" #N ") lgkmcnt(0)" ::: "memory")
-#else
 #define WE_WAIT(N) asm volatile("s_waitcnt vmcnt(" #N ") lgkmcnt(0)\n\ts_barrier" ::: "memory")
-#endif
-#ifdef WE_EXP_NOLOAD
-#define WE_LOADX(SLOT, J, T)
-#else
-#define WE_LOADX(SLOT, J, T) WE_LOAD1(SLOT, J, T)
-#endif
     // two MFMAs of slice SET (numbers 2 U and 2 U + 1) with one fragment read of (RSET, RSLOT, KS) and, if LD, one load
     // (J of step TL into LSLOT) in front; pinned in this order.  The loads are spaced two MFMAs (64 clocks) apart: the
     // path into LDS takes a wave's 1 KB load every 16 clocks and is shared by four waves.
-#define WE_PAIR(SET, RSET, RSLOT, KS, U, LD, LSLOT, J, TL)                                              \
+#define WE_PAIR(SET, RSET, RSLOT, KS, U, LSLOT, J, TL)                                                  \
     {                                                                                                   \
-        if (LD) WE_LOADX(LSLOT, J, TL);                                                                 \
+        if ((J) >= 0) WE_LOAD1(LSLOT, ((J) < 0 ? 0 : (J)), TL);                                         \
         WE_READ1(RSET, RSLOT, KS, ((U) >> 1) + ((U) & 1) * 4);                                          \
         WE_MMA1(SET, (U) >> 1, ((U) & 1) * 2);                                                          \
         WE_MMA1(SET, (U) >> 1, ((U) & 1) * 2 + 1);                                                      \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
-#define WE_SLICE_LD(SET, RSET, RSLOT, KS, LD, LSLOT, J0, TL)                                            \
+    // a slice whose MFMA pairs 0..7 carry the loads J0..J7 (of step TL into LSLOT; -1 = none)
+#define WE_SLICE_LD(SET, RSET, RSLOT, KS, LSLOT, TL, J0, J1, J2, J3, J4, J5, J6, J7)                    \
     {                                                                                                   \
-        WE_PAIR(SET, RSET, RSLOT, KS, 0, LD, LSLOT, (J0) + 0, TL); WE_PAIR(SET, RSET, RSLOT, KS, 1, LD, LSLOT, (J0) + 1, TL); \
-        WE_PAIR(SET, RSET, RSLOT, KS, 2, LD, LSLOT, (J0) + 2, TL); WE_PAIR(SET, RSET, RSLOT, KS, 3, LD, LSLOT, (J0) + 3, TL); \
-        WE_PAIR(SET, RSET, RSLOT, KS, 4, LD, LSLOT, (J0) + 4, TL); WE_PAIR(SET, RSET, RSLOT, KS, 5, LD, LSLOT, (J0) + 5, TL); \
-        WE_PAIR(SET, RSET, RSLOT, KS, 6, LD, LSLOT, (J0) + 6, TL); WE_PAIR(SET, RSET, RSLOT, KS, 7, LD, LSLOT, (J0) + 7, TL); \
+        WE_PAIR(SET, RSET, RSLOT, KS, 0, LSLOT, J0, TL); WE_PAIR(SET, RSET, RSLOT, KS, 1, LSLOT, J1, TL); \
+        WE_PAIR(SET, RSET, RSLOT, KS, 2, LSLOT, J2, TL); WE_PAIR(SET, RSET, RSLOT, KS, 3, LSLOT, J3, TL); \
+        WE_PAIR(SET, RSET, RSLOT, KS, 4, LSLOT, J4, TL); WE_PAIR(SET, RSET, RSLOT, KS, 5, LSLOT, J5, TL); \
+        WE_PAIR(SET, RSET, RSLOT, KS, 6, LSLOT, J6, TL); WE_PAIR(SET, RSET, RSLOT, KS, 7, LSLOT, J7, TL); \
     }
     // step T out of CUR.  The A rows of step T + 1 were requested into NXT during the last slice of step T - 1; its B
     // rows follow during slice 0 here; the A rows of step T + 2 go into CUR during the last slice.  Past the end of K
     // the last step is requested again (kl clamps it): the same instruction stream for every step, no branches around
     // the MFMAs; the extra data lands in a free slot and is never read.
+    // step T out of CUR.  Loads 0..7 (the A rows) of step T + 2 go into CUR during the last slice, right after the barrier
+    // that frees it; loads 8..15 (the B rows) follow during slice 0 of the next step.  Later than that they miss the
+    // next barrier (measured: 5 + 5 + 6 over three slices is 3 % slower), all 16 in one slice back up behind the load
+    // path (5 % slower).
 #define WE_STEP(CUR, NXT, T)                                                                            \
     {                                                                                                   \
         const int t1_ = min((T) + 1, nk - 1), t2_ = min((T) + 2, nk - 1);                               \
-        WE_SLICE_LD(0, 1, CUR, 1, true, NXT, 8, t1_);                                                   \
+        WE_SLICE_LD(0, 1, CUR, 1, NXT, t1_, 8, 9, 10, 11, 12, 13, 14, 15);                              \
         WE_SLICE(1, 0, CUR, 2);                                                                         \
         WE_SLICE(0, 1, CUR, 3);                                                                         \
         WE_WAIT(0);                                                                                     \
-        WE_SLICE_LD(1, 0, NXT, 0, true, CUR, 0, t2_);                                                   \
+        WE_SLICE_LD(1, 0, NXT, 0, CUR, t2_, 0, 1, 2, 3, 4, 5, 6, 7);                                    \
     }
 
     const int nk = g.K / BK;
     WE_FILL(sl0, 0);
     {
+        // the A rows of step 1, which the schedule would have requested during "step -1"
         const int t1_ = min(1, nk - 1);
         WE_LOAD1(sl1, 0, t1_); WE_LOAD1(sl1, 1, t1_); WE_LOAD1(sl1, 2, t1_); WE_LOAD1(sl1, 3, t1_);
         WE_LOAD1(sl1, 4, t1_); WE_LOAD1(sl1, 5, t1_); WE_LOAD1(sl1, 6, t1_); WE_LOAD1(sl1, 7, t1_);
@@ -1082,7 +878,6 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4e_kernel(GemmArgs g, int tile
 #undef WE_MMA
 #undef WE_SLICE
 #undef WE_WAIT
-#undef WE_LOADX
 #undef WE_PAIR
 #undef WE_SLICE_LD
 #undef WE_STEP
@@ -1137,18 +932,6 @@ hipError_t launch_w4e(const GemmArgs &g, hipStream_t s) {
     if (g.out_fp32) return launch_w4e_epi<EPI_FULL_F32>(g, s);
     if (g.R) return launch_w4e_epi<EPI_FULL_BF16_RES>(g, s);
     return g.bias ? launch_w4e_epi<EPI_FULL_BF16_BIAS>(g, s) : launch_w4e_epi<EPI_FULL_BF16>(g, s);
-}
-
-hipError_t launch_w4d(const GemmArgs &g, hipStream_t s) {
-    if (g.glu_F > 0) return launch_w4d_epi<EPI_GLU>(g, s);
-    if (g.rope_cos) return g.bias ? launch_w4d_epi<EPI_ROPE_BIAS>(g, s) : launch_w4d_epi<EPI_ROPE>(g, s);
-    if (g.glu_bwd_gu) return launch_w4d_epi<EPI_GLU_BWD>(g, s);
-    const bool full = g.N % W4_BN == 0 && !(g.ldc & 7) && !((uintptr_t)g.C & 15) &&
-                      (!g.R || (!(g.ldr & 3) && !((uintptr_t)g.R & 7))) && !((uintptr_t)g.bias & 7);
-    if (!full || (g.bias && g.R)) return launch_w4d_epi<EPI_GENERAL>(g, s);
-    if (g.out_fp32) return launch_w4d_epi<EPI_FULL_F32>(g, s);
-    if (g.R) return launch_w4d_epi<EPI_FULL_BF16_RES>(g, s);
-    return g.bias ? launch_w4d_epi<EPI_FULL_BF16_BIAS>(g, s) : launch_w4d_epi<EPI_FULL_BF16>(g, s);
 }
 
 
@@ -1357,7 +1140,7 @@ int variant_override() {
 static bool takes_w4(const GemmArgs &g) {
     const int64_t big_tiles = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256);
     const int v = variant_override();
-    return g.K % BK == 0 && (v == 6 || v == 9 || v == 11 || ((v == 0 || v == 8 || v == 10) && big_tiles >= 192));
+    return g.K % BK == 0 && (v == 6 || ((v == 0 || v == 5) && big_tiles >= 192));
 }
 
 bool gemm_nt_fuses_rope(const GemmArgs &g) {
@@ -1398,14 +1181,11 @@ hipError_t gemm_nt(const GemmArgs &g, hipStream_t s) {
     switch (variant_override()) {   // diagnostic override (MT_GEMM_VARIANT), 0 = heuristic
         case 2: return launch<256, 256, 2, 4>(g, s);
         case 3: return launch<128, 128, 2, 2>(g, s);
-        case 6: if (g.K % BK == 0) return launch_w4(g, s); break;
-        case 8: if (g.K % BK == 0 && big_tiles >= 192) return launch_w4d(g, s); break;
-        case 9: if (g.K % BK == 0) return launch_w4d(g, s); break;
-        case 10: if (g.K % BK == 0 && big_tiles >= 192) return launch_w4e(g, s); break;
-        case 11: if (g.K % BK == 0) return launch_w4e(g, s); break;
+        case 5: if (g.K % BK == 0 && big_tiles >= 192) return launch_w4(g, s); break;   // register-staged 4-wave kernel
+        case 6: if (g.K % BK == 0) return launch_w4e(g, s); break;                      // 4-wave kernel on any grid
         default: break;
     }
-    if (big_tiles >= 192) return (g.K % BK == 0) ? launch_w4(g, s) : launch<256, 256, 2, 4>(g, s);
+    if (big_tiles >= 192) return (g.K % BK == 0) ? launch_w4e(g, s) : launch<256, 256, 2, 4>(g, s);
     return launch<128, 128, 2, 2>(g, s);
 }
 
