@@ -1090,6 +1090,166 @@ __global__ __launch_bounds__(W4_NT) void gemm_tn_w4_kernel(GemmArgs g, int tiles
     else w4_store(g, acc, m0, n0, wm, wn, l32, hl);
 }
 
+// The same product with the loads written straight into LDS, as in gemm_nt_w4e_kernel: two slots of 64 KB
+// (A [64 k][256 m] | B [64 k][256 n] bf16, rows of 512 bytes, unpadded), a wave-load fills two k rows, loads spaced two
+// MFMAs apart, one barrier per k-step.  The transposing reads touch 8 k rows x 64 bytes per instruction; the 64-byte
+// column group cg of k row r is stored at group position cg ^ (r & 7), which puts the four rows that half a wave reads
+// together on disjoint banks (unswizzled they would all sit on the same 16).
+constexpr int WT_HALF = 64 * 256 * 2, WT_SLOT = 2 * WT_HALF;
+
+template <int EPI>
+__global__ __launch_bounds__(W4_NT) void gemm_tn_w4e_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+    __shared__ __attribute__((aligned(1024))) char sl0[WT_SLOT];
+    __shared__ __attribute__((aligned(1024))) char sl1[WT_SLOT];
+    typedef __attribute__((address_space(3))) void *lptr;
+    typedef __attribute__((address_space(3))) s16x4 *trptr;
+    constexpr int BM = W4_BM, BN = W4_BN;
+    const int n_tiles = tiles_m * tiles_n, nb = n_tiles * g.split_k;
+    int pid = blockIdx.x;
+    {
+        const int q = nb / kXcd, r = nb % kXcd, x = pid % kXcd;
+        pid = x * q + (x < r ? x : r) + pid / kXcd;
+    }
+    // split reduction: units are ordered chunk-major, so the workgroups running together still form tile patches
+    // that walk the same K range; chunk 0 owns C, the others a slice of the workspace
+    const int chunk = pid / n_tiles;
+    pid -= chunk * n_tiles;
+    const int nk_all = g.K / BK;
+    const int kb = (int)((int64_t)chunk * nk_all / g.split_k), ke = (int)((int64_t)(chunk + 1) * nk_all / g.split_k);
+    if (chunk > 0) {
+        g.C = g.split_ws + (int64_t)(chunk - 1) * g.M * g.N;
+        g.ldc = g.N;
+        g.accumulate = 0;
+    }
+    const int group = kGroupM * tiles_n;
+    const int first_m = (pid / group) * kGroupM;
+    const int gsz = min(tiles_m - first_m, kGroupM);
+    const int tm = first_m + (pid % group) % gsz;
+    const int tn = (pid % group) / gsz;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, hl = lane >> 5;
+
+    // loader: wave w fills k rows 16 w .. 16 w + 15 of the A half and of the B half of a slot, two rows per load;
+    // lane l delivers to the 16-byte position l & 31 of row l >> 5 and fetches the chunk that belongs there.
+    // Chunks past the matrix edge re-read the last chunk; they only feed outputs that are never stored.
+    const bf16_t *abase = g.A + (int64_t)kb * BK * g.lda;
+    const bf16_t *bbase = g.B + (int64_t)kb * BK * g.ldb;
+    uint32_t off[16];   // byte offsets from abase (0..7) / bbase (8..15)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int r = wave * 16 + j * 2 + (lane >> 5);
+        const int c16 = ((((lane & 31) >> 2) ^ (r & 7)) << 2) | (lane & 3);
+        off[j] = (uint32_t)(r * (int)g.lda + min(m0 + c16 * 8, g.M - 8)) * 2u;
+        off[8 + j] = (uint32_t)(r * (int)g.ldb + min(n0 + c16 * 8, g.N - 8)) * 2u;
+    }
+    const uint32_t fill_off = (uint32_t)(wave * 16 * 512);
+    // transposing fragment reads (see read_tr_frag): lane (g, i) of a wave supplies k row (g >> 1) * 4 + (i >> 2) of the
+    // slice (and that row + 8), columns (g & 1) * 16 + (i & 3) * 4 .. + 3 of the block's 32; block b of the wave's
+    // quadrant is column group cg = 4 wm + b (A) or 4 wn + b (B), stored at group position cg ^ (row & 7)
+    uint32_t rd[8];
+    {
+        const int gq = lane >> 4, ii = lane & 15;
+        const int row = (gq >> 1) * 4 + (ii >> 2), inner = (gq & 1) * 16 + (ii & 3) * 4;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            rd[b] = (uint32_t)((row * 256 + (((wm * 4 + b) ^ (row & 7)) * 32) + inner) * 2);
+            rd[4 + b] = (uint32_t)(WT_HALF + (row * 256 + (((wn * 4 + b) ^ (row & 7)) * 32) + inner) * 2);
+        }
+    }
+    bf16x8 fr[2][8];
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // one load-to-LDS as assembly, ordered by hand (see gemm_nt_w4e_kernel); a k-step advances both operands by 64 rows
+#define WT_LOAD1(SLOT, J, T)                                                                            \
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"                       \
+                 :                                                                                      \
+                 : "v"(off[J]), "s"((J) < 8 ? abase + (int64_t)(T) * BK * g.lda : bbase + (int64_t)(T) * BK * g.ldb), \
+                   "s"((uint32_t)(uintptr_t)(lptr)(SLOT) + ((J) < 8 ? 0u : (uint32_t)WT_HALF) + fill_off + ((J) & 7) * 1024u) \
+                 : "memory")
+#define WT_READ1(SET, SLOT, KS, IDX)                                                                    \
+    {                                                                                                   \
+        const s16x4 lo_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((trptr)((SLOT) + rd[IDX] + (KS) * 8192));        \
+        const s16x4 hi_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((trptr)((SLOT) + rd[IDX] + (KS) * 8192 + 4096)); \
+        typedef __attribute__((ext_vector_type(8))) short s16x8_;                                       \
+        const s16x8_ v_ = {lo_[0], lo_[1], lo_[2], lo_[3], hi_[0], hi_[1], hi_[2], hi_[3]};             \
+        fr[SET][IDX] = __builtin_bit_cast(bf16x8, v_);                                                  \
+    }
+#define WT_READ(SET, SLOT, KS)                                                                          \
+    {                                                                                                   \
+        WT_READ1(SET, SLOT, KS, 0); WT_READ1(SET, SLOT, KS, 4); WT_READ1(SET, SLOT, KS, 1); WT_READ1(SET, SLOT, KS, 5); \
+        WT_READ1(SET, SLOT, KS, 2); WT_READ1(SET, SLOT, KS, 6); WT_READ1(SET, SLOT, KS, 3); WT_READ1(SET, SLOT, KS, 7); \
+    }
+#define WT_MMA1(SET, I, J) acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[SET][4 + (J)], fr[SET][I], acc[I][J], 0, 0, 0)
+#define WT_WAIT(N) asm volatile("s_waitcnt vmcnt(" #N ") lgkmcnt(0)\n\ts_barrier" ::: "memory")
+    // two MFMAs of slice SET with one fragment (two reads) of (RSET, RSLOT, KS) and, if J >= 0, load J of step TL into
+    // LSLOT in front; pinned in this order
+#define WT_PAIR(SET, RSET, RSLOT, KS, U, LSLOT, J, TL)                                                  \
+    {                                                                                                   \
+        if ((J) >= 0) WT_LOAD1(LSLOT, ((J) < 0 ? 0 : (J)), TL);                                         \
+        WT_READ1(RSET, RSLOT, KS, ((U) >> 1) + ((U) & 1) * 4);                                          \
+        WT_MMA1(SET, (U) >> 1, ((U) & 1) * 2);                                                          \
+        WT_MMA1(SET, (U) >> 1, ((U) & 1) * 2 + 1);                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+    }
+#define WT_SLICE(SET, RSET, RSLOT, KS, LSLOT, TL, J0, J1, J2, J3, J4, J5, J6, J7)                       \
+    {                                                                                                   \
+        WT_PAIR(SET, RSET, RSLOT, KS, 0, LSLOT, J0, TL); WT_PAIR(SET, RSET, RSLOT, KS, 1, LSLOT, J1, TL); \
+        WT_PAIR(SET, RSET, RSLOT, KS, 2, LSLOT, J2, TL); WT_PAIR(SET, RSET, RSLOT, KS, 3, LSLOT, J3, TL); \
+        WT_PAIR(SET, RSET, RSLOT, KS, 4, LSLOT, J4, TL); WT_PAIR(SET, RSET, RSLOT, KS, 5, LSLOT, J5, TL); \
+        WT_PAIR(SET, RSET, RSLOT, KS, 6, LSLOT, J6, TL); WT_PAIR(SET, RSET, RSLOT, KS, 7, LSLOT, J7, TL); \
+    }
+    // step T out of CUR: the schedule of gemm_nt_w4e_kernel
+#define WT_STEP(CUR, NXT, T)                                                                            \
+    {                                                                                                   \
+        const int t1_ = min((T) + 1, nk - 1), t2_ = min((T) + 2, nk - 1);                               \
+        WT_SLICE(0, 1, CUR, 1, NXT, t1_, 8, 9, 10, 11, 12, 13, 14, 15);                                 \
+        WT_SLICE(1, 0, CUR, 2, NXT, t1_, -1, -1, -1, -1, -1, -1, -1, -1);                               \
+        WT_SLICE(0, 1, CUR, 3, NXT, t1_, -1, -1, -1, -1, -1, -1, -1, -1);                               \
+        WT_WAIT(0);                                                                                     \
+        WT_SLICE(1, 0, NXT, 0, CUR, t2_, 0, 1, 2, 3, 4, 5, 6, 7);                                       \
+    }
+
+    const int nk = ke - kb;
+    {
+        WT_LOAD1(sl0, 0, 0); WT_LOAD1(sl0, 1, 0); WT_LOAD1(sl0, 2, 0); WT_LOAD1(sl0, 3, 0);
+        WT_LOAD1(sl0, 4, 0); WT_LOAD1(sl0, 5, 0); WT_LOAD1(sl0, 6, 0); WT_LOAD1(sl0, 7, 0);
+        WT_LOAD1(sl0, 8, 0); WT_LOAD1(sl0, 9, 0); WT_LOAD1(sl0, 10, 0); WT_LOAD1(sl0, 11, 0);
+        WT_LOAD1(sl0, 12, 0); WT_LOAD1(sl0, 13, 0); WT_LOAD1(sl0, 14, 0); WT_LOAD1(sl0, 15, 0);
+        const int t1_ = min(1, nk - 1);
+        WT_LOAD1(sl1, 0, t1_); WT_LOAD1(sl1, 1, t1_); WT_LOAD1(sl1, 2, t1_); WT_LOAD1(sl1, 3, t1_);
+        WT_LOAD1(sl1, 4, t1_); WT_LOAD1(sl1, 5, t1_); WT_LOAD1(sl1, 6, t1_); WT_LOAD1(sl1, 7, t1_);
+    }
+    WT_WAIT(8);
+    WT_READ(0, sl0, 0);
+    int kt = 0;
+    for (; kt + 2 <= nk; kt += 2) {
+        WT_STEP(sl0, sl1, kt);
+        WT_STEP(sl1, sl0, kt + 1);
+    }
+    if (kt < nk) WT_STEP(sl0, sl1, kt);
+    WT_WAIT(0);
+#undef WT_LOAD1
+#undef WT_READ1
+#undef WT_READ
+#undef WT_MMA1
+#undef WT_WAIT
+#undef WT_PAIR
+#undef WT_SLICE
+#undef WT_STEP
+    if constexpr (EPI == EPI_FULL_F32) w4_store_full_f32(g, acc, m0, n0, wm, wn, l32, hl);
+    else w4_store(g, acc, m0, n0, wm, wn, l32, hl);
+}
+
 // C (pitch ldc) += ws[0] + ws[1] + ... (n_ws slices of M x N floats, pitch N), added in that order
 __global__ __launch_bounds__(256) void split_reduce_kernel(float *C, int64_t ldc, const float *ws, int n_ws, int M, int N) {
     const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4, total = (int64_t)M * N;
@@ -1101,19 +1261,25 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(float *C, int64_t ldc
     *reinterpret_cast<f32x4 *>(C + row * ldc + col) = v;
 }
 
+int variant_override();
+
 template <int EPI>
 hipError_t launch_tn_epi(const GemmArgs &g, hipStream_t s) {
-    constexpr size_t lds = (size_t)2 * TN_STAGE_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tn_w4_kernel<EPI>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = (g.N + W4_BN - 1) / W4_BN;
-    hipLaunchKernelGGL(gemm_tn_w4_kernel<EPI>, dim3((unsigned)(tiles_m * tiles_n * g.split_k)), dim3(W4_NT), lds, s, g, tiles_m,
-                       tiles_n);
+    const dim3 grid((unsigned)(tiles_m * tiles_n * g.split_k));
+    if (variant_override() == 5) {   // diagnostic: the register-staged kernel
+        constexpr size_t lds = (size_t)2 * TN_STAGE_BYTES;
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tn_w4_kernel<EPI>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(gemm_tn_w4_kernel<EPI>, grid, dim3(W4_NT), lds, s, g, tiles_m, tiles_n);
+    } else {
+        hipLaunchKernelGGL(gemm_tn_w4e_kernel<EPI>, grid, dim3(W4_NT), 0, s, g, tiles_m, tiles_n);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || g.split_k == 1) return e;
     const int64_t quads = ((int64_t)g.M * g.N + 3) / 4;
