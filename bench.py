@@ -178,7 +178,7 @@ def run_workload(name: str, steps: int, warmup: int, args, flags: int = 0, adam:
     cls_fl = np.sum([s["class_flops"] for s in per_step], axis=0)
     cls_n = np.sum([s["class_launches"] for s in per_step], axis=0)
     cls_by = np.sum([s["class_bytes"] for s in per_step], axis=0)
-    names = ["gemm_nt_w4_kernel<*> + gemm_tn_w4_kernel<*> (bf16 MFMA GEMM)", "flash_fwd_kernel", "flash_bwd_dkdv_kernel + flash_bwd_dq_kernel"]
+    names = ["gemm_nt_w4e_kernel<*> + gemm_tn_w4e_kernel<*> (bf16 MFMA GEMM)", "flash_fwd_kernel", "flash_bwd_dkdv_kernel + flash_bwd_dq_kernel"]
     dom = int(np.argmax(cls_ms))
     achieved = cls_fl[dom] / (cls_ms[dom] * 1e-3) / 1e12 if cls_ms[dom] > 0 else 0.0
     traffic, traffic_note = measured_traffic(name, dom)
