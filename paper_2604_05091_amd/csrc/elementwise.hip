@@ -118,17 +118,25 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(bf16_t *dx, float *par
         for (int k = 0; k < 8; ++k) dg[i][k] = 0.f;
     const uint4 *gr = reinterpret_cast<const uint4 *>(gain);
 
+    // up to 8 chunks per lane (d <= 4096) the row stays in registers between the two passes; wider rows are read again
+    constexpr bool kKeep = NCH <= 8;
     for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < n; row += nwaves) {
         const uint4 *xr = reinterpret_cast<const uint4 *>(x + row * d);
         const uint4 *dyr = reinterpret_cast<const uint4 *>(dy + row * d);
+        uint4 xk[kKeep ? NCH : 1], yk[kKeep ? NCH : 1];
         float ss = 0.f, dot = 0.f;
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
             const int c = lane + 64 * i;
             if (c < nch) {
                 float xf[8], yf[8], gf[8];
-                unpack8(xr[c], xf);
-                unpack8(dyr[c], yf);
+                const uint4 xu = xr[c], yu = dyr[c];
+                if (kKeep) {
+                    xk[i] = xu;
+                    yk[i] = yu;
+                }
+                unpack8(xu, xf);
+                unpack8(yu, yf);
                 unpack8(gr[c], gf);
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
@@ -148,8 +156,8 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(bf16_t *dx, float *par
             const int c = lane + 64 * i;
             if (c < nch) {
                 float xf[8], yf[8], gf[8], of[8];
-                unpack8(xr[c], xf);
-                unpack8(dyr[c], yf);
+                unpack8(kKeep ? xk[i] : xr[c], xf);
+                unpack8(kKeep ? yk[i] : dyr[c], yf);
                 unpack8(gr[c], gf);
                 if (rr) {
                     unpack8(rr[c], of);

@@ -235,6 +235,7 @@ struct mt_handle {
     hipStream_t s_comp = nullptr, s_h2d = nullptr, s_d2h = nullptr;
     std::vector<hipEvent_t> w_ready, w_free, g_ready, g_free, h2d_start, comp_start, d2h_start;
     std::vector<hipEvent_t> gm_ready, gm_free, d2hm_start;  // the same three for a block's early (MLP) gradient piece
+    std::vector<hipEvent_t> sub_copied;  // copy-done events of the sub-ranges a large gradient piece is cut into (grown on demand)
     hipEvent_t ev_ref = nullptr, ev_inputs = nullptr;
     int resident[2] = {-1, -1};
 
@@ -574,7 +575,7 @@ void free_handle(mt_handle *h) {
         v.clear();
     };
     kill_events(h->w_ready); kill_events(h->w_free); kill_events(h->g_ready); kill_events(h->g_free);
-    kill_events(h->gm_ready); kill_events(h->gm_free); kill_events(h->d2hm_start);
+    kill_events(h->gm_ready); kill_events(h->gm_free); kill_events(h->d2hm_start); kill_events(h->sub_copied);
     kill_events(h->h2d_start); kill_events(h->comp_start); kill_events(h->d2h_start);
     for (auto &sp : h->spans) {
         if (sp.a) (void)hipEventDestroy(sp.a);
@@ -628,14 +629,17 @@ struct AdamHyper {
     int64_t step;
 };
 
-// Adam on the tensors of a unit that lie inside [off, off + count) of its block
+// Adam on the part of a unit's tensors that lies inside [off, off + count) of its block (the update is
+// elementwise, so ranges that partition the block may cut through tensors)
 void adam_range(mt_handle *h, int unit, size_t off, size_t count, const AdamHyper &hp) {
     for (int i = 0; i < h->n_tensors; ++i) {
         const TensorRef &t = h->tref[i];
-        if (t.unit != unit || t.off < off || t.off + t.numel > off + count) continue;
+        if (t.unit != unit) continue;
+        const size_t b = std::max(off, (size_t)t.off), e = std::min(off + count, (size_t)t.off + (size_t)t.numel);
+        if (b >= e) continue;
         Unit &u = h->units[unit];
-        host_adam(h->params[i], u.h_grad + t.off, h->adam_m[unit] + t.off, h->adam_v[unit] + t.off,
-                  u.h_shadow ? u.h_shadow + t.off : nullptr, t.numel, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.wd, hp.step);
+        host_adam(h->params[i] + (b - t.off), u.h_grad + b, h->adam_m[unit] + b, h->adam_v[unit] + b,
+                  u.h_shadow ? u.h_shadow + b : nullptr, e - b, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.wd, hp.step);
     }
 }
 
@@ -1434,7 +1438,8 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     // A layer's block leaves in two pieces: the MLP part (two thirds of it) as soon as the MLP backward is done,
     // the rest at the end of the block, so the host update of the step's last block is mostly over when the GPU stops.
     struct GPiece { int unit; size_t dev_off, off, count; bool add, run_adam; };  // offsets in Gbuf and in the unit's block
-    size_t slab_seq = 0;
+    size_t slab_seq = 0, sub_used = 0;
+    constexpr size_t kSubPiece = (size_t)16 << 20;  // elements: 64 MiB of gradients, about a millisecond on the link
     std::vector<char> early_issued(D.L + 2, 0);
     // copies the pieces on S_d2h after `ready`, brackets them with `start` / `copied`, hands them to the host worker
     auto offload_pieces = [&](int r, const std::vector<GPiece> &pieces, hipEvent_t ready, hipEvent_t start,
@@ -1452,13 +1457,33 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
                 dst = h->slabs[slab];
                 slab_of[i] = slab;
             }
-            HIPCHK(hipMemcpyAsync(dst, h->Gbuf[r & 1] + pc.dev_off, pc.count * 4, hipMemcpyDeviceToHost, sd));
             d2h_bytes += pc.count * 4;
+            if (apply_opt && slab_of[i] < 0 && pc.run_adam && pc.count > 2 * kSubPiece) {
+                // a large piece that lands in place: copied and handed over in sub-ranges, so that the host update of
+                // the first one starts while the rest is still on the link (what remains after the GPU's last kernel
+                // is one sub-range's copy plus the piece's update, not the piece's copy plus its update)
+                for (size_t b = 0; b < pc.count; b += kSubPiece) {
+                    const size_t cnt = std::min(kSubPiece, pc.count - b);
+                    HIPCHK(hipMemcpyAsync(dst + b, h->Gbuf[r & 1] + pc.dev_off + b, cnt * 4, hipMemcpyDeviceToHost, sd));
+                    if (sub_used == h->sub_copied.size()) {
+                        hipEvent_t ev = nullptr;
+                        HIPCHK(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+                        h->sub_copied.push_back(ev);
+                    }
+                    hipEvent_t ev = h->sub_copied[sub_used++];
+                    HIPCHK(hipEventRecord(ev, sd));
+                    worker->push(ev, pc.unit, pc.off + b, cnt, -1, false, true);
+                }
+                slab_of[i] = -2;  // handed over
+                continue;
+            }
+            HIPCHK(hipMemcpyAsync(dst, h->Gbuf[r & 1] + pc.dev_off, pc.count * 4, hipMemcpyDeviceToHost, sd));
         }
         HIPCHK(hipEventRecord(copied, sd));
         if (worker)
             for (size_t i = 0; i < pieces.size(); ++i)
-                worker->push(copied, pieces[i].unit, pieces[i].off, pieces[i].count, slab_of[i], pieces[i].add, pieces[i].run_adam);
+                if (slab_of[i] != -2)
+                    worker->push(copied, pieces[i].unit, pieces[i].off, pieces[i].count, slab_of[i], pieces[i].add, pieces[i].run_adam);
         if (serial) HIPCHK(hipDeviceSynchronize());
         return MT_OK;
     };

@@ -5,7 +5,9 @@
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
+#include <atomic>
 #include <condition_variable>
+#include <functional>
 #include <mutex>
 #include <thread>
 #include <vector>
@@ -29,12 +31,27 @@ namespace {
 // Fork-join pool: host_threads() - 1 workers created on first use and kept for the life of the process (spawning
 // 15 threads per call costs ~0.2 ms, a third of the Adam update of a 4 M-element tensor).  One job at a time;
 // a caller that finds the pool busy (the optimizer thread and the weight-packing thread can overlap) falls back
-// to threads of its own.
+// to threads of its own.  A job is a range cut into chunks that the threads take from a shared counter: inside a
+// training step the cores are also running the launching thread, the copy workers and the driver's own threads,
+// and with one fixed share per thread the whole job waited for whichever thread had lost its core.
+struct ChunkedJob {
+    const std::function<void(size_t, size_t)> *fn;
+    size_t n, chunk;
+    std::atomic<size_t> next{0};
+    void drain() {
+        for (;;) {
+            const size_t b = next.fetch_add(1, std::memory_order_relaxed) * chunk;
+            if (b >= n) return;
+            (*fn)(b, b + chunk < n ? b + chunk : n);
+        }
+    }
+};
+
 class ForkJoinPool {
   public:
     ForkJoinPool() {
         const int n = host_threads() - 1;
-        for (int i = 0; i < n; ++i) workers_.emplace_back([this, i] { work(i); });
+        for (int i = 0; i < n; ++i) workers_.emplace_back([this] { work(); });
     }
     ~ForkJoinPool() {
         {
@@ -44,16 +61,16 @@ class ForkJoinPool {
         cv_work_.notify_all();
         for (auto &t : workers_) t.join();
     }
-    bool try_run(const std::function<void(size_t, size_t)> &fn, size_t n, size_t per, size_t nt) {
+    bool try_run(ChunkedJob &job) {
         if (workers_.empty() || !job_mu_.try_lock()) return false;
         {
             std::lock_guard<std::mutex> lk(mu_);
-            fn_ = &fn; n_ = n; per_ = per; nt_ = nt;
+            job_ = &job;
             pending_ = (int)workers_.size();
             ++gen_;
         }
         cv_work_.notify_all();
-        fn(0, per < n ? per : n);
+        job.drain();
         {
             std::unique_lock<std::mutex> lk(mu_);
             cv_done_.wait(lk, [this] { return pending_ == 0; });
@@ -63,28 +80,24 @@ class ForkJoinPool {
     }
 
   private:
-    void work(int id) {
+    void work() {
         uint64_t seen = 0;
         for (;;) {
             std::unique_lock<std::mutex> lk(mu_);
             cv_work_.wait(lk, [&] { return stop_ || gen_ != seen; });
             if (stop_) return;
             seen = gen_;
-            const size_t t = (size_t)id + 1, b = t * per_, e = b + per_ < n_ ? b + per_ : n_;
-            const std::function<void(size_t, size_t)> *fn = fn_;
-            if (t < nt_ && b < n_) {
-                lk.unlock();
-                (*fn)(b, e);
-                lk.lock();
-            }
+            ChunkedJob *job = job_;
+            lk.unlock();
+            job->drain();
+            lk.lock();
             if (--pending_ == 0) cv_done_.notify_one();
         }
     }
     std::vector<std::thread> workers_;
     std::mutex mu_, job_mu_;
     std::condition_variable cv_work_, cv_done_;
-    const std::function<void(size_t, size_t)> *fn_ = nullptr;
-    size_t n_ = 0, per_ = 0, nt_ = 0;
+    ChunkedJob *job_ = nullptr;
     uint64_t gen_ = 0;
     int pending_ = 0;
     bool stop_ = false;
@@ -102,18 +115,21 @@ void parallel_for(size_t n, size_t min_chunk, const std::function<void(size_t, s
         fn(0, n);
         return;
     }
-    // chunk boundaries on multiples of 64 elements so vector loops stay aligned
-    const size_t per = ((n + nt - 1) / nt + 63) & ~(size_t)63;
+    // about 16 chunks per thread, none below min_chunk; boundaries on multiples of 64 elements so vector loops
+    // stay aligned
+    size_t chunk = (n + nt * 16 - 1) / (nt * 16);
+    if (chunk < min_chunk) chunk = min_chunk;
+    chunk = (chunk + 63) & ~(size_t)63;
+    ChunkedJob job;
+    job.fn = &fn;
+    job.n = n;
+    job.chunk = chunk;
     static ForkJoinPool pool;
-    if (pool.try_run(fn, n, per, nt)) return;
+    if (pool.try_run(job)) return;
     std::vector<std::thread> th;
     th.reserve(nt);
-    for (size_t t = 1; t < nt; ++t) {
-        const size_t b = t * per, e = b + per < n ? b + per : n;
-        if (b >= n) break;
-        th.emplace_back([&fn, b, e] { fn(b, e); });
-    }
-    fn(0, per < n ? per : n);
+    for (size_t t = 1; t < nt; ++t) th.emplace_back([&job] { job.drain(); });
+    job.drain();
     for (auto &t : th) t.join();
 }
 
