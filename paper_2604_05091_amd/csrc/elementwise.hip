@@ -265,7 +265,7 @@ __global__ __launch_bounds__(256) void rope_kernel(bf16_t *x, int64_t ld, int64_
 }
 
 // ------------------------------------------------------------------ SwiGLU
-__device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + __expf(-v)); }
+__device__ __forceinline__ float sigmoidf_(float v) { return sigmoid_rcp(v); }
 
 __global__ __launch_bounds__(256) void swiglu_fwd_kernel(bf16_t *sout, const bf16_t *gu, int64_t n, int F) {
     const int cpr = F >> 3;

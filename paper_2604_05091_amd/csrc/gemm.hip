@@ -481,7 +481,7 @@ __device__ __forceinline__ void w4_store_glu(const GemmArgs &g, const f32x16 (&a
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const float g0 = bflo(gw[k]), g1 = bfhi(gw[k]);
-            sw[k] = pack2bf(g0 * (1.0f / (1.0f + __expf(-g0))) * bflo(uw[k]), g1 * (1.0f / (1.0f + __expf(-g1))) * bfhi(uw[k]));
+            sw[k] = pack2bf(g0 * sigmoid_rcp(g0) * bflo(uw[k]), g1 * sigmoid_rcp(g1) * bfhi(uw[k]));
         }
         *reinterpret_cast<uint4 *>(g.glu_out + row * g.ld_glu + col) = uint4{sw[0], sw[1], sw[2], sw[3]};
     }
@@ -493,6 +493,23 @@ __device__ __forceinline__ void w4_store_glu(const GemmArgs &g, const f32x16 (&a
 __device__ __forceinline__ void w4_store_glu_bwd(const GemmArgs &g, const f32x16 (&acc)[4][4], int m0, int n0, int wm,
                                                  int wn, int l32, int hl, bf16_t *region) {
     const int lane = hl * 32 + l32;
+    const int lr = lane >> 4, lc = (lane & 15) * 8;
+    const int col = n0 + wn * 128 + lc;
+    const bool col_ok = col < g.N;
+    // The forward's gate and up values come from memory, a microsecond or two away.  The loads of the first kDepth
+    // row passes are issued before the accumulators are converted (the k-loop's fragment registers are free by now),
+    // each later pass is requested when the pass kDepth before it has been consumed, so the second half never waits
+    // for a load it has only just issued.  Rows past M re-read row M - 1 (never stored).
+    constexpr int kDepth = 12;
+    uint4 gq[kDepth], uq[kDepth];
+    const bf16_t *gu = g.glu_bwd_gu + (col_ok ? col : 0);
+    const int64_t row0 = m0 + wm * 128 + lr;
+#pragma unroll
+    for (int it = 0; it < kDepth; ++it) {
+        const int64_t row = min(row0 + it * 4, (int64_t)g.M - 1);
+        gq[it] = *reinterpret_cast<const uint4 *>(gu + row * g.ld_glu_bwd);
+        uq[it] = *reinterpret_cast<const uint4 *>(gu + row * g.ld_glu_bwd + g.N);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         bf16_t *lp = region + (i * 32 + l32) * W4_EP_PITCH + hl * 4;
@@ -507,18 +524,18 @@ __device__ __forceinline__ void w4_store_glu_bwd(const GemmArgs &g, const f32x16
             }
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    const int lr = lane >> 4, lc = (lane & 15) * 8;
-    const int col = n0 + wn * 128 + lc;
-    if (col >= g.N) return;
     bf16_t *C = reinterpret_cast<bf16_t *>(g.C);
-#pragma unroll 4
+#pragma unroll
     for (int it = 0; it < 32; ++it) {
         const int r = it * 4 + lr;
         const int64_t row = m0 + wm * 128 + r;
-        if (row >= g.M) continue;
         const uint4 dv = *reinterpret_cast<const uint4 *>(region + r * W4_EP_PITCH + lc);
-        const uint4 gv = *reinterpret_cast<const uint4 *>(g.glu_bwd_gu + row * g.ld_glu_bwd + col);
-        const uint4 uv = *reinterpret_cast<const uint4 *>(g.glu_bwd_gu + row * g.ld_glu_bwd + g.N + col);
+        const uint4 gv = gq[it % kDepth], uv = uq[it % kDepth];
+        if (it + kDepth < 32) {
+            const int64_t nrow = min(row0 + (it + kDepth) * 4, (int64_t)g.M - 1);
+            gq[it % kDepth] = *reinterpret_cast<const uint4 *>(gu + nrow * g.ld_glu_bwd);
+            uq[it % kDepth] = *reinterpret_cast<const uint4 *>(gu + nrow * g.ld_glu_bwd + g.N);
+        }
         const uint32_t dw[4] = {dv.x, dv.y, dv.z, dv.w}, gw[4] = {gv.x, gv.y, gv.z, gv.w}, uw[4] = {uv.x, uv.y, uv.z, uv.w};
         uint32_t og[4], ou[4];
 #pragma unroll
@@ -529,8 +546,10 @@ __device__ __forceinline__ void w4_store_glu_bwd(const GemmArgs &g, const f32x16
             og[k] = pack2bf(a0, a1);
             ou[k] = pack2bf(b0, b1);
         }
-        *reinterpret_cast<uint4 *>(C + row * g.ldc + col) = uint4{og[0], og[1], og[2], og[3]};
-        *reinterpret_cast<uint4 *>(C + row * g.ldc + g.N + col) = uint4{ou[0], ou[1], ou[2], ou[3]};
+        if (col_ok && row < g.M) {
+            *reinterpret_cast<uint4 *>(C + row * g.ldc + col) = uint4{og[0], og[1], og[2], og[3]};
+            *reinterpret_cast<uint4 *>(C + row * g.ldc + g.N + col) = uint4{ou[0], ou[1], ou[2], ou[3]};
+        }
     }
 }
 
