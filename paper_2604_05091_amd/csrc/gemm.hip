@@ -499,8 +499,10 @@ __device__ __forceinline__ void w4_store_glu_bwd(const GemmArgs &g, const f32x16
     // The forward's gate and up values come from memory, a microsecond or two away.  The loads of the first kDepth
     // row passes are issued before the accumulators are converted (the k-loop's fragment registers are free by now),
     // each later pass is requested when the pass kDepth before it has been consumed, so the second half never waits
-    // for a load it has only just issued.  Rows past M re-read row M - 1 (never stored).
-    constexpr int kDepth = 12;
+    // for a load it has only just issued.  Rows past M re-read row M - 1 (never stored).  Measured at the 7B shape:
+    // depth 2: 5.48 ms, 4: 5.43, 6: 5.44, 8: 5.46, 12: 5.51, 16: 5.6, 32: 5.7 (loads issued on demand, 4 at a
+    // time: 5.93): beyond a few passes the requests only queue up behind the chip-wide burst of every tile's store.
+    constexpr int kDepth = 4;
     uint4 gq[kDepth], uq[kDepth];
     const bf16_t *gu = g.glu_bwd_gu + (col_ok ? col : 0);
     const int64_t row0 = m0 + wm * 128 + lr;
