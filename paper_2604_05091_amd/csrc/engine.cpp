@@ -1439,7 +1439,13 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     // the rest at the end of the block, so the host update of the step's last block is mostly over when the GPU stops.
     struct GPiece { int unit; size_t dev_off, off, count; bool add, run_adam; };  // offsets in Gbuf and in the unit's block
     size_t slab_seq = 0, sub_used = 0;
-    constexpr size_t kSubPiece = (size_t)16 << 20;  // elements: 64 MiB of gradients, about a millisecond on the link
+    // elements per sub-range: 64 MiB of gradients, about a millisecond on the link (MT_SUBPIECE_ELEMS overrides it, so
+    // that a test on a small model can cut its gradient pieces, and tensors, at odd places)
+    size_t kSubPiece = (size_t)16 << 20;
+    if (const char *e = getenv("MT_SUBPIECE_ELEMS")) {
+        const long long v = atoll(e);
+        if (v > 0) kSubPiece = (size_t)v;
+    }
     std::vector<char> early_issued(D.L + 2, 0);
     // copies the pieces on S_d2h after `ready`, brackets them with `start` / `copied`, hands them to the host worker
     auto offload_pieces = [&](int r, const std::vector<GPiece> &pieces, hipEvent_t ready, hipEvent_t start,

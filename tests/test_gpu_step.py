@@ -125,6 +125,32 @@ def test_overlapped_adam_equals_separate_calls_bitwise():
     assert not np.array_equal(pa[1], params[1])
 
 
+def test_gradient_pieces_in_sub_ranges_give_the_same_update(monkeypatch):
+    """Large gradient pieces leave in sub-ranges with a copy-done event each, and the optimizer updates each
+    sub-range as it lands.  With the sub-range forced down to 1000 elements every piece of this small model is cut,
+    mid-tensor and off every vector boundary; parameters and Adam moments must equal the separate-call route bitwise."""
+    shape = ModelShape(3, 128, 4, 2, 64, 344, 520)
+    params = mt_inputs.make_params(shape, seed=31, std=0.05)
+    tok, lab = mt_inputs.make_batch(shape.vocab, 2, 64, seed=32)
+    pa, pb = [p.copy() for p in params], [p.copy() for p in params]
+    with mt.TrainHandle(make_cfg(shape, 2, 64), pa) as ha, mt.TrainHandle(make_cfg(shape, 2, 64), pb) as hb:
+        for step in (1, 2):
+            monkeypatch.delenv("MT_SUBPIECE_ELEMS", raising=False)
+            la = ha.train_step(tok, lab)
+            ha.adam_step(3e-4, wd=0.01, step=step)
+            monkeypatch.setenv("MT_SUBPIECE_ELEMS", "1000")
+            lb = hb.train_step_adam(tok, lab, 3e-4, wd=0.01, step=step)
+            assert la == lb
+            for i, (a, b) in enumerate(zip(pa, pb)):
+                assert np.array_equal(a, b), (step, i)
+                assert np.array_equal(ha.tensor(i, KIND_ADAM_V), hb.tensor(i, KIND_ADAM_V)), (step, i)
+                assert np.array_equal(ha.tensor(i), hb.tensor(i)), (step, i)
+            ga, gb = ha.grads(), hb.grads()
+            for i, (a, b) in enumerate(zip(ga, gb)):
+                assert np.array_equal(a, b), (step, i)
+    monkeypatch.delenv("MT_SUBPIECE_ELEMS", raising=False)
+
+
 def test_gradient_slab_pool_equals_fully_pinned_gradients():
     """Gradient blocks in pageable memory behind 4 recycled pinned slabs (the paper's slab pool) must give
     the same bytes as the fully pinned layout, with and without the overlapped optimizer."""
