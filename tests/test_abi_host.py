@@ -110,6 +110,37 @@ def test_host_adam_matches_oracle(orc64):
                             1e-8, 0.0, 0) == -1
 
 
+def test_host_adam_from_two_threads_at_once_equals_one_at_a_time():
+    """The host pool runs one job at a time; a caller that finds it busy (the optimizer thread next to the weight
+    packing thread) spawns threads of its own.  Both take chunks from a shared counter.  Two updates issued at the
+    same moment must give, bit for bit, what the same updates give one after the other."""
+    import threading
+    L = mt.lib()
+    rng = np.random.default_rng(5)
+    n = 3_000_017                                # ~46 chunks of 65536 with a ragged tail
+    def fresh(seed):
+        r = np.random.default_rng(seed)
+        return [(r.standard_normal(n) * 0.02).astype(np.float32), (r.standard_normal(n) * 1e-3).astype(np.float32),
+                np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.uint16)]
+    def run(a, reps):
+        for t in range(1, reps + 1):
+            assert L.mt_k_host_adam(a[0].ctypes.data, a[1].ctypes.data, a[2].ctypes.data, a[3].ctypes.data,
+                                    a[4].ctypes.data, n, 1e-3, 0.9, 0.999, 1e-8, 0.01, t) == 0
+    ref = [fresh(1), fresh(2)]
+    for a in ref:
+        run(a, 3)
+    got = [fresh(1), fresh(2)]
+    th = [threading.Thread(target=run, args=(a, 3)) for a in got]
+    for t in th:
+        t.start()
+    for t in th:
+        t.join()
+    for a, b in zip(ref, got):
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    assert not np.array_equal(got[0][0], fresh(1)[0])
+
+
 def test_host_bf16_rounding_is_nearest_even():
     import torch
     L = mt.lib()
