@@ -1444,7 +1444,7 @@ mt_status train_step_core(mt_handle *h, const int32_t *tokens, const int32_t *la
     size_t kSubPiece = (size_t)16 << 20;
     if (const char *e = getenv("MT_SUBPIECE_ELEMS")) {
         const long long v = atoll(e);
-        if (v > 0) kSubPiece = (size_t)v;
+        if (v > 0) kSubPiece = (size_t)std::max<long long>(v, 256);  // one event per sub-range: keep their number sane
     }
     std::vector<char> early_issued(D.L + 2, 0);
     // copies the pieces on S_d2h after `ready`, brackets them with `start` / `copied`, hands them to the host worker
