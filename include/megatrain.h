@@ -27,7 +27,8 @@
  *   - Environment (read once): MT_HOST_THREADS = threads of the host Adam / conversion loops (default: all
  *     cores); MT_PINNED_BUDGET_GB = pinned host memory the library may take before it switches to the
  *     gradient slab pool (default 56); MT_PROGRESS=1 prints one line to stderr whenever the GPU finishes a
- *     unit of a step (for steps that run for minutes); MT_GEMM_VARIANT forces one GEMM kernel (diagnostics);
+ *     unit of a step (for steps that run for minutes); MT_GEMM_VARIANT forces one GEMM kernel, MT_GROUP_M the
+ *     tile-row group of the large-grid GEMM kernels' tile order (diagnostics);
  *     MT_SUBPIECE_ELEMS (read at every step) = elements per sub-range in which mt_train_step_adam copies and
  *     updates a large gradient piece (default 16 Mi; tests use small values to cut through tensors).
  *

@@ -112,6 +112,9 @@ struct GemmArgs {
     // that fill the last round of workgroups badly (see gemm_tn_pick_split).
     int32_t split_k = 1;
     float *split_ws = nullptr;
+    // tile order of the large-grid kernels: tile rows per group (a group is walked column by column); 0 = the
+    // launcher chooses (gemm_pick_group_m)
+    int32_t group_m = 0;
 };
 hipError_t gemm_nt(const GemmArgs &g, hipStream_t s);
 // true when gemm_nt would apply g.rope_* in its epilogue for this problem (large grid, K % 64 == 0, head-aligned

@@ -32,6 +32,12 @@ constexpr int BK = 64;
 constexpr int LDT = BK + 8;
 constexpr int kXcd = 8;
 constexpr int kGroupM = 8;
+// Tile-row group of the large-grid (load-to-LDS) kernels: the 32 workgroups of an XCD then cover 4 x 8 tiles and a
+// group's A rows are left after two patches.  Measured inside the step against 8 (8 x 4 patches): 14B GEMM class
+// +0.9 %, 1.3B +0.9 %, 7B +0.2 %; 3 and 6 lose at 14B.  (Stand-alone timings of one GEMM repeated on the same
+// operands favour small groups far more, up to 7 % at K = 11008, but there the operands are still in the memory-side
+// cache from the previous repetition.)
+constexpr int kGroupMLarge = 4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 template <int BM, int BN, int WGM, int WGN>
@@ -746,9 +752,10 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4e_kernel(GemmArgs g, int tile
         const int q = nb / kXcd, r = nb % kXcd, x = pid % kXcd;
         pid = x * q + (x < r ? x : r) + pid / kXcd;
     }
-    const int group = kGroupM * tiles_n;
-    const int first_m = (pid / group) * kGroupM;
-    const int gsz = min(tiles_m - first_m, kGroupM);
+    const int gm = g.group_m > 0 ? g.group_m : kGroupMLarge;
+    const int group = gm * tiles_n;
+    const int first_m = (pid / group) * gm;
+    const int gsz = min(tiles_m - first_m, gm);
     const int tm = first_m + (pid % group) % gsz;
     const int tn = (pid % group) / gsz;
     const int m0 = tm * W4_BM, n0 = tn * W4_BN;
@@ -907,9 +914,20 @@ __global__ __launch_bounds__(W4_NT) void gemm_nt_w4e_kernel(GemmArgs g, int tile
     w4_epilogue<EPI>(g, acc, m0, n0, tn, wm, wn, l32, hl, region);
 }
 
+// MT_GROUP_M (diagnostics): forces the tile-row group of the large-grid kernels
+int group_m_override() {
+    static const int v = [] {
+        const char *e = getenv("MT_GROUP_M");
+        return e ? atoi(e) : 0;
+    }();
+    return v;
+}
+
 template <int EPI>
-hipError_t launch_w4e_epi(const GemmArgs &g, hipStream_t s) {
+hipError_t launch_w4e_epi(const GemmArgs &g0, hipStream_t s) {
+    GemmArgs g = g0;
     const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = EPI == EPI_GLU ? g.glu_F / 128 : (g.N + W4_BN - 1) / W4_BN;
+    if (group_m_override() > 0) g.group_m = group_m_override();
     hipLaunchKernelGGL(gemm_nt_w4e_kernel<EPI>, dim3((unsigned)(tiles_m * tiles_n)), dim3(W4_NT), 0, s, g, tiles_m, tiles_n);
     return hipGetLastError();
 }
@@ -1142,9 +1160,10 @@ __global__ __launch_bounds__(W4_NT) void gemm_tn_w4e_kernel(GemmArgs g, int tile
         g.ldc = g.N;
         g.accumulate = 0;
     }
-    const int group = kGroupM * tiles_n;
-    const int first_m = (pid / group) * kGroupM;
-    const int gsz = min(tiles_m - first_m, kGroupM);
+    const int gm = g.group_m > 0 ? g.group_m : kGroupMLarge;
+    const int group = gm * tiles_n;
+    const int first_m = (pid / group) * gm;
+    const int gsz = min(tiles_m - first_m, gm);
     const int tm = first_m + (pid % group) % gsz;
     const int tn = (pid % group) / gsz;
     const int m0 = tm * BM, n0 = tn * BN;
@@ -1285,7 +1304,9 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(float *C, int64_t ldc
 int variant_override();
 
 template <int EPI>
-hipError_t launch_tn_epi(const GemmArgs &g, hipStream_t s) {
+hipError_t launch_tn_epi(const GemmArgs &g0, hipStream_t s) {
+    GemmArgs g = g0;
+    if (group_m_override() > 0) g.group_m = group_m_override();
     const int tiles_m = (g.M + W4_BM - 1) / W4_BM, tiles_n = (g.N + W4_BN - 1) / W4_BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n * g.split_k));
     if (variant_override() == 5) {   // diagnostic: the register-staged kernel
