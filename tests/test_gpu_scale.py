@@ -60,7 +60,8 @@ def test_many_tokens_take_the_large_grid_kernels_and_match_oracle(orc64, qkv_bia
 
 
 def _check_dk_dv_of_late_keys(orc64, qkv, dout, DQKV, r0, T, nq, h, hd, back):
-    """dK and dV rows of keys close to the end of a sequence (T - 1 - d for d in back) against the oracle's single
+    """dK and dV rows of sampled keys (T - 1 - d for d in back; the cost on the CPU grows with the number of queries
+    that see the key, so long sequences sample keys near their end) against the oracle's single
     key row (orc_attention_key_row: only the queries from the key to the end see it), on the same bf16 inputs."""
     f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
     K = f64(qkv[r0:r0 + T, nq + h * hd: nq + (h + 1) * hd])
@@ -116,7 +117,7 @@ def test_attention_rows_at_128k_context(orc64):
             else:
                 assert rel_l2(dq, dq_ref) < 3e-2 and cosine(dq, dq_ref) > 0.999, (h, t, rel_l2(dq, dq_ref))
     # dK, dV of keys in the last key block (owned by different waves of the dK/dV workgroup)
-    _check_dk_dv_of_late_keys(orc64, qkv, dout, DQKV, 0, T, nq, 1, hd, (0, 37, 140, 255))
+    _check_dk_dv_of_late_keys(orc64, qkv, dout, DQKV, 0, T, nq, 1, hd, (0, 37, 140, 255, 4096, 8191))
 
 
 # ----------------------------------------------------------------------------- full-size launches, sampled outputs
@@ -196,6 +197,10 @@ def test_attention_at_benchmark_shape_sampled_rows(orc64):
     assert rel_l2(dv, dv_ref) < 3e-2 and rel_l2(dk, dk_ref) < 3e-2, (rel_l2(dv, dv_ref), rel_l2(dk, dk_ref))
     # and keys further back, which several queries see, from the definition
     _check_dk_dv_of_late_keys(orc64, qkv, dout, DQKV, 4 * T, T, nq, 11, hd, (0, 33, 100, 250, 300))
+    # at T = 4096 the oracle can also afford the earliest keys, which every query of the sequence sees: keys 0, 1,
+    # 63 | 64 (a tile seam), 255 | 256 (a key-block seam), 2047
+    _check_dk_dv_of_late_keys(orc64, qkv, dout, DQKV, 9 * T, T, nq, 30, hd,
+                              (T - 1, T - 2, T - 64, T - 65, T - 256, T - 257, T - 2048))
 
 
 # ----------------------------------------------------------------------------- weight gradients at the benchmark shapes
