@@ -260,6 +260,46 @@ def copy_calibration() -> int:
     return 0
 
 
+def gemm_occupancy_probe() -> int:
+    """One round of 256 x 256 GEMM tiles on 32, 128 and 256 of the 256 CUs (and 16 rounds on all of them) for five
+    reduction lengths: the slope over K is the time of one 64-deep k-step of the kernel, the intercept its fixed cost
+    per tile.  The same kernel on an eighth of the chip is not held back by the chip's power limit; torch only holds
+    the buffers.  MT_GEMM_VARIANT=6 sends every grid to the large-grid kernel."""
+    os.environ["MT_GEMM_VARIANT"] = "6"
+    import torch
+    import paper_2604_05091_amd as mt
+    L = mt.lib()
+    out = []
+    for (M, N) in ((2048, 1024), (4096, 2048), (8192, 2048), (65536, 4096)):
+        tiles = (M // 256) * (N // 256)
+        rounds = max(1.0, tiles / 256)
+        pts = []
+        for K in (512, 1024, 2048, 4096, 8192):
+            g = torch.Generator(device="cuda").manual_seed(K + tiles)
+            A = torch.randn((M, K), device="cuda", generator=g).to(torch.bfloat16)
+            B = torch.randn((N, K), device="cuda", generator=g).to(torch.bfloat16)
+            C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+            run = lambda: L.mt_k_gemm_nt(A.data_ptr(), K, B.data_ptr(), K, C.data_ptr(), N, None, 0, M, N, K, 0, 0, None)
+            if run() != 0:
+                raise RuntimeError("mt_k_gemm_nt failed")
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                run()
+            e1.record()
+            torch.cuda.synchronize()
+            pts.append((K, e0.elapsed_time(e1) / 20 / rounds * 1e3))
+            del A, B, C
+        (k1, t1), (k2, t2) = pts[1], pts[-1]
+        step_us = (t2 - t1) / (k2 - k1) * 64
+        out.append({"tiles": tiles, "cus_busy": min(tiles, 256), "us_per_round": {str(k): round(t, 2) for k, t in pts},
+                    "us_per_k_step": round(step_us, 3), "fixed_us_per_tile": round(t1 - step_us * k1 / 64, 2),
+                    "mfma_rate_of_peak_in_loop": round(64 * 32 / 2.4e3 / step_us, 3)})
+    print(json.dumps({"gemm_occupancy_probe": out}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -280,6 +320,8 @@ def main() -> int:
                     help="call mt_train_step then mt_adam_step instead of the overlapped mt_train_step_adam")
     ap.add_argument("--overlap-check", action="store_true",
                     help="also time the train step pipelined / serial / kernels only / copies only (four more handles)")
+    ap.add_argument("--gemm-occupancy-probe", action="store_true",
+                    help="run only the GEMM kernel on 32 / 128 / 256 CUs over five K (k-step time and fixed cost per tile)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device copy, three times (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -288,6 +330,8 @@ def main() -> int:
         return 2
     if args.copy_calibration:
         return copy_calibration()
+    if args.gemm_occupancy_probe:
+        return gemm_occupancy_probe()
 
     import mt_inputs
     import paper_2604_05091_amd as mt
